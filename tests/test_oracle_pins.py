@@ -1,0 +1,358 @@
+"""Pins for the CPU oracle: every check here compares oracle/fb_oracle.py with something
+other than itself — an exactness claim or printed value of the paper, a closed form, an
+invariant, brute force on tiny inputs, or a library routine (torch float64 SDPA).
+
+Chosen so that a plausible slip (dropped scale, bias sign, transposed operand, mask off by
+one, wrong softmax axis, missing Jacobian term) fails at least one of them."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fb_oracle as O
+from paper_2505_12044_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")
+
+
+def _golden():
+    vals = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                k, v = line.split("=", 1)
+                vals[k.strip()] = v.strip()
+    return vals
+
+
+def _rand(rng, *shape):
+    return rng.standard_normal(shape)
+
+
+# ---------------------------------------------------------------- brute force ------
+def _brute_attention(q, k, v, bias, causal, scale):
+    """Pure-Python loops straight from Eq. 1 (tiny sizes only)."""
+    n, c = q.shape
+    m = k.shape[0]
+    out = np.zeros((n, c))
+    lse = np.zeros(n)
+    for i in range(n):
+        s = []
+        for j in range(m):
+            if causal and j > i:
+                s.append(-math.inf)
+                continue
+            dot = sum(q[i, a] * k[j, a] for a in range(c))
+            s.append(dot * scale + (bias[i, j] if bias is not None else 0.0))
+        mx = max(s)
+        e = [math.exp(x - mx) for x in s]
+        z = sum(e)
+        lse[i] = mx + math.log(z)
+        for a in range(c):
+            out[i, a] = sum(e[j] / z * v[j, a] for j in range(m))
+    return out, lse
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_forward_matches_brute_force(causal):
+    rng = np.random.default_rng(1)
+    n, c = 7, 5
+    q, k, v = _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c)
+    b = _rand(rng, n, n)
+    o, lse = O.attention_with_bias(q, k, v, b, causal=causal)
+    o2, lse2 = _brute_attention(q, k, v, b, causal, 1 / math.sqrt(c))
+    np.testing.assert_allclose(o, o2, atol=1e-13)
+    np.testing.assert_allclose(lse, lse2, atol=1e-13)
+
+
+# ---------------------------------------------------------------- paper's exactness claims
+def test_alibi_paper_factors_exact():
+    """Example 3.4 as printed: [1, i] . [-j, 1] = i - j, 1-based, R = 2."""
+    g = _golden()
+    n = 64
+    i = np.arange(1, n + 1, dtype=np.float64)
+    phi_q = np.stack([np.ones(n), i], axis=1)
+    phi_k = np.stack([-i, np.ones(n)], axis=1)
+    assert phi_q.shape[1] == int(g["alibi_rank"])
+    b = O.lowrank_bias(phi_q, phi_k)
+    assert np.array_equal(b, i[:, None] - i[None, :])
+    # the oracle's dense definition with slope -1 (so that -slope (i - j) = i - j), 0-based
+    assert np.array_equal(b, O.alibi_bias(-1.0, n))
+
+
+def test_alibi_workload_factors_equal_dense_definition():
+    """The generator's rank-2 factors reproduce -m_h (i - j) for every (i, j)."""
+    H, n = 16, 512
+    phi_q, phi_k = W.alibi_factors(H, n)
+    slopes = O.alibi_slopes(H)
+    assert slopes[0] == 2.0 ** -0.5 and slopes[-1] == 2.0 ** -8
+    for h in (0, 3, 15):
+        # float32 factors: products of an fp32 slope with integers; compare against the
+        # dense definition evaluated with the same fp32-rounded slope -> exact in float64
+        m32 = float(np.float32(slopes[h]))
+        assert phi_q[0, h, 0, 1] == np.float32(slopes[h])
+        b = O.lowrank_bias(phi_q[0, h], phi_k[0, h])
+        ref = O.alibi_bias(m32, n)
+        # -m*i is rounded to fp32 once when the factor is stored
+        assert np.max(np.abs(b - ref)) <= 2.0 ** -24 * m32 * n * 1.01
+        assert np.max(np.abs(b - O.alibi_bias(slopes[h], n))) < 1e-4
+
+
+def test_distance_factors_exact():
+    """Example 3.5: the nine-column factors give ||x_i - x_j||^2."""
+    g = _golden()
+    rng = np.random.default_rng(2)
+    x = _rand(rng, 33, 3)
+    y = _rand(rng, 21, 3)
+    pq, pk = O.squared_distance_factors(x, y)
+    assert pq.shape[1] == pk.shape[1] == int(g["distance_rank"])
+    np.testing.assert_allclose(O.lowrank_bias(pq, pk), O.squared_distance_bias(x, y), atol=1e-12)
+    # definition check of the dense form itself on one pair
+    assert abs(O.squared_distance_bias(x, y)[3, 4] - sum((x[3, a] - y[4, a]) ** 2 for a in range(3))) < 1e-14
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_concat_identity(causal):
+    """Eq. 3: softmax(q k^T/sqrt(C) + phi_q phi_k^T) v equals plain attention on
+    [q | sqrt(C) phi_q], [k | phi_k] with the 1/sqrt(C) of the ORIGINAL width."""
+    rng = np.random.default_rng(3)
+    n, c, r = 40, 16, 5
+    q, k, v = _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c)
+    pq, pk = _rand(rng, n, r), _rand(rng, n, r)
+    o1, l1 = O.attention_lowrank(q, k, v, pq, pk, causal=causal)
+    qc = np.concatenate([q, math.sqrt(c) * pq], axis=1)
+    kc = np.concatenate([k, pk], axis=1)
+    o2, l2 = O.attention_with_bias(qc, kc, v, None, causal=causal, scale=1 / math.sqrt(c))
+    np.testing.assert_allclose(o1, o2, atol=1e-12)
+    np.testing.assert_allclose(l1, l2, atol=1e-12)
+
+
+# ---------------------------------------------------------------- library cross-check
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("rank", [0, 6])
+def test_matches_torch_sdpa_float64(causal, rank):
+    rng = np.random.default_rng(4)
+    n, c = 96, 32
+    q, k, v = _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c)
+    pq, pk = _rand(rng, n, rank), _rand(rng, n, rank)
+    o, _ = O.attention_lowrank(q, k, v, pq, pk, causal=causal)
+    mask = torch.from_numpy(pq @ pk.T) if rank else torch.zeros(n, n, dtype=torch.float64)
+    if causal:
+        mask = mask.masked_fill(torch.triu(torch.ones(n, n, dtype=torch.bool), 1), -math.inf)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None], torch.from_numpy(k)[None], torch.from_numpy(v)[None],
+        attn_mask=mask[None])
+    np.testing.assert_allclose(o, ref[0].numpy(), atol=1e-10)
+    # R = 0 reduces to plain attention
+    if rank == 0:
+        o0, _ = O.attention_with_bias(q, k, v, None, causal=causal)
+        np.testing.assert_array_equal(o, o0)
+
+
+# ---------------------------------------------------------------- invariants & closed forms
+def test_softmax_rows_sum_to_one_and_convexity():
+    rng = np.random.default_rng(5)
+    n, c = 50, 8
+    q, k, v = _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c)
+    b = 3 * _rand(rng, n, n)
+    for causal in (False, True):
+        o, lse, p = O.attention_with_bias(q, k, v, b, causal=causal, return_probs=True)
+        np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-12)
+        assert np.all(p >= 0)
+        if causal:
+            assert np.all(np.triu(p, 1) == 0)
+            np.testing.assert_allclose(o[0], v[0], atol=1e-14)   # first row sees only key 0
+        assert np.all(o <= v.max(axis=0) + 1e-12) and np.all(o >= v.min(axis=0) - 1e-12)
+
+
+def test_row_shift_invariance():
+    """A rank-1 bias c_i * 1 shifts every score of row i by c_i: o unchanged, lse + c_i."""
+    rng = np.random.default_rng(6)
+    n, c = 31, 8
+    q, k, v = _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c)
+    shift = 5 * _rand(rng, n)
+    o0, l0 = O.attention_with_bias(q, k, v, None)
+    o1, l1 = O.attention_lowrank(q, k, v, shift[:, None], np.ones((n, 1)))
+    np.testing.assert_allclose(o1, o0, atol=1e-12)
+    np.testing.assert_allclose(l1, l0 + shift, atol=1e-12)
+
+
+def test_closed_forms_zero_query():
+    rng = np.random.default_rng(7)
+    n, c = 23, 4
+    v = _rand(rng, n, c)
+    k = _rand(rng, n, c)
+    q = np.zeros((n, c))
+    o, lse = O.attention_with_bias(q, k, v, None)
+    np.testing.assert_allclose(o, np.broadcast_to(v.mean(axis=0), (n, c)), atol=1e-13)
+    np.testing.assert_allclose(lse, math.log(n), atol=1e-13)
+    o, lse = O.attention_with_bias(q, k, v, None, causal=True)
+    pref = np.cumsum(v, axis=0) / np.arange(1, n + 1)[:, None]
+    np.testing.assert_allclose(o, pref, atol=1e-13)
+    np.testing.assert_allclose(lse, np.log(np.arange(1, n + 1)), atol=1e-13)
+    # bias-only weights: phi_q = [1], phi_k = [ln w_j]  ->  o = sum w_j v_j / sum w_j
+    w = rng.uniform(0.1, 3.0, n)
+    o, lse = O.attention_lowrank(q, k, v, np.ones((n, 1)), np.log(w)[:, None])
+    np.testing.assert_allclose(o, np.broadcast_to((w[:, None] * v).sum(0) / w.sum(), (n, c)), atol=1e-12)
+    np.testing.assert_allclose(lse, math.log(w.sum()), atol=1e-12)
+
+
+def test_scale_and_bias_are_not_mixed():
+    """The bias is added AFTER scaling q k^T (Eq. 1): doubling q's scale by hand equals
+    passing a doubled scale, and the bias is unaffected by it."""
+    rng = np.random.default_rng(8)
+    n, c = 12, 4
+    q, k, v = _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c)
+    b = _rand(rng, n, n)
+    o1, _ = O.attention_with_bias(2 * q, k, v, b)
+    o2, _ = O.attention_with_bias(q, k, v, b, scale=2 / math.sqrt(c))
+    np.testing.assert_allclose(o1, o2, atol=1e-13)
+    o3, _ = O.attention_with_bias(q, k, v, 2 * b, scale=2 / math.sqrt(c))
+    assert np.max(np.abs(o3 - o2)) > 1e-3
+
+
+def test_row_offset_slices_match_full_causal():
+    rng = np.random.default_rng(9)
+    n, c, r = 37, 8, 3
+    q, k, v = _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c)
+    pq, pk = _rand(rng, n, r), _rand(rng, n, r)
+    o, lse = O.attention_lowrank(q, k, v, pq, pk, causal=True)
+    o_s, lse_s = O.attention_lowrank(q[11:29], k, v, pq[11:29], pk, causal=True, row_offset=11)
+    np.testing.assert_array_equal(o[11:29], o_s)
+    np.testing.assert_array_equal(lse[11:29], lse_s)
+
+
+# ---------------------------------------------------------------- SVD / energy (Remark 3.8)
+def test_truncated_svd_eckart_young_and_energy():
+    rng = np.random.default_rng(10)
+    b = W.swin_table_bias(rng, 1, 12)[0]           # smooth 144 x 144 relative-position bias
+    s = np.linalg.svd(b, compute_uv=False)
+    prev = np.inf
+    for r in (1, 2, 4, 8, 16, 32, 23 * 23):
+        pq, pk = O.truncated_svd_factors(b, r)
+        err = np.sum((b - O.lowrank_bias(pq, pk)) ** 2)
+        np.testing.assert_allclose(err, np.sum(s[r:] ** 2), rtol=1e-8, atol=1e-10 * np.sum(s ** 2))
+        assert err <= prev * (1 + 1e-12)
+        prev = err
+        np.testing.assert_allclose(O.svd_energy(b, r), 1 - err / np.sum(b * b), atol=1e-10)
+    assert prev < 1e-18 * np.sum(b * b)
+    # the qualitative claim of Remark 3.8: a smooth relative-position bias is low-rank
+    assert O.svd_energy(b, 32) > 0.99
+    # the workload generator's own factorisation agrees with the oracle's
+    fq, fk = W._svd_factors(b, 8)
+    oq, ok = O.truncated_svd_factors(b, 8)
+    np.testing.assert_allclose(fq @ fk.T, oq @ ok.T, atol=1e-10)
+
+
+def test_paper_io_example():
+    g = _golden()
+    val = O.hbm_io_ratio_example(C=64, R=64, sram_bytes=100 * 1024, bytes_per_elem=2)
+    assert abs(val - float(g["hbm_io_ratio_formula"])) < 1e-12
+    assert round(val - 0.5) == int(g["hbm_io_ratio_text"])     # "about 6x" in the text
+
+
+# ---------------------------------------------------------------- gradients
+def _loss(q, k, v, pq, pk, dout, causal):
+    o, _ = O.attention_lowrank(q, k, v, pq, pk, causal=causal)
+    return float(np.sum(o * dout))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_gradients_finite_differences(causal):
+    rng = np.random.default_rng(11)
+    n, c, r = 9, 6, 3
+    arrs = [_rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, r), _rand(rng, n, r)]
+    dout = _rand(rng, n, c)
+    grads = O.attention_lowrank_grads(*arrs, dout, causal=causal)
+    eps = 1e-6
+    for a, g in zip(arrs, grads):
+        num = np.zeros_like(a)
+        it = np.nditer(a, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = a[idx]
+            a[idx] = old + eps
+            lp = _loss(*arrs, dout, causal)
+            a[idx] = old - eps
+            lm = _loss(*arrs, dout, causal)
+            a[idx] = old
+            num[idx] = (lp - lm) / (2 * eps)
+        np.testing.assert_allclose(g, num, rtol=1e-6, atol=1e-8)
+
+
+def test_gradient_identities_and_row_blocking():
+    rng = np.random.default_rng(12)
+    n, c, r = 45, 8, 4
+    q, k, v = _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c)
+    pq, pk = _rand(rng, n, r), _rand(rng, n, r)
+    pk[:, 0] = 1.0                       # a constant key-side column, like ALiBi's "1"
+    dout = _rand(rng, n, c)
+    dq, dk, dv, dpq, dpk = O.attention_lowrank_grads(q, k, v, pq, pk, dout)
+    # rows of ds sum to zero  =>  gradient of the phi_q column paired with the constant is 0
+    np.testing.assert_allclose(dpq[:, 0], 0.0, atol=1e-12)
+    # consistency with the dense-bias gradient: dphi_q = dB phi_k, dphi_k = dB^T phi_q
+    b = O.lowrank_bias(pq, pk)
+    dq2, dk2, dv2, db = O.attention_with_bias_grads(q, k, v, b, dout)
+    np.testing.assert_allclose(db.sum(axis=1), 0.0, atol=1e-12)
+    np.testing.assert_allclose(dpq, db @ pk, atol=1e-12)
+    np.testing.assert_allclose(dpk, db.T @ pq, atol=1e-12)
+    np.testing.assert_allclose(dq, dq2, atol=1e-12)
+    np.testing.assert_allclose(dk, dk2, atol=1e-12)
+    np.testing.assert_allclose(dv, dv2, atol=1e-12)
+    # D_i = sum_j p_ij dp_ij equals sum_c dout_ic o_ic (the shortcut a fused kernel uses)
+    o, _, p = O.attention_with_bias(q, k, v, b, return_probs=True)
+    np.testing.assert_allclose(np.sum(p * (dout @ v.T), axis=1), np.sum(dout * o, axis=1), atol=1e-12)
+    # processing query rows in blocks changes nothing beyond summation order
+    blocked = O.attention_lowrank_grads(q, k, v, pq, pk, dout, row_block=7)
+    for a, bb in zip((dq, dk, dv, dpq, dpk), blocked):
+        np.testing.assert_allclose(a, bb, atol=1e-12)
+    # torch autograd (float64) on the same function as a library cross-check
+    tq, tk, tv, tpq, tpk = (torch.tensor(x, requires_grad=True) for x in (q, k, v, pq, pk))
+    s = tq @ tk.T / math.sqrt(c) + tpq @ tpk.T
+    (torch.softmax(s, dim=1) @ tv * torch.from_numpy(dout)).sum().backward()
+    for a, t in zip((dq, dk, dv, dpq, dpk), (tq, tk, tv, tpq, tpk)):
+        np.testing.assert_allclose(a, t.grad.numpy(), atol=1e-11)
+
+
+# ---------------------------------------------------------------- batched wrappers / workloads
+def test_batched_wrappers_broadcast():
+    w = W.make_workload("vision_relpos", dense=True, B=2, H=2, N=64, R=8)
+    assert w.phi_broadcast and w.phi_q.shape == (1, 2, 64, 8)
+    out, lse = O.batched_attention_lowrank(w.q, w.k, w.v, w.phi_q, w.phi_k)
+    o01, l01 = O.attention_lowrank(w.q[1, 0], w.k[1, 0], w.v[1, 0], w.phi_q[0, 0], w.phi_k[0, 0])
+    np.testing.assert_array_equal(out[1, 0], o01)
+    outd, _ = O.batched_attention_dense(w.q, w.k, w.v, w.bias)
+    # rank-8 truncation of a smooth table: close to, but not equal to, the dense result
+    assert 0 < np.max(np.abs(out - outd)) < 0.5
+
+
+def test_workload_recipes():
+    # values are representable in the storage type, shapes follow the configuration
+    w = W.make_workload("pairformer", B=3, N=128, dense=True)
+    assert w.q.shape == (3, 4, 128, 32) and w.phi_q.shape == (1, 4, 128, 16)
+    np.testing.assert_array_equal(W.round_bf16(w.q), w.q)
+    np.testing.assert_array_equal(W.round_bf16(w.phi_k), w.phi_k)
+    # rank-1 + noise construction: rank 16 keeps most of the energy
+    assert O.svd_energy(w.bias_exact[0, 0], 16) > 0.5
+    w5 = W.make_workload("long_train", B=1, H=2, N=512)
+    bias = O.lowrank_bias(w5.phi_q[0, 0], w5.phi_k[0, 0])
+    assert 0.85 < bias.std() < 1.15 and w5.dout is not None
+    w1 = W.make_workload("tiny_fp32", dense=True)
+    assert w1.q.dtype == np.float32 and w1.bias.shape == (1, 2, 256, 256)
+    assert 0.4 < w1.phi_q.std() < 0.6
+    # same seed -> same arrays
+    w1b = W.make_workload("tiny_fp32")
+    np.testing.assert_array_equal(w1.q, w1b.q)
+
+
+def test_bf16_rounding_helper():
+    x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -9, -3.14159, 4095.0, 1e-30], dtype=np.float32)
+    r = W.round_bf16(x)
+    t = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(r, t)
+    rng = np.random.default_rng(0)
+    y = rng.standard_normal(10000).astype(np.float32) * 100
+    np.testing.assert_array_equal(W.round_bf16(y), torch.from_numpy(y).to(torch.bfloat16).float().numpy())
