@@ -1,0 +1,121 @@
+/*
+ * flashbias.h — C-ABI of the MI355X (gfx950) low-rank-bias attention library.
+ *
+ * The operation is exact softmax attention with an additive bias (FlashBias,
+ * arxiv 2505.12044, Sec. 2.1, Eq. 1):
+ *
+ *     o = softmax(q k^T * scale + b [+ causal mask]) v,     scale = 1/sqrt(C) by default,
+ *
+ * where the bias is supplied as low-rank factors b = phi_q phi_k^T (Sec. 3.2, Eq. 2) and
+ * is folded into the score contraction as [q*scale | phi_q] [k | phi_k]^T (Eq. 3), so the
+ * N x N bias never exists in device memory.  fb_dense_bias_attn_fwd is the baseline the
+ * paper compares against (fused attention that streams a materialised bias tile by tile,
+ * Example 3.9).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller: contiguous, row-major,
+ *     16-byte aligned.  The library never allocates, frees or keeps them.
+ *   - Layouts: q, k, v, out, dout, dq, dk, dv: [B, H, N, C];  lse: [B, H, N] float;
+ *     phi_q, phi_k: [Bp, H, N, R] with Bp = 1 when phi_batch_broadcast != 0, else Bp = B;
+ *     bias: [Bb, H, N, N] with Bb = 1 when bias_batch_broadcast != 0, else Bb = B.
+ *   - Queries and keys have the same length N (self-attention); with causal != 0 key j is
+ *     visible to query i iff j <= i (0-based).  N may be any positive value (ragged tails
+ *     are handled inside the kernels).
+ *   - dtype is the storage type of q, k, v, out (and dout, dq, dk, dv, bias); phi_dtype is
+ *     the storage type of phi_q, phi_k (and dphi_q, dphi_k).  With dtype = FB_BF16 all
+ *     contractions run as bf16 MFMA with fp32 accumulation; fp32 factors are then split
+ *     into three bf16 limbs inside the kernel (six product columns per rank), which keeps
+ *     ~24 bits of each factor (needed e.g. for ALiBi positions up to N).  With
+ *     dtype = FB_F32 everything is fp32 FMA and phi_dtype must be FB_F32.
+ *   - Supported: C in {32, 64, 128}; 0 <= R, with the padded factor width (R for bf16
+ *     factors, 6R for fp32 factors in a bf16 run, rounded up to 16) at most 64 (forward) or
+ *     32 (backward); fp32 forward: R <= 64.  R = 0 (phi pointers may be NULL) is plain attention.
+ *   - scale <= 0 selects 1/sqrt(C).
+ *   - stream is a hipStream_t passed as void*; NULL is the default stream.  Calls only
+ *     enqueue work: they never synchronise and never block on the device.
+ *   - Return value: FB_OK or an fb_status for errors detectable on the host (bad argument,
+ *     unsupported shape, misalignment, workspace too small, launch failure).  Outputs are
+ *     fully overwritten on success and untouched on error.  No global state; thread-safe.
+ */
+#ifndef FLASHBIAS_H_
+#define FLASHBIAS_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FB_OK = 0,
+    FB_ERR_NULL = 1,         /* a required pointer is NULL                          */
+    FB_ERR_SHAPE = 2,        /* B, H, N <= 0, R < 0, or sizes overflow the indexing */
+    FB_ERR_UNSUPPORTED = 3,  /* C / R / dtype combination has no kernel             */
+    FB_ERR_ALIGN = 4,        /* a pointer is not 16-byte aligned                    */
+    FB_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than the size query says  */
+    FB_ERR_LAUNCH = 6        /* the HIP runtime rejected a launch                   */
+} fb_status;
+
+typedef enum { FB_F32 = 0, FB_BF16 = 1 } fb_dtype;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int fb_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char* fb_status_string(int status);
+
+/*
+ * Process-wide tuning knob for experiments (benchmarks sweep it; results never depend on
+ * it).  name = "fwd_qb": 32-row query blocks per wave in the bf16 forward kernels, 1 or 2
+ * (0 restores the automatic choice).  Returns FB_OK, FB_ERR_NULL, FB_ERR_SHAPE (value out
+ * of range) or FB_ERR_UNSUPPORTED (unknown name).  Not synchronised with concurrent calls.
+ */
+int fb_tune_set(const char* name, int value);
+
+/*
+ * Forward with factorised bias (Eq. 3; tiled evaluation as in the proof of Corollary 3.7).
+ *   out [B,H,N,C] dtype, lse [B,H,N] float: natural-log log-sum-exp of each score row
+ *   (scaled, biased, masked), which the backward consumes.
+ */
+int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
+                        const void* phi_q, const void* phi_k,
+                        void* out, float* lse,
+                        int B, int H, int N, int C, int R, int causal,
+                        fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                        float scale, void* stream);
+
+/*
+ * Forward with a dense bias streamed from device memory (the baseline of Example 3.9:
+ * HBM traffic Theta(N M C^2 / S + N M)).  bias has the storage type `dtype`.
+ */
+int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const void* bias,
+                           void* out, float* lse,
+                           int B, int H, int N, int C, int causal,
+                           fb_dtype dtype, int bias_batch_broadcast,
+                           float scale, void* stream);
+
+/*
+ * Backward of fb_lowrank_attn_fwd for an upstream gradient dout (loss L = sum(dout * out)):
+ * dq, dk, dv [B,H,N,C] dtype; dphi_q, dphi_k [B,H,N,R] phi_dtype, always per batch element
+ * (a caller whose factors are shared over the batch sums them over B).  The factor
+ * gradients are the trailing R columns of the same contractions that give dq and dk
+ * (Sec. 3.2 "Speed up training"; Sec. 4.1 "Implementation choices").
+ * `out` and `lse` are the forward's results.  Needs dtype = FB_BF16.
+ * workspace: device scratch of at least fb_lowrank_attn_bwd_workspace_bytes(...) bytes,
+ * 16-byte aligned, owned by the caller; its contents on entry are ignored.
+ * Results are deterministic (no floating-point atomics).
+ */
+size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype);
+
+int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
+                        const void* phi_q, const void* phi_k,
+                        const void* out, const float* lse, const void* dout,
+                        void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                        int B, int H, int N, int C, int R, int causal,
+                        fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                        float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHBIAS_H_ */

@@ -1,0 +1,167 @@
+// C-ABI entry points: argument validation and kernel selection.  No device work happens
+// here beyond enqueueing kernels on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstring>
+
+#include "../../include/flashbias.h"
+#include "fb_launch.h"
+#include "fb_params.h"
+
+namespace {
+
+std::atomic<int> g_fwd_qb{0};   // 0 = choose automatically
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int padded_rank(int R, fb_dtype dtype, fb_dtype phi_dtype) {
+    if (R == 0) return 0;
+    const int cols = (dtype == FB_BF16 && phi_dtype == FB_F32) ? 6 * R : R;
+    return (cols + 15) / 16 * 16;
+}
+
+int check_common(int B, int H, int N, int C, int R) {
+    if (B <= 0 || H <= 0 || N <= 0 || R < 0) return FB_ERR_SHAPE;
+    if ((long long)B * H * N * (long long)(C > R ? C : R) >= (1LL << 31)) return FB_ERR_SHAPE;
+    if (C != 32 && C != 64 && C != 128) return FB_ERR_UNSUPPORTED;
+    return FB_OK;
+}
+
+int pick_qb(int B, int H, int N, int C, int rp) {
+    const int forced = g_fwd_qb.load(std::memory_order_relaxed);
+    if (forced == 1 || forced == 2) return forced;
+    // Two query blocks per wave halve the LDS traffic per MFMA but need 256-row tiles: use
+    // them when that still leaves every CU several workgroups.
+    const long long tiles256 = (long long)B * H * ((N + 255) / 256);
+    if (N % 256 != 0 && N < 1024) return 1;
+    return tiles256 >= 512 ? 2 : 1;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fb_version(void) { return 100; }
+
+const char* fb_status_string(int status) {
+    switch (status) {
+        case FB_OK: return "ok";
+        case FB_ERR_NULL: return "required pointer is NULL";
+        case FB_ERR_SHAPE: return "invalid shape";
+        case FB_ERR_UNSUPPORTED: return "unsupported C / R / dtype combination";
+        case FB_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case FB_ERR_WORKSPACE: return "workspace missing or too small";
+        case FB_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int fb_tune_set(const char* name, int value) {
+    if (name == nullptr) return FB_ERR_NULL;
+    if (std::strcmp(name, "fwd_qb") == 0) {
+        if (value < 0 || value > 2) return FB_ERR_SHAPE;
+        g_fwd_qb.store(value, std::memory_order_relaxed);
+        return FB_OK;
+    }
+    return FB_ERR_UNSUPPORTED;
+}
+
+int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
+                        const void* phi_q, const void* phi_k, void* out, float* lse,
+                        int B, int H, int N, int C, int R, int causal,
+                        fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                        float scale, void* stream) {
+    if (!q || !k || !v || !out || !lse) return FB_ERR_NULL;
+    if (int st = check_common(B, H, N, C, R)) return st;
+    if (R > 0 && (!phi_q || !phi_k)) return FB_ERR_NULL;
+    if (dtype != FB_F32 && dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (dtype == FB_F32 && R > 0 && phi_dtype != FB_F32) return FB_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
+        return FB_ERR_ALIGN;
+    if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k))) return FB_ERR_ALIGN;
+    const int rp = padded_rank(R, dtype, phi_dtype);
+    if (rp > 64) return FB_ERR_UNSUPPORTED;
+
+    FwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.phi_q = phi_q; p.phi_k = phi_k; p.bias = nullptr;
+    p.out = out; p.lse = lse;
+    p.B = B; p.H = H; p.N = N; p.R = R; p.causal = causal != 0;
+    p.phi_f32 = phi_dtype == FB_F32;
+    p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
+    p.bias_bstride = 0;
+    p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    int rc;
+    if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, false, (hipStream_t)stream);
+    else rc = fb_launch_fwd_bf16(p, C, rp, false, pick_qb(B, H, N, C, rp), (hipStream_t)stream);
+    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
+int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const void* bias,
+                           void* out, float* lse, int B, int H, int N, int C, int causal,
+                           fb_dtype dtype, int bias_batch_broadcast, float scale, void* stream) {
+    if (!q || !k || !v || !bias || !out || !lse) return FB_ERR_NULL;
+    if (int st = check_common(B, H, N, C, 0)) return st;
+    if (dtype != FB_F32 && dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(bias) || !aligned16(out) ||
+        !aligned16(lse))
+        return FB_ERR_ALIGN;
+
+    FwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.phi_q = nullptr; p.phi_k = nullptr; p.bias = bias;
+    p.out = out; p.lse = lse;
+    p.B = B; p.H = H; p.N = N; p.R = 0; p.causal = causal != 0;
+    p.phi_f32 = 0;
+    p.phi_bstride = 0;
+    p.bias_bstride = bias_batch_broadcast ? 0 : (long long)H * N * N;
+    p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    int rc;
+    if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, true, (hipStream_t)stream);
+    else rc = fb_launch_fwd_bf16(p, C, 0, true, pick_qb(B, H, N, C, 0), (hipStream_t)stream);
+    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
+size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype) {
+    (void)C; (void)R; (void)dtype;
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    return (size_t)B * H * N * sizeof(float);   // delta = rowsum(dout * out)
+}
+
+int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
+                        const void* phi_q, const void* phi_k,
+                        const void* out, const float* lse, const void* dout,
+                        void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                        int B, int H, int N, int C, int R, int causal,
+                        fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                        float scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return FB_ERR_NULL;
+    if (int st = check_common(B, H, N, C, R)) return st;
+    if (R > 0 && (!phi_q || !phi_k || !dphi_q || !dphi_k)) return FB_ERR_NULL;
+    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
+    for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
+    if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k) || !aligned16(dphi_q) || !aligned16(dphi_k)))
+        return FB_ERR_ALIGN;
+    const int rp = padded_rank(R, dtype, phi_dtype);
+    if (rp > 32) return FB_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, R, dtype))
+        return FB_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FB_ERR_ALIGN;
+
+    BwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.phi_q = phi_q; p.phi_k = phi_k;
+    p.out = out; p.lse = lse; p.dout = dout;
+    p.dq = dq; p.dk = dk; p.dv = dv; p.dphi_q = dphi_q; p.dphi_k = dphi_k;
+    p.delta = (float*)workspace;
+    p.B = B; p.H = H; p.N = N; p.R = R; p.causal = causal != 0;
+    p.phi_f32 = phi_dtype == FB_F32;
+    p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
+    p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    const int rc = fb_launch_bwd_bf16(p, C, rp, (hipStream_t)stream);
+    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
+}  // extern "C"

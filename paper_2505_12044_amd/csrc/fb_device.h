@@ -1,0 +1,150 @@
+// Device-side building blocks for the gfx950 (CDNA4, wave64) bf16 kernels: vector types,
+// MFMA wrappers with their operand layouts, cross-half lane exchange, the LDS transpose
+// read, and the bf16 limb split used for fp32 bias factors.
+#ifndef FB_DEVICE_H_
+#define FB_DEVICE_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+#define FB_DEV __device__ __forceinline__
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- MFMA 32x32x16 bf16, fp32 accumulate -------------------------------------------------
+// D[32x32] += A[32x16] * B[16x32].  Lane l (0..63), hf = l / 32:
+//   A operand: row l % 32, the eight k-slots 8*hf .. 8*hf+7
+//   B operand: column l % 32, the same eight k-slots
+//   D / C: column l % 32, rows 8*(r/4) + 4*hf + (r%4) for accumulator register r = 0..15.
+// Only "same k-slot on both operands" matters for correctness, so a kernel may assign any
+// eight of its contraction indices to a lane's slots as long as A and B agree.
+FB_DEV f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+FB_DEV bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+FB_DEV uint4 as_uint4(bf16x8 v) { return __builtin_bit_cast(uint4, v); }
+
+// Exchange across the two 32-lane halves (v_permlane32_swap): given registers (a, b) the
+// instruction returns ({a.lo, b.lo}, {a.hi, b.hi}) where .lo/.hi are the values held by lanes
+// 0..31 / 32..63.  Feeding the same value twice yields both halves' values in every lane.
+// The second operand goes through an empty asm so the compiler cannot see that the two
+// inputs are equal (it would otherwise treat the two results as equal as well).
+struct HalfPair { float lo, hi; };
+FB_DEV HalfPair half_pair(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    unsigned w = u;
+    asm volatile("" : "+v"(w));
+    auto r = __builtin_amdgcn_permlane32_swap(u, w, false, false);
+    HalfPair p;
+    p.lo = __builtin_bit_cast(float, (unsigned)r[0]);
+    p.hi = __builtin_bit_cast(float, (unsigned)r[1]);
+    return p;
+}
+FB_DEV float half_max(float x) { const HalfPair p = half_pair(x); return fmaxf(p.lo, p.hi); }
+FB_DEV float half_sum(float x) { const HalfPair p = half_pair(x); return p.lo + p.hi; }
+
+// ---- LDS transpose read (ds_read_b64_tr_b16) ----------------------------------------------
+// Within each group of 16 lanes, lane i passes the address of four consecutive 16-bit
+// elements; read as a 4 x 16 matrix M[e][j] whose row e, columns 4*(i%4)..4*(i%4)+3 come
+// from lane i = 4*e + j/4, lane j receives column j: {M[0][j], M[1][j], M[2][j], M[3][j]}.
+// With a row-major [row][col] tile and lane i pointing at &tile[r0 + i/4][c0 + 4*(i%4)],
+// lane j therefore receives tile[r0..r0+3][c0 + j]: four rows of one column.
+FB_DEV s16x4 lds_read_tr16(const bf16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(p));
+}
+FB_DEV bf16x8 join_tr(s16x4 lo, s16x4 hi) {
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+FB_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- bf16 limbs of an fp32 value ----------------------------------------------------------
+// x = x1 + x2 + x3 (+ ~2^-24 |x|) with each limb a bf16 value.  For a product a*b the six
+// column pairs (a1,b1) (a1,b2) (a2,b1) (a1,b3) (a2,b2) (a3,b1) recover it to ~2^-24.
+FB_DEV bf16_t bf16_limb(float x, int n) {
+    bf16_t l = (bf16_t)x;
+    if (n == 0) return l;
+    x -= (float)l;
+    l = (bf16_t)x;
+    if (n == 1) return l;
+    x -= (float)l;
+    return (bf16_t)x;
+}
+// limb index used in product column `slot` (0..5) on the query side and on the key side
+FB_DEV int q_limb_of_slot(int slot) { return (0x210100 >> (4 * slot)) & 0xF; }  // 0,0,1,0,1,2
+FB_DEV int k_limb_of_slot(int slot) { return (0x012010 >> (4 * slot)) & 0xF; }  // 0,1,0,2,1,0
+
+// Eight consecutive columns [8*c8, 8*c8+8) of a factor row widened to the padded layout.
+//   bf16 factors: column j holds phi[j] for j < R, else 0.
+//   fp32 factors: column j holds limb (slot j % 6) of phi[j / 6] for j / 6 < R, else 0.
+template <bool QSIDE>
+FB_DEV bf16x8 phi_chunk_gather(const void* row, int c8, int R, bool f32) {
+    bf16x8 out;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        const int j = c8 * 8 + e;
+        bf16_t val = (bf16_t)0.f;
+        if (!f32) {
+            if (j < R) val = ((const bf16_t*)row)[j];
+        } else {
+            const int r = j / 6, slot = j - 6 * r;
+            if (r < R) {
+                const float x = ((const float*)row)[r];
+                val = bf16_limb(x, QSIDE ? q_limb_of_slot(slot) : k_limb_of_slot(slot));
+            }
+        }
+        out[e] = val;
+    }
+    return out;
+}
+
+// Two-step variant for the key side, so the global loads of the next tile can stay in
+// flight during compute: phi_chunk_raw issues the loads, phi_chunk_finish converts.
+FB_DEV uint4 phi_chunk_raw(const void* row, int c8, int R, bool f32, bool row_valid) {
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (!row_valid) return raw;
+    if (!f32) {
+        if ((R & 7) == 0) {
+            if (c8 * 8 < R) raw = *(const uint4*)((const bf16_t*)row + c8 * 8);
+        } else {
+            raw = as_uint4(phi_chunk_gather<false>(row, c8, R, false));
+        }
+    } else {
+        const int r0 = (c8 * 8) / 6;
+        const float* f = (const float*)row;
+        if (r0 < R) raw.x = __builtin_bit_cast(unsigned, f[r0]);
+        if (r0 + 1 < R) raw.y = __builtin_bit_cast(unsigned, f[r0 + 1]);
+        if (r0 + 2 < R) raw.z = __builtin_bit_cast(unsigned, f[r0 + 2]);
+    }
+    return raw;
+}
+FB_DEV bf16x8 phi_chunk_finish(uint4 raw, int c8, bool f32) {
+    if (!f32) return as_bf16x8(raw);
+    bf16x8 out;
+    const int r0 = (c8 * 8) / 6;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        const int j = c8 * 8 + e;
+        const int r = j / 6, slot = j - 6 * r;
+        const int d = r - r0;
+        const unsigned u = d == 0 ? raw.x : (d == 1 ? raw.y : raw.z);
+        out[e] = bf16_limb(__builtin_bit_cast(float, u), k_limb_of_slot(slot));
+    }
+    return out;
+}
+
+#endif

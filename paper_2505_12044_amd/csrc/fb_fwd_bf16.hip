@@ -1,0 +1,410 @@
+// bf16 MFMA forward for attention with an additive bias, gfx950.
+//
+//   low-rank mode: scores = [q*scale | phi_q | 0] . [k | phi_k | 0]   (FlashBias Eq. 3)
+//   dense mode   : scores = (q*scale) . k + bias tile streamed from HBM  (the baseline of
+//                  Example 3.9)
+//
+// Work split.  One workgroup = 4 waves = BQ = 128*QB query rows of one (b, h); it walks the
+// key/value sequence in tiles of BK keys staged in LDS (register-prefetched one tile ahead,
+// two LDS buffers, one barrier per tile).  Each wave owns 32*QB query rows.
+//
+// Orientation.  Every contraction is computed transposed so that a query is a LANE and the
+// keys (or output channels) of a 32-wide block sit in that lane's accumulator registers:
+//   S^T[key][query]   = sum_c  Kt[key][c]   * Qreg[query][c]      (A = K tile from LDS)
+//   O^T[chan][query] += sum_key V^T[chan][key] * P^T[key][query]   (A = V via LDS transpose read)
+// The query operand is loop-invariant and stays in registers; the softmax row maximum and
+// sum are per-lane reductions over registers plus ONE exchange with the lane 32 away; the
+// exponentiated scores are already in the B-operand layout of the second MFMA, so P never
+// touches LDS; and rescaling O by a per-query factor is a per-lane multiply.
+#include <hip/hip_runtime.h>
+
+#include "fb_device.h"
+#include "fb_launch.h"
+#include "fb_params.h"
+
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+// The running reference maximum of a row is only raised when the true maximum exceeds it by
+// more than this (log2 units); until then probabilities are at most 2^tau, which fp32 sums
+// and bf16 P (same exponent range) hold without loss.  The final o = O / l is unaffected.
+constexpr float kRescaleTau = 8.0f;
+
+template <int C, int RP, int QB, int BK, bool DENSE>
+struct Cfg {
+    static constexpr int KS = (C + RP) / 16;          // MFMA k-steps of the score contraction
+    static constexpr int KP = C + RP + 8;             // K-tile row pitch (elements): 16 B pad
+    static constexpr int VP = (C == 32) ? 32 : C + 32;  // V-tile row pitch: odd multiple of 64 B
+    static constexpr int BQ = kWaves * QB * 32;
+    static constexpr int KB = BK / 32;                // 32-key blocks per tile
+    static constexpr int KCH = BK * C / 8;            // 16-byte chunks of the K (or V) part of a tile
+    static constexpr int KIT = KCH / kThreads;        // per-thread chunks
+    static constexpr int PCH = BK * RP / 8;           // chunks of the factor part
+    static constexpr int PIT = (PCH + kThreads - 1) / kThreads;
+    static constexpr int BP = BK + 4;                 // dense: bias tile row pitch (elements)
+    static constexpr int BROWS = QB * 32;             // dense: bias rows per wave
+    static constexpr int BIT = BROWS * (BK / 8) / 64;  // dense: per-lane 16-byte chunks
+    static constexpr size_t kLds =
+        (size_t)2 * BK * (KP + VP) * 2 + (DENSE ? (size_t)kWaves * BROWS * BP * 2 : 0);
+    static_assert(KCH % kThreads == 0, "tile must split evenly over the workgroup");
+    static_assert(BK % 32 == 0 && (C % 32) == 0 && (RP % 16) == 0, "shape granularity");
+};
+
+template <int C, int RP, int QB, int BK, bool CAUSAL, bool DENSE>
+__global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
+    using K = Cfg<C, RP, QB, BK, DENSE>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* const kt = (bf16_t*)smem;                 // [2][BK][KP]
+    bf16_t* const vt = kt + 2 * BK * K::KP;           // [2][BK][VP]
+    bf16_t* const bt = vt + 2 * BK * K::VP;           // dense: [waves][BROWS][BP]
+
+    // ---- which tile: contiguous runs of tiles per XCD (workgroup w lands on XCD w % 8), so the
+    // workgroups sharing one head's K/V also share one L2; causal tiles go heaviest first.
+    const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+    if (L >= p.total_tiles) return;
+    const int bh = L / p.n_qtiles;
+    int qt = L - bh * p.n_qtiles;
+    if (CAUSAL) qt = p.n_qtiles - 1 - qt;
+    const int b = bh / p.H, h = bh - b * p.H;
+    const int N = p.N, R = p.R;
+    const bool phi_f32 = p.phi_f32 != 0;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hf = lane >> 5;
+    const int q0 = qt * K::BQ;
+    const int qw0 = q0 + wave * (QB * 32);
+
+    const size_t base = (size_t)bh * N * C;
+    const bf16_t* qg = (const bf16_t*)p.q + base;
+    const bf16_t* kg = (const bf16_t*)p.k + base;
+    const bf16_t* vg = (const bf16_t*)p.v + base;
+    const size_t phi_esz = phi_f32 ? 4 : 2;
+    const unsigned char* pqg = nullptr;
+    const unsigned char* pkg = nullptr;
+    if (RP > 0) {
+        const size_t pbase = ((size_t)b * p.phi_bstride + (size_t)h * N * R) * phi_esz;
+        pqg = (const unsigned char*)p.phi_q + pbase;
+        pkg = (const unsigned char*)p.phi_k + pbase;
+    }
+    const bf16_t* bg = nullptr;
+    if (DENSE) bg = (const bf16_t*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * N;
+
+    // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout) ----
+    bf16x8 qreg[QB][K::KS];
+#pragma unroll
+    for (int qb = 0; qb < QB; qb++) {
+        const int qi = qw0 + qb * 32 + l32;
+        const bool ok = qi < N;
+#pragma unroll
+        for (int ks = 0; ks < K::KS; ks++) {
+            bf16x8 val;
+            if (ks < C / 16) {
+                uint4 raw = make_uint4(0, 0, 0, 0);
+                if (ok) raw = *(const uint4*)(qg + (size_t)qi * C + ks * 16 + 8 * hf);
+                const bf16x8 x = as_bf16x8(raw);
+#pragma unroll
+                for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
+            } else {
+                const int c8 = (ks - C / 16) * 2 + hf;
+                if (ok) {
+                    val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
+                }
+            }
+            qreg[qb][ks] = val;
+        }
+    }
+
+    f32x16 oacc[QB][C / 32];
+    float mref[QB], lsum[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; qb++) {
+        mref[qb] = -INFINITY;
+        lsum[qb] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < C / 32; cb++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) oacc[qb][cb][r] = 0.f;
+    }
+
+    const int kend = CAUSAL ? min(N, q0 + K::BQ) : N;
+    const int nT = (kend + BK - 1) / BK;
+
+    // ---- tile staging: global -> registers -> LDS ----
+    uint4 kraw[K::KIT], vraw[K::KIT];
+    uint4 praw[K::PIT > 0 ? K::PIT : 1];
+    uint4 braw[DENSE ? K::BIT : 1];
+    const bool bias_fast = DENSE && ((N & 7) == 0);
+
+    auto load_tile = [&](int t) {
+        const int k0 = t * BK;
+#pragma unroll
+        for (int it = 0; it < K::KIT; it++) {
+            const int e = tid + it * kThreads;
+            const int row = e / (C / 8), c8 = e % (C / 8);
+            const int j = k0 + row;
+            uint4 a = make_uint4(0, 0, 0, 0), bb = a;
+            if (j < N) {
+                a = *(const uint4*)(kg + (size_t)j * C + c8 * 8);
+                bb = *(const uint4*)(vg + (size_t)j * C + c8 * 8);
+            }
+            kraw[it] = a;
+            vraw[it] = bb;
+        }
+        if (RP > 0) {
+#pragma unroll
+            for (int it = 0; it < K::PIT; it++) {
+                const int e = tid + it * kThreads;
+                if (e < K::PCH) {
+                    const int row = e / (RP / 8), c8 = e % (RP / 8);
+                    const int j = k0 + row;
+                    praw[it] = phi_chunk_raw(pkg + (size_t)j * R * phi_esz, c8, R, phi_f32, j < N);
+                }
+            }
+        }
+        if (DENSE) {
+#pragma unroll
+            for (int it = 0; it < K::BIT; it++) {
+                const int e = lane + it * 64;
+                const int row = e / (BK / 8), c8 = e % (BK / 8);
+                const int qi = qw0 + row;
+                const int j = k0 + c8 * 8;
+                uint4 a = make_uint4(0, 0, 0, 0);
+                // chunks wholly above the diagonal are never read when causal
+                if (qi < N && j < N && !(CAUSAL && j > qi)) {
+                    const bf16_t* src = bg + (size_t)qi * N + j;
+                    if (bias_fast) {
+                        a = *(const uint4*)src;
+                    } else {
+                        bf16x8 tmp;
+#pragma unroll
+                        for (int x = 0; x < 8; x++) tmp[x] = (j + x < N) ? src[x] : (bf16_t)0.f;
+                        a = as_uint4(tmp);
+                    }
+                }
+                braw[it] = a;
+            }
+        }
+    };
+
+    auto store_tile = [&](int buf) {
+        bf16_t* kdst = kt + buf * BK * K::KP;
+        bf16_t* vdst = vt + buf * BK * K::VP;
+#pragma unroll
+        for (int it = 0; it < K::KIT; it++) {
+            const int e = tid + it * kThreads;
+            const int row = e / (C / 8), c8 = e % (C / 8);
+            *(uint4*)(kdst + row * K::KP + c8 * 8) = kraw[it];
+            *(uint4*)(vdst + row * K::VP + c8 * 8) = vraw[it];
+        }
+        if (RP > 0) {
+#pragma unroll
+            for (int it = 0; it < K::PIT; it++) {
+                const int e = tid + it * kThreads;
+                if (e < K::PCH) {
+                    const int row = e / (RP / 8), c8 = e % (RP / 8);
+                    *(uint4*)(kdst + row * K::KP + C + c8 * 8) =
+                        as_uint4(phi_chunk_finish(praw[it], c8, phi_f32));
+                }
+            }
+        }
+        if (DENSE) {
+            bf16_t* bdst = bt + wave * K::BROWS * K::BP;
+#pragma unroll
+            for (int it = 0; it < K::BIT; it++) {
+                const int e = lane + it * 64;
+                const int row = e / (BK / 8), c8 = e % (BK / 8);
+                uint2* d = (uint2*)(bdst + row * K::BP + c8 * 8);   // 8-byte aligned rows
+                d[0] = make_uint2(braw[it].x, braw[it].y);
+                d[1] = make_uint2(braw[it].z, braw[it].w);
+            }
+        }
+    };
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int t = 0; t < nT; t++) {
+        const bool more = t + 1 < nT;
+        if (more) load_tile(t + 1);
+
+        const bf16_t* ksrc = kt + (t & 1) * BK * K::KP;
+        const bf16_t* vsrc = vt + (t & 1) * BK * K::VP;
+        const int k0 = t * BK;
+
+#pragma unroll
+        for (int kb = 0; kb < K::KB; kb++) {
+            const int kb0 = k0 + kb * 32;
+            // this wave's rows all precede the block: nothing visible (wave-uniform)
+            if (CAUSAL && kb0 > qw0 + QB * 32 - 1) continue;
+
+            // ---- S^T = Kt . Qreg ----
+            f32x16 s[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) s[qb][r] = 0.f;
+            const bf16_t* krow = ksrc + (kb * 32 + l32) * K::KP + 8 * hf;
+#pragma unroll
+            for (int ks = 0; ks < K::KS; ks++) {
+                const bf16x8 a = as_bf16x8(*(const uint4*)(krow + ks * 16));
+#pragma unroll
+                for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(a, qreg[qb][ks], s[qb]);
+            }
+
+            bf16x8 pb[QB][2];
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++) {
+                const int qmin = qw0 + qb * 32;
+                const int qi = qmin + l32;
+                if (DENSE) {
+                    const bf16_t* brow = bt + (wave * K::BROWS + qb * 32 + l32) * K::BP + kb * 32 + 4 * hf;
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        const uint2 u = *(const uint2*)(brow + 8 * g);
+                        const bf16x4 bv = __builtin_bit_cast(bf16x4, u);
+#pragma unroll
+                        for (int x = 0; x < 4; x++) s[qb][4 * g + x] += (float)bv[x];
+                    }
+                }
+                const bool diag = CAUSAL && (kb0 + 31 > qmin);
+                if (diag || kb0 + 32 > N) {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const int key = kb0 + 8 * (r / 4) + 4 * hf + (r % 4);
+                        if (key >= N || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
+                    }
+                }
+                // ---- online softmax: the row lives in this lane and the one 32 away ----
+                float mx = s[qb][0];
+#pragma unroll
+                for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[qb][r]);
+                mx = half_max(mx) * kLog2e;
+                if (__any(mx > mref[qb] + kRescaleTau)) {
+                    const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
+                    const float alpha = fast_exp2(mref[qb] - mnew);
+                    mref[qb] = mnew;
+                    lsum[qb] *= alpha;
+#pragma unroll
+                    for (int cb = 0; cb < C / 32; cb++)
+#pragma unroll
+                        for (int r = 0; r < 16; r++) oacc[qb][cb][r] *= alpha;
+                }
+                const float nm = -mref[qb];
+                float ps = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const float pr = fast_exp2(fmaf(s[qb][r], kLog2e, nm));
+                    ps += pr;
+                    pb[qb][r / 8][r % 8] = (bf16_t)pr;
+                }
+                lsum[qb] += ps;
+            }
+
+            // ---- O^T += V^T . P^T ----
+            // lane -> (row group, column group) of the LDS transpose read: 16-lane block
+            // blk = l32 / 16 covers channels 16*blk..+15, i = lane % 16 supplies row i/4,
+            // columns 4*(i%4)..+3; the half hf selects keys 4*hf..4*hf+3 (+8 for the high part),
+            // matching the keys of accumulator registers 0..3 / 4..7 of each 16-key group.
+            const int i16 = lane & 15, blk = l32 >> 4;
+            const bf16_t* vbase = vsrc + (kb * 32 + 4 * hf + (i16 >> 2)) * K::VP + 16 * blk + 4 * (i16 & 3);
+#pragma unroll
+            for (int cb = 0; cb < C / 32; cb++) {
+#pragma unroll
+                for (int kk = 0; kk < 2; kk++) {
+                    const bf16_t* vp = vbase + (kk * 16) * K::VP + cb * 32;
+                    const bf16x8 a = join_tr(lds_read_tr16(vp), lds_read_tr16(vp + 8 * K::VP));
+#pragma unroll
+                    for (int qb = 0; qb < QB; qb++) oacc[qb][cb] = mfma32(a, pb[qb][kk], oacc[qb][cb]);
+                }
+            }
+        }
+
+        if (more) store_tile((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: o = O / l, lse = m + ln l ----
+#pragma unroll
+    for (int qb = 0; qb < QB; qb++) {
+        const int qi = qw0 + qb * 32 + l32;
+        const float ltot = half_sum(lsum[qb]);
+        const float inv = 1.f / ltot;
+        if (qi < N) {
+            bf16_t* og = (bf16_t*)p.out + base + (size_t)qi * C;
+#pragma unroll
+            for (int cb = 0; cb < C / 32; cb++) {
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(oacc[qb][cb][4 * g + x] * inv);
+                    *(uint2*)(og + cb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(uint2, o4);
+                }
+            }
+            if (hf == 0) p.lse[(size_t)bh * N + qi] = (mref[qb] + __log2f(ltot)) * kLn2;
+        }
+    }
+}
+
+template <int C, int RP, int QB, int BK, bool CAUSAL, bool DENSE>
+int launch(const FwdParams& pin, hipStream_t stream) {
+    using K = Cfg<C, RP, QB, BK, DENSE>;
+    auto kern = fwd_bf16_kernel<C, RP, QB, BK, CAUSAL, DENSE>;
+    static bool attr_done = false;   // benign race: the call is idempotent
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)K::kLds) != hipSuccess)
+            return 1;
+        attr_done = true;
+    }
+    FwdParams p = pin;
+    p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
+    p.total_tiles = p.B * p.H * p.n_qtiles;
+    p.tiles_per_xcd = (p.total_tiles + 7) / 8;
+    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds, stream, p);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+template <int C, int RP, int QB, bool DENSE>
+int dispatch_causal(const FwdParams& p, hipStream_t stream) {
+    if (p.causal) return launch<C, RP, QB, 64, true, DENSE>(p, stream);
+    return launch<C, RP, QB, 64, false, DENSE>(p, stream);
+}
+
+template <int C, int RP, bool DENSE>
+int dispatch_qb(const FwdParams& p, int qb, hipStream_t stream) {
+    if (qb == 2) return dispatch_causal<C, RP, 2, DENSE>(p, stream);
+    return dispatch_causal<C, RP, 1, DENSE>(p, stream);
+}
+
+template <int C>
+int dispatch_rp(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream) {
+    if (dense) return dispatch_qb<C, 0, true>(p, qb, stream);
+    switch (rp) {
+        case 0: return dispatch_qb<C, 0, false>(p, qb, stream);
+        case 16: return dispatch_qb<C, 16, false>(p, qb, stream);
+        case 32: return dispatch_qb<C, 32, false>(p, qb, stream);
+        case 48: return dispatch_qb<C, 48, false>(p, qb, stream);
+        case 64: return dispatch_qb<C, 64, false>(p, qb, stream);
+        default: return -1;
+    }
+}
+
+}  // namespace
+
+// rp: padded factor width (multiple of 16, <= 64); qb: 32-row query blocks per wave (1 or 2).
+// Returns 0 on success, 1 on launch failure, -1 when no instantiation fits.
+int fb_launch_fwd_bf16(const FwdParams& p, int C, int rp, bool dense, int qb, hipStream_t stream) {
+    switch (C) {
+        case 32: return dispatch_rp<32>(p, rp, dense, qb, stream);
+        case 64: return dispatch_rp<64>(p, rp, dense, qb, stream);
+        case 128: return dispatch_rp<128>(p, rp, dense, qb, stream);
+        default: return -1;
+    }
+}

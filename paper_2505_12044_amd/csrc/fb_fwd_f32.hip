@@ -1,0 +1,147 @@
+// fp32 forward: attention with a factorised or dense additive bias, all arithmetic in fp32
+// FMA (gfx950's fp32 matrix rate equals its fp32 vector rate, so there is nothing to gain
+// from MFMA here).  This is the full-precision path (tolerance 1e-4 against float64).
+//
+// One thread owns one query row: [q*scale | phi_q] and the output accumulator live in
+// registers; key/value tiles are staged in LDS and read by all lanes at the same address
+// (a broadcast, conflict-free).  Scores of a tile are [q*scale | phi_q] . [k | phi_k]
+// (FlashBias Eq. 3) followed by an online softmax over tiles.
+#include <hip/hip_runtime.h>
+
+#include "fb_launch.h"
+#include "fb_params.h"
+
+namespace {
+
+constexpr int kThreads = 128;  // queries per workgroup
+constexpr int kTK = 32;        // keys per LDS tile
+
+template <int C, int RP, bool DENSE>
+__global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
+    constexpr int W = C + RP;
+    __shared__ float ks[kTK][W];
+    __shared__ float vs[kTK][C];
+
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.x / p.n_qtiles;
+    const int qt = blockIdx.x % p.n_qtiles;
+    const int b = bh / p.H, h = bh % p.H;
+    const int N = p.N, R = p.R;
+    const int i = qt * kThreads + tid;
+    const bool valid = i < N;
+
+    const size_t base = (size_t)bh * N * C;
+    const float* qg = (const float*)p.q + base;
+    const float* kg = (const float*)p.k + base;
+    const float* vg = (const float*)p.v + base;
+    const float* pqg = nullptr;
+    const float* pkg = nullptr;
+    if (RP > 0) {
+        const size_t pbase = (size_t)b * p.phi_bstride + (size_t)h * N * R;
+        pqg = (const float*)p.phi_q + pbase;
+        pkg = (const float*)p.phi_k + pbase;
+    }
+    const float* bg = nullptr;
+    if (DENSE) bg = (const float*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * N;
+
+    float qr[W];
+    float o[C];
+#pragma unroll
+    for (int c = 0; c < C; c++) {
+        qr[c] = valid ? qg[(size_t)i * C + c] * p.scale : 0.f;
+        o[c] = 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < RP; r++) qr[C + r] = (valid && r < R) ? pqg[(size_t)i * R + r] : 0.f;
+
+    float m = -INFINITY, l = 0.f;
+    const int n_keys = p.causal ? min(N, (qt + 1) * kThreads) : N;
+
+    for (int j0 = 0; j0 < n_keys; j0 += kTK) {
+        __syncthreads();
+        for (int e = tid; e < kTK * W; e += kThreads) {
+            const int jj = e / W, c = e % W;
+            const int j = j0 + jj;
+            float x = 0.f;
+            if (j < N) {
+                if (c < C) x = kg[(size_t)j * C + c];
+                else if (c - C < R) x = pkg[(size_t)j * R + (c - C)];
+            }
+            ks[jj][c] = x;
+        }
+        for (int e = tid; e < kTK * C; e += kThreads) {
+            const int jj = e / C, c = e % C;
+            const int j = j0 + jj;
+            vs[jj][c] = j < N ? vg[(size_t)j * C + c] : 0.f;
+        }
+        __syncthreads();
+
+        float s[kTK];
+        float mt = -INFINITY;
+#pragma unroll
+        for (int jj = 0; jj < kTK; jj++) {
+            float acc = 0.f;
+#pragma unroll
+            for (int c = 0; c < W; c++) acc = fmaf(qr[c], ks[jj][c], acc);
+            const int j = j0 + jj;
+            if (DENSE) {
+                if (valid && j < N) acc += bg[(size_t)i * N + j];
+            }
+            if (j >= N || (p.causal && j > i)) acc = -INFINITY;
+            s[jj] = acc;
+            mt = fmaxf(mt, acc);
+        }
+        const float m_new = fmaxf(m, mt);
+        const float alpha = expf(m - m_new);
+        l *= alpha;
+#pragma unroll
+        for (int c = 0; c < C; c++) o[c] *= alpha;
+#pragma unroll
+        for (int jj = 0; jj < kTK; jj++) {
+            const float pj = expf(s[jj] - m_new);
+            l += pj;
+#pragma unroll
+            for (int c = 0; c < C; c++) o[c] = fmaf(pj, vs[jj][c], o[c]);
+        }
+        m = m_new;
+    }
+
+    if (valid) {
+        const float inv = 1.f / l;
+        float* og = (float*)p.out + base + (size_t)i * C;
+#pragma unroll
+        for (int c = 0; c < C; c++) og[c] = o[c] * inv;
+        p.lse[(size_t)bh * N + i] = m + logf(l);
+    }
+}
+
+template <int C, int RP, bool DENSE>
+int launch(const FwdParams& p, hipStream_t stream) {
+    FwdParams q = p;
+    q.n_qtiles = (p.N + kThreads - 1) / kThreads;
+    q.total_tiles = p.B * p.H * q.n_qtiles;
+    hipLaunchKernelGGL((fwd_f32_kernel<C, RP, DENSE>), dim3(q.total_tiles), dim3(kThreads), 0, stream, q);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+template <int C>
+int dispatch_c(const FwdParams& p, bool dense, hipStream_t stream) {
+    if (dense) return launch<C, 0, true>(p, stream);
+    if (p.R == 0) return launch<C, 0, false>(p, stream);
+    if (p.R <= 8) return launch<C, 8, false>(p, stream);
+    if (p.R <= 32) return launch<C, 32, false>(p, stream);
+    return launch<C, 64, false>(p, stream);
+}
+
+}  // namespace
+
+// Returns 0 on success, 1 on launch failure, -1 when no instantiation fits.
+int fb_launch_fwd_f32(const FwdParams& p, int C, bool dense, hipStream_t stream) {
+    if (p.R > 64) return -1;
+    switch (C) {
+        case 32: return dispatch_c<32>(p, dense, stream);
+        case 64: return dispatch_c<64>(p, dense, stream);
+        case 128: return dispatch_c<128>(p, dense, stream);
+        default: return -1;
+    }
+}

@@ -1,0 +1,15 @@
+// Internal launchers (one per kernel family); defined in the matching .hip file.
+// Each returns 0 on success, 1 when the HIP runtime rejected the launch, -1 when the
+// requested shape has no instantiation.
+#ifndef FB_LAUNCH_H_
+#define FB_LAUNCH_H_
+
+#include <hip/hip_runtime.h>
+
+#include "fb_params.h"
+
+int fb_launch_fwd_f32(const FwdParams& p, int C, bool dense, hipStream_t stream);
+int fb_launch_fwd_bf16(const FwdParams& p, int C, int rp, bool dense, int qb, hipStream_t stream);
+int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream);
+
+#endif

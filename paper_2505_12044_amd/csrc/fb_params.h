@@ -1,0 +1,44 @@
+// Host/device-shared parameter blocks for the attention kernels (plain data only).
+#ifndef FB_PARAMS_H_
+#define FB_PARAMS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+struct FwdParams {
+    const void* q;        // [B,H,N,C]
+    const void* k;
+    const void* v;
+    const void* phi_q;    // [Bp,H,N,R] or null
+    const void* phi_k;
+    const void* bias;     // [Bb,H,N,N] or null (dense-bias mode)
+    void* out;            // [B,H,N,C]
+    float* lse;           // [B,H,N]
+    int B, H, N, R;
+    int causal;
+    int phi_f32;          // factors stored as float (else bf16)
+    long long phi_bstride;   // elements between batch items of phi (0 when shared over batch)
+    long long bias_bstride;  // elements between batch items of bias (0 when shared)
+    float scale;
+    int n_qtiles;         // query tiles per (b,h)
+    int total_tiles;      // B*H*n_qtiles
+    int tiles_per_xcd;    // ceil(total_tiles / 8)
+};
+
+struct BwdParams {
+    const void* q; const void* k; const void* v;
+    const void* phi_q; const void* phi_k;
+    const void* out; const float* lse; const void* dout;
+    void* dq; void* dk; void* dv; void* dphi_q; void* dphi_k;
+    float* delta;         // [B,H,N] workspace: rowsum(dout * out)
+    int B, H, N, R;
+    int causal;
+    int phi_f32;
+    long long phi_bstride;
+    float scale;
+    int n_tiles;          // tiles per (b,h) along the kernel's outer dimension
+    int total_tiles;
+    int tiles_per_xcd;
+};
+
+#endif
