@@ -132,6 +132,7 @@ FB_DEV uint4 phi_chunk_raw(const void* row, int c8, int R, bool f32, bool row_va
     }
     return raw;
 }
+template <bool QSIDE = false>
 FB_DEV bf16x8 phi_chunk_finish(uint4 raw, int c8, bool f32) {
     if (!f32) return as_bf16x8(raw);
     bf16x8 out;
@@ -142,7 +143,8 @@ FB_DEV bf16x8 phi_chunk_finish(uint4 raw, int c8, bool f32) {
         const int r = j / 6, slot = j - 6 * r;
         const int d = r - r0;
         const unsigned u = d == 0 ? raw.x : (d == 1 ? raw.y : raw.z);
-        out[e] = bf16_limb(__builtin_bit_cast(float, u), k_limb_of_slot(slot));
+        out[e] = bf16_limb(__builtin_bit_cast(float, u),
+                           QSIDE ? q_limb_of_slot(slot) : k_limb_of_slot(slot));
     }
     return out;
 }
