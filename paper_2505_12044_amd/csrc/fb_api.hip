@@ -29,14 +29,17 @@ int check_common(int B, int H, int N, int C, int R) {
     return FB_OK;
 }
 
-int pick_qb(int B, int H, int N, int C, int rp) {
+int pick_qb(int B, int H, int N, int C, int rp, bool dense) {
     const int forced = g_fwd_qb.load(std::memory_order_relaxed);
     if (forced == 1 || forced == 2) return forced;
-    // Two query blocks per wave halve the LDS traffic per MFMA but need 256-row tiles: use
-    // them when that still leaves every CU several workgroups.
-    const long long tiles256 = (long long)B * H * ((N + 255) / 256);
+    (void)rp;
+    // Two query blocks per wave halve the LDS traffic per MFMA but double the accumulator
+    // registers: they fit the 256-register budget (two waves per SIMD) only for C <= 64, and
+    // only pay when 256-row tiles still leave every CU several workgroups.
+    if (C == 128 || dense) return 1;
     if (N % 256 != 0 && N < 1024) return 1;
-    return tiles256 >= 512 ? 2 : 1;
+    const long long tiles256 = (long long)B * H * ((N + 255) / 256);
+    return tiles256 >= 1024 ? 2 : 1;
 }
 
 }  // namespace
@@ -95,7 +98,7 @@ int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int rc;
     if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, false, (hipStream_t)stream);
-    else rc = fb_launch_fwd_bf16(p, C, rp, false, pick_qb(B, H, N, C, rp), (hipStream_t)stream);
+    else rc = fb_launch_fwd_bf16(p, C, rp, false, pick_qb(B, H, N, C, rp, false), (hipStream_t)stream);
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
@@ -119,7 +122,7 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int rc;
     if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, true, (hipStream_t)stream);
-    else rc = fb_launch_fwd_bf16(p, C, 0, true, pick_qb(B, H, N, C, 0), (hipStream_t)stream);
+    else rc = fb_launch_fwd_bf16(p, C, 0, true, pick_qb(B, H, N, C, 0, true), (hipStream_t)stream);
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 

@@ -47,8 +47,8 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const bf16_t* __restrict
     const int c8 = (int)(gid % LPR);
     float acc = 0.f;
     if (row < rows) {
-        const bf16x8 a = as_bf16x8(*(const uint4*)(out + row * C + c8 * 8));
-        const bf16x8 b = as_bf16x8(*(const uint4*)(dout + row * C + c8 * 8));
+        const bf16x8 a = as_bf16x8(*(const u32x4*)(out + row * C + c8 * 8));
+        const bf16x8 b = as_bf16x8(*(const u32x4*)(dout + row * C + c8 * 8));
 #pragma unroll
         for (int e = 0; e < 8; e++) acc = fmaf((float)a[e], (float)b[e], acc);
     }
@@ -152,8 +152,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
     for (int ks = 0; ks < K::KS; ks++) {
         bf16x8 val;
         if (ks < C / 16) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (qok) raw = *(const uint4*)(qg + (size_t)qi * C + ks * 16 + 8 * hf);
+            u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+            if (qok) raw = *(const u32x4*)(qg + (size_t)qi * C + ks * 16 + 8 * hf);
             const bf16x8 x = as_bf16x8(raw);
 #pragma unroll
             for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
@@ -170,8 +170,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
     }
 #pragma unroll
     for (int cs = 0; cs < C / 16; cs++) {
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        if (qok) raw = *(const uint4*)(dog + (size_t)qi * C + cs * 16 + 8 * hf);
+        u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+        if (qok) raw = *(const u32x4*)(dog + (size_t)qi * C + cs * 16 + 8 * hf);
         doreg[cs] = as_bf16x8(raw);
     }
     const float lse2 = qok ? p.lse[(size_t)bh * N + qi] * kLog2e : INFINITY;
@@ -186,8 +186,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
     const int kend = CAUSAL ? min(N, q0 + BQ) : N;
     const int nT = (kend + BK - 1) / BK;
 
-    uint4 kraw[K::XIT], vraw[K::XIT];
-    uint4 praw[K::PIT > 0 ? K::PIT : 1];
+    u32x4 kraw[K::XIT], vraw[K::XIT];
+    u32x4 praw[K::PIT > 0 ? K::PIT : 1];
 
     auto load_tile = [&](int t) {
         const int k0 = t * BK;
@@ -196,10 +196,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
             const int e = tid + it * kThreads;
             const int row = e / (C / 8), c8 = e % (C / 8);
             const int j = k0 + row;
-            uint4 a = make_uint4(0, 0, 0, 0), bb = a;
+            u32x4 a = u32x4{0u, 0u, 0u, 0u}, bb = a;
             if (j < N) {
-                a = *(const uint4*)(kg + (size_t)j * C + c8 * 8);
-                bb = *(const uint4*)(vg + (size_t)j * C + c8 * 8);
+                a = *(const u32x4*)(kg + (size_t)j * C + c8 * 8);
+                bb = *(const u32x4*)(vg + (size_t)j * C + c8 * 8);
             }
             kraw[it] = a;
             vraw[it] = bb;
@@ -223,8 +223,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
         for (int it = 0; it < K::XIT; it++) {
             const int e = tid + it * kThreads;
             const int row = e / (C / 8), c8 = e % (C / 8);
-            *(uint4*)(kdst + row * K::AP + c8 * 8) = kraw[it];
-            *(uint4*)(vdst + row * K::DP + c8 * 8) = vraw[it];
+            *(u32x4*)(kdst + row * K::AP + c8 * 8) = kraw[it];
+            *(u32x4*)(vdst + row * K::DP + c8 * 8) = vraw[it];
         }
         if (RP > 0) {
 #pragma unroll
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
                 const int e = tid + it * kThreads;
                 if (e < K::PCH) {
                     const int row = e / (K::RP2 / 8), c8 = e % (K::RP2 / 8);
-                    *(uint4*)(kdst + row * K::AP + C + c8 * 8) =
+                    *(u32x4*)(kdst + row * K::AP + C + c8 * 8) =
                         as_uint4(phi_chunk_finish<false>(praw[it], c8, phi_f32));
                 }
             }
@@ -261,10 +261,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
             const bf16_t* vrow = vsrc + (kb * 32 + l32) * K::DP + 8 * hf;
 #pragma unroll
             for (int ks = 0; ks < K::KS; ks++)
-                s = mfma32(as_bf16x8(*(const uint4*)(krow + ks * 16)), qreg[ks], s);
+                s = mfma32(as_bf16x8(*(const u32x4*)(krow + ks * 16)), qreg[ks], s);
 #pragma unroll
             for (int cs = 0; cs < C / 16; cs++)
-                dp = mfma32(as_bf16x8(*(const uint4*)(vrow + cs * 16)), doreg[cs], dp);
+                dp = mfma32(as_bf16x8(*(const u32x4*)(vrow + cs * 16)), doreg[cs], dp);
 
             bf16x8 dsb[2];
             const bool need_mask = (CAUSAL && kb0 + 31 > q0 + wave * 32) || kb0 + 32 > N;
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
                 bf16x4 o4;
 #pragma unroll
                 for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(dacc[mb][4 * g + x] * p.scale);
-                *(uint2*)(dqg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(uint2, o4);
+                *(u32x2*)(dqg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, o4);
             }
     }
     if (RP > 0) {
@@ -362,8 +362,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
     for (int ks = 0; ks < K::KS; ks++) {
         bf16x8 val;
         if (ks < C / 16) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (kok) raw = *(const uint4*)(kg + (size_t)ki * C + ks * 16 + 8 * hf);
+            u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+            if (kok) raw = *(const u32x4*)(kg + (size_t)ki * C + ks * 16 + 8 * hf);
             val = as_bf16x8(raw);
         } else {
             const int c8 = (ks - C / 16) * 2 + hf;
@@ -378,8 +378,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
     }
 #pragma unroll
     for (int cs = 0; cs < C / 16; cs++) {
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        if (kok) raw = *(const uint4*)(vg + (size_t)ki * C + cs * 16 + 8 * hf);
+        u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+        if (kok) raw = *(const u32x4*)(vg + (size_t)ki * C + cs * 16 + 8 * hf);
         vreg[cs] = as_bf16x8(raw);
     }
 
@@ -395,8 +395,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
     const int nQT = (N + BQ - 1) / BQ;
     const int t0 = CAUSAL ? k0 / BQ : 0;
 
-    uint4 qraw[K::XIT], draw[K::XIT];
-    uint4 praw[K::PIT > 0 ? K::PIT : 1];
+    u32x4 qraw[K::XIT], draw[K::XIT];
+    u32x4 praw[K::PIT > 0 ? K::PIT : 1];
     float vecraw = 0.f;
 
     auto load_tile = [&](int t) {
@@ -406,10 +406,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
             const int e = tid + it * kThreads;
             const int row = e / (C / 8), c8 = e % (C / 8);
             const int i = r0 + row;
-            uint4 a = make_uint4(0, 0, 0, 0), bb = a;
+            u32x4 a = u32x4{0u, 0u, 0u, 0u}, bb = a;
             if (i < N) {
-                a = *(const uint4*)(qg + (size_t)i * C + c8 * 8);
-                bb = *(const uint4*)(dog + (size_t)i * C + c8 * 8);
+                a = *(const u32x4*)(qg + (size_t)i * C + c8 * 8);
+                bb = *(const u32x4*)(dog + (size_t)i * C + c8 * 8);
             }
             qraw[it] = a;
             draw[it] = bb;
@@ -442,8 +442,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
             bf16x8 y;
 #pragma unroll
             for (int z = 0; z < 8; z++) y[z] = (bf16_t)((float)x[z] * p.scale);
-            *(uint4*)(adst + row * K::AP + c8 * 8) = as_uint4(y);
-            *(uint4*)(ddst + row * K::DP + c8 * 8) = draw[it];
+            *(u32x4*)(adst + row * K::AP + c8 * 8) = as_uint4(y);
+            *(u32x4*)(ddst + row * K::DP + c8 * 8) = draw[it];
         }
         if (RP > 0) {
 #pragma unroll
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
                 const int e = tid + it * kThreads;
                 if (e < K::PCH) {
                     const int row = e / (K::RP2 / 8), c8 = e % (K::RP2 / 8);
-                    *(uint4*)(adst + row * K::AP + C + c8 * 8) =
+                    *(u32x4*)(adst + row * K::AP + C + c8 * 8) =
                         as_uint4(phi_chunk_finish<true>(praw[it], c8, phi_f32));
                 }
             }
@@ -487,10 +487,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
             const bf16_t* drow = dsrc + (qb * 32 + l32) * K::DP + 8 * hf;
 #pragma unroll
             for (int ks = 0; ks < K::KS; ks++)
-                s = mfma32(as_bf16x8(*(const uint4*)(arow + ks * 16)), akreg[ks], s);
+                s = mfma32(as_bf16x8(*(const u32x4*)(arow + ks * 16)), akreg[ks], s);
 #pragma unroll
             for (int cs = 0; cs < C / 16; cs++)
-                dp = mfma32(as_bf16x8(*(const uint4*)(drow + cs * 16)), vreg[cs], dp);
+                dp = mfma32(as_bf16x8(*(const u32x4*)(drow + cs * 16)), vreg[cs], dp);
 
             bf16x8 pb[2], dsb[2];
             const bool need_mask = CAUSAL && qb0 < kw0 + 31;
@@ -549,8 +549,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
                     a4[x] = (bf16_t)dvacc[mb][4 * g + x];
                     b4[x] = (bf16_t)dkacc[mb][4 * g + x];
                 }
-                *(uint2*)(dvg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(uint2, a4);
-                *(uint2*)(dkg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(uint2, b4);
+                *(u32x2*)(dvg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, a4);
+                *(u32x2*)(dkg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, b4);
             }
     }
     if (RP > 0) {

@@ -16,6 +16,8 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 #define FB_DEV __device__ __forceinline__
 
@@ -33,8 +35,8 @@ FB_DEV f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-FB_DEV bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
-FB_DEV uint4 as_uint4(bf16x8 v) { return __builtin_bit_cast(uint4, v); }
+FB_DEV bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
+FB_DEV u32x4 as_uint4(bf16x8 v) { return __builtin_bit_cast(u32x4, v); }
 
 // Exchange across the two 32-lane halves (v_permlane32_swap): given registers (a, b) the
 // instruction returns ({a.lo, b.lo}, {a.hi, b.hi}) where .lo/.hi are the values held by lanes
@@ -114,12 +116,12 @@ FB_DEV bf16x8 phi_chunk_gather(const void* row, int c8, int R, bool f32) {
 
 // Two-step variant for the key side, so the global loads of the next tile can stay in
 // flight during compute: phi_chunk_raw issues the loads, phi_chunk_finish converts.
-FB_DEV uint4 phi_chunk_raw(const void* row, int c8, int R, bool f32, bool row_valid) {
-    uint4 raw = make_uint4(0, 0, 0, 0);
+FB_DEV u32x4 phi_chunk_raw(const void* row, int c8, int R, bool f32, bool row_valid) {
+    u32x4 raw = u32x4{0u, 0u, 0u, 0u};
     if (!row_valid) return raw;
     if (!f32) {
         if ((R & 7) == 0) {
-            if (c8 * 8 < R) raw = *(const uint4*)((const bf16_t*)row + c8 * 8);
+            if (c8 * 8 < R) raw = *(const u32x4*)((const bf16_t*)row + c8 * 8);
         } else {
             raw = as_uint4(phi_chunk_gather<false>(row, c8, R, false));
         }
@@ -133,7 +135,7 @@ FB_DEV uint4 phi_chunk_raw(const void* row, int c8, int R, bool f32, bool row_va
     return raw;
 }
 template <bool QSIDE = false>
-FB_DEV bf16x8 phi_chunk_finish(uint4 raw, int c8, bool f32) {
+FB_DEV bf16x8 phi_chunk_finish(u32x4 raw, int c8, bool f32) {
     if (!f32) return as_bf16x8(raw);
     bf16x8 out;
     const int r0 = (c8 * 8) / 6;

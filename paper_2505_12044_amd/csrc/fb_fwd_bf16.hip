@@ -18,6 +18,8 @@
 // touches LDS; and rescaling O by a per-query factor is a per-lane multiply.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "fb_device.h"
 #include "fb_launch.h"
 #include "fb_params.h"
@@ -39,7 +41,7 @@ struct Cfg {
     static constexpr int BQ = kWaves * QB * 32;
     static constexpr int KB = BK / 32;                // 32-key blocks per tile
     static constexpr int KCH = BK * C / 8;            // 16-byte chunks of the K (or V) part of a tile
-    static constexpr int KIT = KCH / kThreads;        // per-thread chunks
+    static constexpr int KIT = (KCH + kThreads - 1) / kThreads;   // per-thread chunks
     static constexpr int PCH = BK * RP / 8;           // chunks of the factor part
     static constexpr int PIT = (PCH + kThreads - 1) / kThreads;
     static constexpr int BP = BK + 4;                 // dense: bias tile row pitch (elements)
@@ -47,12 +49,13 @@ struct Cfg {
     static constexpr int BIT = BROWS * (BK / 8) / 64;  // dense: per-lane 16-byte chunks
     static constexpr size_t kLds =
         (size_t)2 * BK * (KP + VP) * 2 + (DENSE ? (size_t)kWaves * BROWS * BP * 2 : 0);
-    static_assert(KCH % kThreads == 0, "tile must split evenly over the workgroup");
     static_assert(BK % 32 == 0 && (C % 32) == 0 && (RP % 16) == 0, "shape granularity");
 };
 
+// Two workgroups per CU (two waves per SIMD, at most 256 registers each): while one wave
+// waits on the matrix pipe the other runs its softmax on the vector pipe.
 template <int C, int RP, int QB, int BK, bool CAUSAL, bool DENSE>
-__global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
+__global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     using K = Cfg<C, RP, QB, BK, DENSE>;
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* const kt = (bf16_t*)smem;                 // [2][BK][KP]
@@ -91,29 +94,22 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
     const bf16_t* bg = nullptr;
     if (DENSE) bg = (const bf16_t*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * N;
 
-    // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout) ----
+    // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout).  Rows past N
+    // read row N-1 (finite values) and are never stored.
     bf16x8 qreg[QB][K::KS];
 #pragma unroll
     for (int qb = 0; qb < QB; qb++) {
-        const int qi = qw0 + qb * 32 + l32;
-        const bool ok = qi < N;
+        const int qi = min(qw0 + qb * 32 + l32, N - 1);
 #pragma unroll
         for (int ks = 0; ks < K::KS; ks++) {
             bf16x8 val;
             if (ks < C / 16) {
-                uint4 raw = make_uint4(0, 0, 0, 0);
-                if (ok) raw = *(const uint4*)(qg + (size_t)qi * C + ks * 16 + 8 * hf);
-                const bf16x8 x = as_bf16x8(raw);
+                const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qi * C + ks * 16 + 8 * hf));
 #pragma unroll
                 for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
             } else {
                 const int c8 = (ks - C / 16) * 2 + hf;
-                if (ok) {
-                    val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
-                }
+                val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
             }
             qreg[qb][ks] = val;
         }
@@ -134,10 +130,11 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
     const int kend = CAUSAL ? min(N, q0 + K::BQ) : N;
     const int nT = (kend + BK - 1) / BK;
 
-    // ---- tile staging: global -> registers -> LDS ----
-    uint4 kraw[K::KIT], vraw[K::KIT];
-    uint4 praw[K::PIT > 0 ? K::PIT : 1];
-    uint4 braw[DENSE ? K::BIT : 1];
+    // ---- tile staging: global -> registers -> LDS.  Rows past N are clamped to row N-1; the
+    // keys they stand for are masked to -inf before the softmax, so their values never count.
+    u32x4 kraw[K::KIT], vraw[K::KIT];
+    u32x4 praw[K::PIT > 0 ? K::PIT : 1];
+    u32x4 braw[DENSE ? K::BIT : 1];
     const bool bias_fast = DENSE && ((N & 7) == 0);
 
     auto load_tile = [&](int t) {
@@ -145,24 +142,21 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
 #pragma unroll
         for (int it = 0; it < K::KIT; it++) {
             const int e = tid + it * kThreads;
-            const int row = e / (C / 8), c8 = e % (C / 8);
-            const int j = k0 + row;
-            uint4 a = make_uint4(0, 0, 0, 0), bb = a;
-            if (j < N) {
-                a = *(const uint4*)(kg + (size_t)j * C + c8 * 8);
-                bb = *(const uint4*)(vg + (size_t)j * C + c8 * 8);
+            if (K::KCH % kThreads == 0 || e < K::KCH) {
+                const int row = e / (C / 8), c8 = e % (C / 8);
+                const int j = min(k0 + row, N - 1);
+                kraw[it] = *(const u32x4*)(kg + (size_t)j * C + c8 * 8);
+                vraw[it] = *(const u32x4*)(vg + (size_t)j * C + c8 * 8);
             }
-            kraw[it] = a;
-            vraw[it] = bb;
         }
         if (RP > 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
                 const int e = tid + it * kThreads;
-                if (e < K::PCH) {
+                if (K::PCH % kThreads == 0 || e < K::PCH) {
                     const int row = e / (RP / 8), c8 = e % (RP / 8);
-                    const int j = k0 + row;
-                    praw[it] = phi_chunk_raw(pkg + (size_t)j * R * phi_esz, c8, R, phi_f32, j < N);
+                    const int j = min(k0 + row, N - 1);
+                    praw[it] = phi_chunk_raw(pkg + (size_t)j * R * phi_esz, c8, R, phi_f32, true);
                 }
             }
         }
@@ -173,12 +167,12 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
                 const int row = e / (BK / 8), c8 = e % (BK / 8);
                 const int qi = qw0 + row;
                 const int j = k0 + c8 * 8;
-                uint4 a = make_uint4(0, 0, 0, 0);
+                u32x4 a = u32x4{0u, 0u, 0u, 0u};
                 // chunks wholly above the diagonal are never read when causal
                 if (qi < N && j < N && !(CAUSAL && j > qi)) {
                     const bf16_t* src = bg + (size_t)qi * N + j;
                     if (bias_fast) {
-                        a = *(const uint4*)src;
+                        a = *(const u32x4*)src;
                     } else {
                         bf16x8 tmp;
 #pragma unroll
@@ -197,18 +191,20 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
 #pragma unroll
         for (int it = 0; it < K::KIT; it++) {
             const int e = tid + it * kThreads;
-            const int row = e / (C / 8), c8 = e % (C / 8);
-            *(uint4*)(kdst + row * K::KP + c8 * 8) = kraw[it];
-            *(uint4*)(vdst + row * K::VP + c8 * 8) = vraw[it];
+            if (K::KCH % kThreads == 0 || e < K::KCH) {
+                const int row = e / (C / 8), c8 = e % (C / 8);
+                *(u32x4*)(kdst + row * K::KP + c8 * 8) = kraw[it];
+                *(u32x4*)(vdst + row * K::VP + c8 * 8) = vraw[it];
+            }
         }
         if (RP > 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
                 const int e = tid + it * kThreads;
-                if (e < K::PCH) {
+                if (K::PCH % kThreads == 0 || e < K::PCH) {
                     const int row = e / (RP / 8), c8 = e % (RP / 8);
-                    *(uint4*)(kdst + row * K::KP + C + c8 * 8) =
-                        as_uint4(phi_chunk_finish(praw[it], c8, phi_f32));
+                    *(u32x4*)(kdst + row * K::KP + C + c8 * 8) =
+                        as_uint4(phi_chunk_finish<false>(praw[it], c8, phi_f32));
                 }
             }
         }
@@ -218,9 +214,95 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
             for (int it = 0; it < K::BIT; it++) {
                 const int e = lane + it * 64;
                 const int row = e / (BK / 8), c8 = e % (BK / 8);
-                uint2* d = (uint2*)(bdst + row * K::BP + c8 * 8);   // 8-byte aligned rows
-                d[0] = make_uint2(braw[it].x, braw[it].y);
-                d[1] = make_uint2(braw[it].z, braw[it].w);
+                u32x2* d = (u32x2*)(bdst + row * K::BP + c8 * 8);   // 8-byte aligned rows
+                d[0] = u32x2{braw[it].x, braw[it].y};
+                d[1] = u32x2{braw[it].z, braw[it].w};
+            }
+        }
+    };
+
+    // lane -> (row group, column group) of the LDS transpose read: the 16-lane group
+    // blk = l32 / 16 covers channels 16*blk..+15, lane i = lane % 16 supplies row i/4, columns
+    // 4*(i%4)..+3; the half hf selects keys 4*hf..4*hf+3 (+8 for the high part), matching the
+    // keys of accumulator registers 0..3 / 4..7 of each 16-key group.
+    const int i16 = lane & 15, blk = l32 >> 4;
+    const int vlane_off = (4 * hf + (i16 >> 2)) * K::VP + 16 * blk + 4 * (i16 & 3);
+
+    // One 32-key block against this wave's query blocks.  MASKED instances apply the causal
+    // and sequence-end masks; interior blocks skip that code entirely.
+    auto block = [&](const bf16_t* ksrc, const bf16_t* vsrc, int kb, int kb0, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        // ---- S^T = Kt . Qreg ----
+        f32x16 s[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) s[qb][r] = 0.f;
+        const bf16_t* krow = ksrc + (kb * 32 + l32) * K::KP + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < K::KS; ks++) {
+            const bf16x8 a = as_bf16x8(*(const u32x4*)(krow + ks * 16));
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(a, qreg[qb][ks], s[qb]);
+        }
+
+        bf16x8 pb[QB][2];
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) {
+            const int qi = qw0 + qb * 32 + l32;
+            if (DENSE) {
+                const bf16_t* brow = bt + (wave * K::BROWS + qb * 32 + l32) * K::BP + kb * 32 + 4 * hf;
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    const u32x2 u = *(const u32x2*)(brow + 8 * g);
+                    const bf16x4 bv = __builtin_bit_cast(bf16x4, u);
+#pragma unroll
+                    for (int x = 0; x < 4; x++) s[qb][4 * g + x] += (float)bv[x];
+                }
+            }
+            if (MASKED) {
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int key = kb0 + 8 * (r / 4) + 4 * hf + (r % 4);
+                    if (key >= N || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
+                }
+            }
+            // ---- online softmax: the row lives in this lane and the one 32 away ----
+            float mx = fmaxf(s[qb][0], s[qb][1]);
+#pragma unroll
+            for (int r = 2; r < 16; r++) mx = fmaxf(mx, s[qb][r]);
+            mx = half_max(mx) * kLog2e;
+            if (__any(mx > mref[qb] + kRescaleTau)) {
+                const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
+                const float alpha = fast_exp2(mref[qb] - mnew);
+                mref[qb] = mnew;
+                lsum[qb] *= alpha;
+#pragma unroll
+                for (int cb = 0; cb < C / 32; cb++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) oacc[qb][cb][r] *= alpha;
+            }
+            const float nm = -mref[qb];
+            float ps = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const float pr = fast_exp2(fmaf(s[qb][r], kLog2e, nm));
+                ps += pr;
+                pb[qb][r / 8][r % 8] = (bf16_t)pr;
+            }
+            lsum[qb] += ps;
+        }
+
+        // ---- O^T += V^T . P^T ----
+        const bf16_t* vbase = vsrc + (kb * 32) * K::VP + vlane_off;
+#pragma unroll
+        for (int cb = 0; cb < C / 32; cb++) {
+#pragma unroll
+            for (int kk = 0; kk < 2; kk++) {
+                const bf16_t* vp = vbase + (kk * 16) * K::VP + cb * 32;
+                const bf16x8 a = join_tr(lds_read_tr16(vp), lds_read_tr16(vp + 8 * K::VP));
+#pragma unroll
+                for (int qb = 0; qb < QB; qb++) oacc[qb][cb] = mfma32(a, pb[qb][kk], oacc[qb][cb]);
             }
         }
     };
@@ -236,92 +318,20 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
         const bf16_t* ksrc = kt + (t & 1) * BK * K::KP;
         const bf16_t* vsrc = vt + (t & 1) * BK * K::VP;
         const int k0 = t * BK;
-
+        // wave-uniform: does any key of this tile need masking for any of this wave's rows?
+        const bool tile_masked = (k0 + BK > N) || (CAUSAL && k0 + BK - 1 > qw0);
+        if (!tile_masked) {
 #pragma unroll
-        for (int kb = 0; kb < K::KB; kb++) {
-            const int kb0 = k0 + kb * 32;
-            // this wave's rows all precede the block: nothing visible (wave-uniform)
-            if (CAUSAL && kb0 > qw0 + QB * 32 - 1) continue;
-
-            // ---- S^T = Kt . Qreg ----
-            f32x16 s[QB];
+            for (int kb = 0; kb < K::KB; kb++)
+                block(ksrc, vsrc, kb, k0 + kb * 32, std::false_type{});
+        } else {
 #pragma unroll
-            for (int qb = 0; qb < QB; qb++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) s[qb][r] = 0.f;
-            const bf16_t* krow = ksrc + (kb * 32 + l32) * K::KP + 8 * hf;
-#pragma unroll
-            for (int ks = 0; ks < K::KS; ks++) {
-                const bf16x8 a = as_bf16x8(*(const uint4*)(krow + ks * 16));
-#pragma unroll
-                for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(a, qreg[qb][ks], s[qb]);
-            }
-
-            bf16x8 pb[QB][2];
-#pragma unroll
-            for (int qb = 0; qb < QB; qb++) {
-                const int qmin = qw0 + qb * 32;
-                const int qi = qmin + l32;
-                if (DENSE) {
-                    const bf16_t* brow = bt + (wave * K::BROWS + qb * 32 + l32) * K::BP + kb * 32 + 4 * hf;
-#pragma unroll
-                    for (int g = 0; g < 4; g++) {
-                        const uint2 u = *(const uint2*)(brow + 8 * g);
-                        const bf16x4 bv = __builtin_bit_cast(bf16x4, u);
-#pragma unroll
-                        for (int x = 0; x < 4; x++) s[qb][4 * g + x] += (float)bv[x];
-                    }
-                }
-                const bool diag = CAUSAL && (kb0 + 31 > qmin);
-                if (diag || kb0 + 32 > N) {
-#pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const int key = kb0 + 8 * (r / 4) + 4 * hf + (r % 4);
-                        if (key >= N || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
-                    }
-                }
-                // ---- online softmax: the row lives in this lane and the one 32 away ----
-                float mx = s[qb][0];
-#pragma unroll
-                for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[qb][r]);
-                mx = half_max(mx) * kLog2e;
-                if (__any(mx > mref[qb] + kRescaleTau)) {
-                    const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
-                    const float alpha = fast_exp2(mref[qb] - mnew);
-                    mref[qb] = mnew;
-                    lsum[qb] *= alpha;
-#pragma unroll
-                    for (int cb = 0; cb < C / 32; cb++)
-#pragma unroll
-                        for (int r = 0; r < 16; r++) oacc[qb][cb][r] *= alpha;
-                }
-                const float nm = -mref[qb];
-                float ps = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const float pr = fast_exp2(fmaf(s[qb][r], kLog2e, nm));
-                    ps += pr;
-                    pb[qb][r / 8][r % 8] = (bf16_t)pr;
-                }
-                lsum[qb] += ps;
-            }
-
-            // ---- O^T += V^T . P^T ----
-            // lane -> (row group, column group) of the LDS transpose read: 16-lane block
-            // blk = l32 / 16 covers channels 16*blk..+15, i = lane % 16 supplies row i/4,
-            // columns 4*(i%4)..+3; the half hf selects keys 4*hf..4*hf+3 (+8 for the high part),
-            // matching the keys of accumulator registers 0..3 / 4..7 of each 16-key group.
-            const int i16 = lane & 15, blk = l32 >> 4;
-            const bf16_t* vbase = vsrc + (kb * 32 + 4 * hf + (i16 >> 2)) * K::VP + 16 * blk + 4 * (i16 & 3);
-#pragma unroll
-            for (int cb = 0; cb < C / 32; cb++) {
-#pragma unroll
-                for (int kk = 0; kk < 2; kk++) {
-                    const bf16_t* vp = vbase + (kk * 16) * K::VP + cb * 32;
-                    const bf16x8 a = join_tr(lds_read_tr16(vp), lds_read_tr16(vp + 8 * K::VP));
-#pragma unroll
-                    for (int qb = 0; qb < QB; qb++) oacc[qb][cb] = mfma32(a, pb[qb][kk], oacc[qb][cb]);
-                }
+            for (int kb = 0; kb < K::KB; kb++) {
+                const int kb0 = k0 + kb * 32;
+                // nothing visible: every row of this wave precedes the block (wave-uniform)
+                if (CAUSAL && kb0 > qw0 + QB * 32 - 1) continue;
+                if (kb0 >= N) continue;
+                block(ksrc, vsrc, kb, kb0, std::true_type{});
             }
         }
 
@@ -344,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(FwdParams p) {
                     bf16x4 o4;
 #pragma unroll
                     for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(oacc[qb][cb][4 * g + x] * inv);
-                    *(uint2*)(og + cb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(uint2, o4);
+                    *(u32x2*)(og + cb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, o4);
                 }
             }
             if (hf == 0) p.lse[(size_t)bh * N + qi] = (mref[qb] + __log2f(ltot)) * kLn2;
@@ -371,10 +381,17 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
+// Keys per LDS tile: 64 when two workgroups (two tile pairs) still fit one CU's 160 KB LDS.
+template <int C, int RP, int QB, bool DENSE>
+constexpr int pick_bk() {
+    return Cfg<C, RP, QB, 64, DENSE>::kLds <= 80 * 1024 ? 64 : 32;
+}
+
 template <int C, int RP, int QB, bool DENSE>
 int dispatch_causal(const FwdParams& p, hipStream_t stream) {
-    if (p.causal) return launch<C, RP, QB, 64, true, DENSE>(p, stream);
-    return launch<C, RP, QB, 64, false, DENSE>(p, stream);
+    constexpr int BK = pick_bk<C, RP, QB, DENSE>();
+    if (p.causal) return launch<C, RP, QB, BK, true, DENSE>(p, stream);
+    return launch<C, RP, QB, BK, false, DENSE>(p, stream);
 }
 
 template <int C, int RP, bool DENSE>

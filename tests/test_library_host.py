@@ -1,0 +1,100 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_12044_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "flashbias.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(api.LIB_PATH):
+        from paper_2505_12044_amd import build
+        build.build(force=False)
+    return api.load_library()
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = _declared_symbols()
+    assert set(names) == set(api.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings(lib):
+    assert lib.fb_version() >= 100
+    assert lib.fb_status_string(0) == b"ok"
+    seen = {lib.fb_status_string(i) for i in range(7)}
+    assert len(seen) == 7
+    assert lib.fb_status_string(99) == b"unknown status"
+
+
+def _fwd(lib, **kw):
+    a = dict(q=64, k=64, v=64, phi_q=64, phi_k=64, out=64, lse=64, B=1, H=1, N=16, C=64, R=4,
+             causal=0, dtype=api.FB_BF16, phi_dtype=api.FB_BF16, bcast=0, scale=0.0)
+    a.update(kw)
+    return lib.fb_lowrank_attn_fwd(a["q"], a["k"], a["v"], a["phi_q"], a["phi_k"], a["out"], a["lse"],
+                                   a["B"], a["H"], a["N"], a["C"], a["R"], a["causal"], a["dtype"],
+                                   a["phi_dtype"], a["bcast"], a["scale"], None)
+
+
+def test_forward_argument_errors(lib):
+    # fake non-null addresses: every case below must be rejected before any device access
+    assert _fwd(lib, q=None) == 1
+    assert _fwd(lib, phi_k=None) == 1
+    assert _fwd(lib, N=0) == 2
+    assert _fwd(lib, R=-1) == 2
+    assert _fwd(lib, B=1 << 20, H=1 << 10, N=1 << 12) == 2          # index overflow
+    assert _fwd(lib, C=48) == 3
+    assert _fwd(lib, R=65) == 3                                      # padded width > 64
+    assert _fwd(lib, R=11, phi_dtype=api.FB_F32) == 3                # 6 R > 64 columns
+    assert _fwd(lib, dtype=api.FB_F32, phi_dtype=api.FB_BF16) == 3
+    assert _fwd(lib, dtype=7) == 3
+    assert _fwd(lib, k=72) == 4                                      # misaligned
+
+
+def test_dense_and_backward_argument_errors(lib):
+    f = lib.fb_dense_bias_attn_fwd
+    assert f(64, 64, 64, None, 64, 64, 1, 1, 16, 64, 0, api.FB_BF16, 0, 0.0, None) == 1
+    assert f(64, 64, 64, 64, 64, 64, 1, 1, 16, 96, 0, api.FB_BF16, 0, 0.0, None) == 3
+    assert f(64, 64, 64, 68, 64, 64, 1, 1, 16, 64, 0, api.FB_BF16, 0, 0.0, None) == 4
+    ws = lib.fb_lowrank_attn_bwd_workspace_bytes(2, 3, 100, 64, 8, api.FB_BF16)
+    assert ws == 2 * 3 * 100 * 4
+    assert lib.fb_lowrank_attn_bwd_workspace_bytes(0, 3, 100, 64, 8, api.FB_BF16) == 0
+    g = lib.fb_lowrank_attn_bwd
+    ptrs = [64] * 13
+
+    def bwd(ptrs=ptrs, B=2, H=3, N=100, C=64, R=8, dtype=api.FB_BF16, phi=api.FB_BF16, w=64, wb=ws):
+        return g(*ptrs, B, H, N, C, R, 0, dtype, phi, 0, 0.0, w, wb, None)
+
+    assert bwd(ptrs=[None] + [64] * 12) == 1
+    assert bwd(dtype=api.FB_F32) == 3
+    assert bwd(R=40) == 3                      # padded width > 32 in the backward
+    assert bwd(w=None) == 5
+    assert bwd(wb=ws - 1) == 5
+    assert bwd(w=72) == 4
+
+
+def test_tune_knob(lib):
+    assert lib.fb_tune_set(b"fwd_qb", 2) == 0
+    assert lib.fb_tune_set(b"fwd_qb", 0) == 0
+    assert lib.fb_tune_set(b"fwd_qb", 3) == 2
+    assert lib.fb_tune_set(b"nope", 1) == 3
+    assert lib.fb_tune_set(None, 1) == 1
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(api.FlashBiasError):
+        api.load_library(str(tmp_path / "libflashbias.so"))
