@@ -1,21 +1,31 @@
 // bf16 MFMA forward for attention with an additive bias, gfx950.
 //
 //   low-rank mode: scores = [q*scale | phi_q | 0] . [k | phi_k | 0]   (FlashBias Eq. 3)
-//   dense mode   : scores = (q*scale) . k + bias tile streamed from HBM  (the baseline of
+//   dense mode   : scores = (q*scale) . k + bias block read from HBM  (the baseline of
 //                  Example 3.9)
 //
 // Work split.  One workgroup = 4 waves = BQ = 128*QB query rows of one (b, h); it walks the
-// key/value sequence in tiles of BK keys staged in LDS (register-prefetched one tile ahead,
-// two LDS buffers, one barrier per tile).  Each wave owns 32*QB query rows.
+// key/value sequence in blocks of 32 keys.  Each wave owns 32*QB query rows.
 //
 // Orientation.  Every contraction is computed transposed so that a query is a LANE and the
 // keys (or output channels) of a 32-wide block sit in that lane's accumulator registers:
-//   S^T[key][query]   = sum_c  Kt[key][c]   * Qreg[query][c]      (A = K tile from LDS)
+//   S^T[key][query]   = sum_c  Kt[key][c]   * Qreg[query][c]      (A = K block from LDS)
 //   O^T[chan][query] += sum_key V^T[chan][key] * P^T[key][query]   (A = V via LDS transpose read)
 // The query operand is loop-invariant and stays in registers; the softmax row maximum and
 // sum are per-lane reductions over registers plus ONE exchange with the lane 32 away; the
 // exponentiated scores are already in the B-operand layout of the second MFMA, so P never
 // touches LDS; and rescaling O by a per-query factor is a per-lane multiply.
+//
+// Pipeline (per wave, one 32-key block per iteration t, LDS ring of three blocks):
+//   S  = MFMA chain over K operands of block t          (read from LDS during iteration t-1)
+//   regs -> LDS: block t+2   |  global -> regs: block t+3
+//   issue LDS transpose reads of V block t              (latency hidden by the softmax)
+//   softmax(S) -> P
+//   issue LDS reads of K operands of block t+1          (latency hidden by the next chain)
+//   O += MFMA chain over V operands and P
+//   barrier
+// so neither MFMA chain waits on an LDS round trip, and with two workgroups per CU (two
+// waves per SIMD, <= 256 registers each) one wave's softmax overlaps the other's MFMAs.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -28,39 +38,35 @@ namespace {
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
+constexpr int BK = 32;       // keys per block
+constexpr int NBUF = 3;      // LDS ring depth
 // The running reference maximum of a row is only raised when the true maximum exceeds it by
 // more than this (log2 units); until then probabilities are at most 2^tau, which fp32 sums
 // and bf16 P (same exponent range) hold without loss.  The final o = O / l is unaffected.
 constexpr float kRescaleTau = 8.0f;
 
-template <int C, int RP, int QB, int BK, bool DENSE>
+template <int C, int RP, int QB>
 struct Cfg {
     static constexpr int KS = (C + RP) / 16;          // MFMA k-steps of the score contraction
-    static constexpr int KP = C + RP + 8;             // K-tile row pitch (elements): 16 B pad
-    static constexpr int VP = (C == 32) ? 32 : C + 32;  // V-tile row pitch: odd multiple of 64 B
+    static constexpr int KP = C + RP + 8;             // K-block row pitch (elements): 16 B pad
+    static constexpr int VP = (C == 32) ? 32 : C + 32;  // V-block row pitch: odd multiple of 64 B
     static constexpr int BQ = kWaves * QB * 32;
-    static constexpr int KB = BK / 32;                // 32-key blocks per tile
-    static constexpr int KCH = BK * C / 8;            // 16-byte chunks of the K (or V) part of a tile
+    static constexpr int KCH = BK * C / 8;            // 16-byte chunks of the K (or V) part of a block
     static constexpr int KIT = (KCH + kThreads - 1) / kThreads;   // per-thread chunks
     static constexpr int PCH = BK * RP / 8;           // chunks of the factor part
     static constexpr int PIT = (PCH + kThreads - 1) / kThreads;
-    static constexpr int BP = BK + 4;                 // dense: bias tile row pitch (elements)
-    static constexpr int BROWS = QB * 32;             // dense: bias rows per wave
-    static constexpr int BIT = BROWS * (BK / 8) / 64;  // dense: per-lane 16-byte chunks
-    static constexpr size_t kLds =
-        (size_t)2 * BK * (KP + VP) * 2 + (DENSE ? (size_t)kWaves * BROWS * BP * 2 : 0);
-    static_assert(BK % 32 == 0 && (C % 32) == 0 && (RP % 16) == 0, "shape granularity");
+    static constexpr int KBLK = BK * KP;              // elements per K block buffer
+    static constexpr int VBLK = BK * VP;
+    static constexpr size_t kLds = (size_t)NBUF * (KBLK + VBLK) * 2;
+    static_assert((C % 32) == 0 && (RP % 16) == 0, "shape granularity");
 };
 
-// Two workgroups per CU (two waves per SIMD, at most 256 registers each): while one wave
-// waits on the matrix pipe the other runs its softmax on the vector pipe.
-template <int C, int RP, int QB, int BK, bool CAUSAL, bool DENSE>
+template <int C, int RP, int QB, bool CAUSAL, bool DENSE>
 __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
-    using K = Cfg<C, RP, QB, BK, DENSE>;
+    using K = Cfg<C, RP, QB>;
     extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t* const kt = (bf16_t*)smem;                 // [2][BK][KP]
-    bf16_t* const vt = kt + 2 * BK * K::KP;           // [2][BK][VP]
-    bf16_t* const bt = vt + 2 * BK * K::VP;           // dense: [waves][BROWS][BP]
+    bf16_t* const kt = (bf16_t*)smem;                 // [NBUF][BK][KP]
+    bf16_t* const vt = kt + NBUF * K::KBLK;           // [NBUF][BK][VP]
 
     // ---- which tile: contiguous runs of tiles per XCD (workgroup w lands on XCD w % 8), so the
     // workgroups sharing one head's K/V also share one L2; causal tiles go heaviest first.
@@ -130,14 +136,12 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     const int kend = CAUSAL ? min(N, q0 + K::BQ) : N;
     const int nT = (kend + BK - 1) / BK;
 
-    // ---- tile staging: global -> registers -> LDS.  Rows past N are clamped to row N-1; the
+    // ---- block staging: global -> registers -> LDS.  Rows past N are clamped to row N-1; the
     // keys they stand for are masked to -inf before the softmax, so their values never count.
     u32x4 kraw[K::KIT], vraw[K::KIT];
     u32x4 praw[K::PIT > 0 ? K::PIT : 1];
-    u32x4 braw[DENSE ? K::BIT : 1];
-    const bool bias_fast = DENSE && ((N & 7) == 0);
 
-    auto load_tile = [&](int t) {
+    auto load_block = [&](int t) {
         const int k0 = t * BK;
 #pragma unroll
         for (int it = 0; it < K::KIT; it++) {
@@ -160,34 +164,11 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
                 }
             }
         }
-        if (DENSE) {
-#pragma unroll
-            for (int it = 0; it < K::BIT; it++) {
-                const int e = lane + it * 64;
-                const int row = e / (BK / 8), c8 = e % (BK / 8);
-                const int qi = qw0 + row;
-                const int j = k0 + c8 * 8;
-                u32x4 a = u32x4{0u, 0u, 0u, 0u};
-                // chunks wholly above the diagonal are never read when causal
-                if (qi < N && j < N && !(CAUSAL && j > qi)) {
-                    const bf16_t* src = bg + (size_t)qi * N + j;
-                    if (bias_fast) {
-                        a = *(const u32x4*)src;
-                    } else {
-                        bf16x8 tmp;
-#pragma unroll
-                        for (int x = 0; x < 8; x++) tmp[x] = (j + x < N) ? src[x] : (bf16_t)0.f;
-                        a = as_uint4(tmp);
-                    }
-                }
-                braw[it] = a;
-            }
-        }
     };
 
-    auto store_tile = [&](int buf) {
-        bf16_t* kdst = kt + buf * BK * K::KP;
-        bf16_t* vdst = vt + buf * BK * K::VP;
+    auto store_block = [&](int buf) {
+        bf16_t* kdst = kt + buf * K::KBLK;
+        bf16_t* vdst = vt + buf * K::VBLK;
 #pragma unroll
         for (int it = 0; it < K::KIT; it++) {
             const int e = tid + it * kThreads;
@@ -208,19 +189,41 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
                 }
             }
         }
-        if (DENSE) {
-            bf16_t* bdst = bt + wave * K::BROWS * K::BP;
+    };
+
+    // dense mode: this lane's bias values for block t, already in accumulator order: row
+    // qi, keys 8*g + 4*hf + 0..3 (8 bytes per g).  Chunks wholly above the diagonal or past
+    // the end are not read.
+    u32x2 braw[DENSE ? QB : 1][4];
+    const bool bias_fast = DENSE && ((N & 3) == 0);
+    auto load_bias = [&](int t) {
+        if (!DENSE) return;
+        const int k0 = t * BK;
 #pragma unroll
-            for (int it = 0; it < K::BIT; it++) {
-                const int e = lane + it * 64;
-                const int row = e / (BK / 8), c8 = e % (BK / 8);
-                u32x2* d = (u32x2*)(bdst + row * K::BP + c8 * 8);   // 8-byte aligned rows
-                d[0] = u32x2{braw[it].x, braw[it].y};
-                d[1] = u32x2{braw[it].z, braw[it].w};
+        for (int qb = 0; qb < QB; qb++) {
+            const int qi = qw0 + qb * 32 + l32;
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                const int j = k0 + 8 * g + 4 * hf;
+                u32x2 a = u32x2{0u, 0u};
+                if (qi < N && j < N && !(CAUSAL && j > qi)) {
+                    const bf16_t* src = bg + (size_t)qi * N + j;
+                    if (bias_fast) {
+                        a = *(const u32x2*)src;
+                    } else {
+                        bf16x4 tmp;
+#pragma unroll
+                        for (int x = 0; x < 4; x++) tmp[x] = (j + x < N) ? src[x] : (bf16_t)0.f;
+                        a = __builtin_bit_cast(u32x2, tmp);
+                    }
+                }
+                braw[qb][g] = a;
             }
         }
     };
 
+    // ---- LDS operand reads ----
+    const int krow_off = l32 * K::KP + 8 * hf;
     // lane -> (row group, column group) of the LDS transpose read: the 16-lane group
     // blk = l32 / 16 covers channels 16*blk..+15, lane i = lane % 16 supplies row i/4, columns
     // 4*(i%4)..+3; the half hf selects keys 4*hf..4*hf+3 (+8 for the high part), matching the
@@ -228,46 +231,88 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     const int i16 = lane & 15, blk = l32 >> 4;
     const int vlane_off = (4 * hf + (i16 >> 2)) * K::VP + 16 * blk + 4 * (i16 & 3);
 
-    // One 32-key block against this wave's query blocks.  MASKED instances apply the causal
-    // and sequence-end masks; interior blocks skip that code entirely.
-    auto block = [&](const bf16_t* ksrc, const bf16_t* vsrc, int kb, int kb0, auto masked_tag) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
+    bf16x8 ka[K::KS];
+    auto read_k = [&](int buf) {
+        const bf16_t* krow = kt + buf * K::KBLK + krow_off;
+#pragma unroll
+        for (int ks = 0; ks < K::KS; ks++) ka[ks] = as_bf16x8(*(const u32x4*)(krow + ks * 16));
+    };
+
+    // ---- prologue: blocks 0 and 1 into LDS, block 2 in flight, K operands of block 0 ----
+    load_block(0);
+    store_block(0);
+    load_block(1);
+    store_block(1);
+    load_block(2);
+    load_bias(0);
+    __syncthreads();
+    read_k(0);
+
+    int buf = 0;                 // t % NBUF
+    for (int t = 0; t < nT; t++) {
+        const int kb0 = t * BK;
+        const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;       // (t+1) % NBUF
+        const int buf2 = buf1 == NBUF - 1 ? 0 : buf1 + 1;     // (t+2) % NBUF
+        // wave-uniform: is this block wholly invisible to this wave (causal), or does it need masks?
+        const bool skip = CAUSAL && kb0 > qw0 + QB * 32 - 1;
+        const bool masked = (kb0 + BK > N) || (CAUSAL && kb0 + BK - 1 > qw0);
+
         // ---- S^T = Kt . Qreg ----
         f32x16 s[QB];
 #pragma unroll
-        for (int qb = 0; qb < QB; qb++)
+        for (int qb = 0; qb < QB; qb++) {
+            if (DENSE) {
 #pragma unroll
-            for (int r = 0; r < 16; r++) s[qb][r] = 0.f;
-        const bf16_t* krow = ksrc + (kb * 32 + l32) * K::KP + 8 * hf;
+                for (int g = 0; g < 4; g++) {
+                    const bf16x4 bv = __builtin_bit_cast(bf16x4, braw[qb][g]);
 #pragma unroll
-        for (int ks = 0; ks < K::KS; ks++) {
-            const bf16x8 a = as_bf16x8(*(const u32x4*)(krow + ks * 16));
+                    for (int x = 0; x < 4; x++) s[qb][4 * g + x] = (float)bv[x];
+                }
+            } else {
 #pragma unroll
-            for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(a, qreg[qb][ks], s[qb]);
+                for (int r = 0; r < 16; r++) s[qb][r] = 0.f;
+            }
         }
+        if (!skip) {
+#pragma unroll
+            for (int ks = 0; ks < K::KS; ks++)
+#pragma unroll
+                for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(ka[ks], qreg[qb][ks], s[qb]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 
+        // ---- staging: block t+2 registers -> LDS, block t+3 global -> registers ----
+        store_block(buf2);
+        load_block(t + 3);
+        load_bias(t + 1);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- issue the V operand reads now; they land while the softmax runs ----
+        bf16x8 va[C / 32][2];
+        {
+            const bf16_t* vbase = vt + buf * K::VBLK + vlane_off;
+#pragma unroll
+            for (int cb = 0; cb < C / 32; cb++)
+#pragma unroll
+                for (int kk = 0; kk < 2; kk++) {
+                    const bf16_t* vp = vbase + (kk * 16) * K::VP + cb * 32;
+                    va[cb][kk] = join_tr(lds_read_tr16(vp), lds_read_tr16(vp + 8 * K::VP));
+                }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- online softmax: a row lives in this lane and the one 32 away ----
         bf16x8 pb[QB][2];
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) {
-            const int qi = qw0 + qb * 32 + l32;
-            if (DENSE) {
-                const bf16_t* brow = bt + (wave * K::BROWS + qb * 32 + l32) * K::BP + kb * 32 + 4 * hf;
-#pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    const u32x2 u = *(const u32x2*)(brow + 8 * g);
-                    const bf16x4 bv = __builtin_bit_cast(bf16x4, u);
-#pragma unroll
-                    for (int x = 0; x < 4; x++) s[qb][4 * g + x] += (float)bv[x];
-                }
-            }
-            if (MASKED) {
+            if (masked) {
+                const int qi = qw0 + qb * 32 + l32;
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int key = kb0 + 8 * (r / 4) + 4 * hf + (r % 4);
                     if (key >= N || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
                 }
             }
-            // ---- online softmax: the row lives in this lane and the one 32 away ----
             float mx = fmaxf(s[qb][0], s[qb][1]);
 #pragma unroll
             for (int r = 2; r < 16; r++) mx = fmaxf(mx, s[qb][r]);
@@ -292,51 +337,23 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
             }
             lsum[qb] += ps;
         }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- K operands of the next block: in flight during the O chain ----
+        read_k(buf1);
+        __builtin_amdgcn_sched_barrier(0);
 
         // ---- O^T += V^T . P^T ----
-        const bf16_t* vbase = vsrc + (kb * 32) * K::VP + vlane_off;
+        if (!skip) {
 #pragma unroll
-        for (int cb = 0; cb < C / 32; cb++) {
+            for (int cb = 0; cb < C / 32; cb++)
 #pragma unroll
-            for (int kk = 0; kk < 2; kk++) {
-                const bf16_t* vp = vbase + (kk * 16) * K::VP + cb * 32;
-                const bf16x8 a = join_tr(lds_read_tr16(vp), lds_read_tr16(vp + 8 * K::VP));
+                for (int kk = 0; kk < 2; kk++)
 #pragma unroll
-                for (int qb = 0; qb < QB; qb++) oacc[qb][cb] = mfma32(a, pb[qb][kk], oacc[qb][cb]);
-            }
+                    for (int qb = 0; qb < QB; qb++) oacc[qb][cb] = mfma32(va[cb][kk], pb[qb][kk], oacc[qb][cb]);
         }
-    };
-
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (int t = 0; t < nT; t++) {
-        const bool more = t + 1 < nT;
-        if (more) load_tile(t + 1);
-
-        const bf16_t* ksrc = kt + (t & 1) * BK * K::KP;
-        const bf16_t* vsrc = vt + (t & 1) * BK * K::VP;
-        const int k0 = t * BK;
-        // wave-uniform: does any key of this tile need masking for any of this wave's rows?
-        const bool tile_masked = (k0 + BK > N) || (CAUSAL && k0 + BK - 1 > qw0);
-        if (!tile_masked) {
-#pragma unroll
-            for (int kb = 0; kb < K::KB; kb++)
-                block(ksrc, vsrc, kb, k0 + kb * 32, std::false_type{});
-        } else {
-#pragma unroll
-            for (int kb = 0; kb < K::KB; kb++) {
-                const int kb0 = k0 + kb * 32;
-                // nothing visible: every row of this wave precedes the block (wave-uniform)
-                if (CAUSAL && kb0 > qw0 + QB * 32 - 1) continue;
-                if (kb0 >= N) continue;
-                block(ksrc, vsrc, kb, kb0, std::true_type{});
-            }
-        }
-
-        if (more) store_tile((t + 1) & 1);
         __syncthreads();
+        buf = buf1;
     }
 
     // ---- epilogue: o = O / l, lse = m + ln l ----
@@ -362,10 +379,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     }
 }
 
-template <int C, int RP, int QB, int BK, bool CAUSAL, bool DENSE>
+template <int C, int RP, int QB, bool CAUSAL, bool DENSE>
 int launch(const FwdParams& pin, hipStream_t stream) {
-    using K = Cfg<C, RP, QB, BK, DENSE>;
-    auto kern = fwd_bf16_kernel<C, RP, QB, BK, CAUSAL, DENSE>;
+    using K = Cfg<C, RP, QB>;
+    auto kern = fwd_bf16_kernel<C, RP, QB, CAUSAL, DENSE>;
     static bool attr_done = false;   // benign race: the call is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -381,22 +398,17 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
-// Keys per LDS tile: 64 when two workgroups (two tile pairs) still fit one CU's 160 KB LDS.
-template <int C, int RP, int QB, bool DENSE>
-constexpr int pick_bk() {
-    return Cfg<C, RP, QB, 64, DENSE>::kLds <= 80 * 1024 ? 64 : 32;
-}
-
 template <int C, int RP, int QB, bool DENSE>
 int dispatch_causal(const FwdParams& p, hipStream_t stream) {
-    constexpr int BK = pick_bk<C, RP, QB, DENSE>();
-    if (p.causal) return launch<C, RP, QB, BK, true, DENSE>(p, stream);
-    return launch<C, RP, QB, BK, false, DENSE>(p, stream);
+    if (p.causal) return launch<C, RP, QB, true, DENSE>(p, stream);
+    return launch<C, RP, QB, false, DENSE>(p, stream);
 }
 
 template <int C, int RP, bool DENSE>
 int dispatch_qb(const FwdParams& p, int qb, hipStream_t stream) {
-    if (qb == 2) return dispatch_causal<C, RP, 2, DENSE>(p, stream);
+    if constexpr (C <= 64) {
+        if (qb == 2) return dispatch_causal<C, RP, 2, DENSE>(p, stream);
+    }
     return dispatch_causal<C, RP, 1, DENSE>(p, stream);
 }
 
@@ -415,7 +427,8 @@ int dispatch_rp(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stre
 
 }  // namespace
 
-// rp: padded factor width (multiple of 16, <= 64); qb: 32-row query blocks per wave (1 or 2).
+// rp: padded factor width (multiple of 16, <= 64); qb: 32-row query blocks per wave (1 or 2;
+// 2 exists for C <= 64 only and falls back to 1 otherwise).
 // Returns 0 on success, 1 on launch failure, -1 when no instantiation fits.
 int fb_launch_fwd_bf16(const FwdParams& p, int C, int rp, bool dense, int qb, hipStream_t stream) {
     switch (C) {
