@@ -66,8 +66,9 @@ const char* fb_status_string(int status);
 
 /*
  * Process-wide tuning knob for experiments (benchmarks sweep it; results never depend on
- * it).  name = "fwd_qb": 32-row query blocks per wave in the bf16 forward kernels, 1 or 2
- * (0 restores the automatic choice).  Returns FB_OK, FB_ERR_NULL, FB_ERR_SHAPE (value out
+ * it).  name = "fwd_qb": bf16 forward kernel variant: 1 or 2 = four-wave kernel with that many
+ * 32-row query blocks per wave, 8 = eight-wave ping-pong kernel (0 restores the automatic
+ * choice).  Returns FB_OK, FB_ERR_NULL, FB_ERR_SHAPE (value out
  * of range) or FB_ERR_UNSUPPORTED (unknown name).  Not synchronised with concurrent calls.
  */
 int fb_tune_set(const char* name, int value);

@@ -11,7 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflashbias.so")
 
-SOURCES = ["fb_api.hip", "fb_fwd_f32.hip", "fb_fwd_bf16.hip", "fb_bwd_bf16.hip"]
+SOURCES = ["fb_api.hip", "fb_fwd_f32.hip", "fb_fwd_bf16.hip", "fb_fwd_bf16_c32.hip",
+           "fb_fwd_bf16_c64.hip", "fb_fwd_bf16_c128.hip", "fb_bwd_bf16.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffast-math", "-fno-finite-math-only",
@@ -35,7 +36,8 @@ def _compile(src: str, force: bool) -> str:
     deps.append(os.path.join(HERE, "..", "include", "flashbias.h"))
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    cmd = [_hipcc(), *FLAGS, "-c", srcp, "-o", obj]
+    extra = os.environ.get("FB_EXTRA_FLAGS", "").split()
+    cmd = [_hipcc(), *FLAGS, *extra, "-c", srcp, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
@@ -47,7 +49,7 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
-def build(force: bool = True, jobs: int = 4) -> str:
+def build(force: bool = True, jobs: int = 7) -> str:
     """Compile every kernel source and link the shared library.  force=False reuses objects
     that are newer than all sources and headers."""
     os.makedirs(OBJ, exist_ok=True)

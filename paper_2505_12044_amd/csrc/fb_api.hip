@@ -31,7 +31,7 @@ int check_common(int B, int H, int N, int C, int R) {
 
 int pick_qb(int B, int H, int N, int C, int rp, bool dense) {
     const int forced = g_fwd_qb.load(std::memory_order_relaxed);
-    if (forced == 1 || forced == 2) return forced;
+    if (forced == 1 || forced == 2 || forced == 8) return forced;
     (void)rp;
     // Two query blocks per wave halve the LDS traffic per MFMA but double the accumulator
     // registers: they fit the 256-register budget (two waves per SIMD) only for C <= 64, and
@@ -64,7 +64,7 @@ const char* fb_status_string(int status) {
 int fb_tune_set(const char* name, int value) {
     if (name == nullptr) return FB_ERR_NULL;
     if (std::strcmp(name, "fwd_qb") == 0) {
-        if (value < 0 || value > 2) return FB_ERR_SHAPE;
+        if (value != 0 && value != 1 && value != 2 && value != 8) return FB_ERR_SHAPE;
         g_fwd_qb.store(value, std::memory_order_relaxed);
         return FB_OK;
     }

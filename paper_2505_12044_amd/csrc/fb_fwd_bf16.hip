@@ -1,440 +1,16 @@
-// bf16 MFMA forward for attention with an additive bias, gfx950.
-//
-//   low-rank mode: scores = [q*scale | phi_q | 0] . [k | phi_k | 0]   (FlashBias Eq. 3)
-//   dense mode   : scores = (q*scale) . k + bias block read from HBM  (the baseline of
-//                  Example 3.9)
-//
-// Work split.  One workgroup = 4 waves = BQ = 128*QB query rows of one (b, h); it walks the
-// key/value sequence in blocks of 32 keys.  Each wave owns 32*QB query rows.
-//
-// Orientation.  Every contraction is computed transposed so that a query is a LANE and the
-// keys (or output channels) of a 32-wide block sit in that lane's accumulator registers:
-//   S^T[key][query]   = sum_c  Kt[key][c]   * Qreg[query][c]      (A = K block from LDS)
-//   O^T[chan][query] += sum_key V^T[chan][key] * P^T[key][query]   (A = V via LDS transpose read)
-// The query operand is loop-invariant and stays in registers; the softmax row maximum and
-// sum are per-lane reductions over registers plus ONE exchange with the lane 32 away; the
-// exponentiated scores are already in the B-operand layout of the second MFMA, so P never
-// touches LDS; and rescaling O by a per-query factor is a per-lane multiply.
-//
-// Pipeline (per wave, one 32-key block per iteration t, LDS ring of three blocks):
-//   S  = MFMA chain over K operands of block t          (read from LDS during iteration t-1)
-//   regs -> LDS: block t+2   |  global -> regs: block t+3
-//   issue LDS transpose reads of V block t              (latency hidden by the softmax)
-//   softmax(S) -> P
-//   issue LDS reads of K operands of block t+1          (latency hidden by the next chain)
-//   O += MFMA chain over V operands and P
-//   barrier
-// so neither MFMA chain waits on an LDS round trip, and with two workgroups per CU (two
-// waves per SIMD, <= 256 registers each) one wave's softmax overlaps the other's MFMAs.
-#include <hip/hip_runtime.h>
-
-#include <type_traits>
-
-#include "fb_device.h"
+// Head-dimension switch of the bf16 forward; the kernels live in fb_fwd_bf16_impl.h and are
+// instantiated per C in fb_fwd_bf16_c{32,64,128}.hip.
 #include "fb_launch.h"
-#include "fb_params.h"
 
-namespace {
+int fb_launch_fwd_bf16_c32(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream);
+int fb_launch_fwd_bf16_c64(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream);
+int fb_launch_fwd_bf16_c128(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream);
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
-constexpr int BK = 32;       // keys per block
-constexpr int NBUF = 3;      // LDS ring depth
-// The running reference maximum of a row is only raised when the true maximum exceeds it by
-// more than this (log2 units); until then probabilities are at most 2^tau, which fp32 sums
-// and bf16 P (same exponent range) hold without loss.  The final o = O / l is unaffected.
-constexpr float kRescaleTau = 8.0f;
-
-template <int C, int RP, int QB>
-struct Cfg {
-    static constexpr int KS = (C + RP) / 16;          // MFMA k-steps of the score contraction
-    static constexpr int KP = C + RP + 8;             // K-block row pitch (elements): 16 B pad
-    static constexpr int VP = (C == 32) ? 32 : C + 32;  // V-block row pitch: odd multiple of 64 B
-    static constexpr int BQ = kWaves * QB * 32;
-    static constexpr int KCH = BK * C / 8;            // 16-byte chunks of the K (or V) part of a block
-    static constexpr int KIT = (KCH + kThreads - 1) / kThreads;   // per-thread chunks
-    static constexpr int PCH = BK * RP / 8;           // chunks of the factor part
-    static constexpr int PIT = (PCH + kThreads - 1) / kThreads;
-    static constexpr int KBLK = BK * KP;              // elements per K block buffer
-    static constexpr int VBLK = BK * VP;
-    static constexpr size_t kLds = (size_t)NBUF * (KBLK + VBLK) * 2;
-    static_assert((C % 32) == 0 && (RP % 16) == 0, "shape granularity");
-};
-
-template <int C, int RP, int QB, bool CAUSAL, bool DENSE>
-__global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
-    using K = Cfg<C, RP, QB>;
-    extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t* const kt = (bf16_t*)smem;                 // [NBUF][BK][KP]
-    bf16_t* const vt = kt + NBUF * K::KBLK;           // [NBUF][BK][VP]
-
-    // ---- which tile: contiguous runs of tiles per XCD (workgroup w lands on XCD w % 8), so the
-    // workgroups sharing one head's K/V also share one L2; causal tiles go heaviest first.
-    const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
-    if (L >= p.total_tiles) return;
-    const int bh = L / p.n_qtiles;
-    int qt = L - bh * p.n_qtiles;
-    if (CAUSAL) qt = p.n_qtiles - 1 - qt;
-    const int b = bh / p.H, h = bh - b * p.H;
-    const int N = p.N, R = p.R;
-    const bool phi_f32 = p.phi_f32 != 0;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hf = lane >> 5;
-    const int q0 = qt * K::BQ;
-    const int qw0 = q0 + wave * (QB * 32);
-
-    const size_t base = (size_t)bh * N * C;
-    const bf16_t* qg = (const bf16_t*)p.q + base;
-    const bf16_t* kg = (const bf16_t*)p.k + base;
-    const bf16_t* vg = (const bf16_t*)p.v + base;
-    const size_t phi_esz = phi_f32 ? 4 : 2;
-    const unsigned char* pqg = nullptr;
-    const unsigned char* pkg = nullptr;
-    if (RP > 0) {
-        const size_t pbase = ((size_t)b * p.phi_bstride + (size_t)h * N * R) * phi_esz;
-        pqg = (const unsigned char*)p.phi_q + pbase;
-        pkg = (const unsigned char*)p.phi_k + pbase;
-    }
-    const bf16_t* bg = nullptr;
-    if (DENSE) bg = (const bf16_t*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * N;
-
-    // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout).  Rows past N
-    // read row N-1 (finite values) and are never stored.
-    bf16x8 qreg[QB][K::KS];
-#pragma unroll
-    for (int qb = 0; qb < QB; qb++) {
-        const int qi = min(qw0 + qb * 32 + l32, N - 1);
-#pragma unroll
-        for (int ks = 0; ks < K::KS; ks++) {
-            bf16x8 val;
-            if (ks < C / 16) {
-                const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qi * C + ks * 16 + 8 * hf));
-#pragma unroll
-                for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
-            } else {
-                const int c8 = (ks - C / 16) * 2 + hf;
-                val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
-            }
-            qreg[qb][ks] = val;
-        }
-    }
-
-    f32x16 oacc[QB][C / 32];
-    float mref[QB], lsum[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; qb++) {
-        mref[qb] = -INFINITY;
-        lsum[qb] = 0.f;
-#pragma unroll
-        for (int cb = 0; cb < C / 32; cb++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) oacc[qb][cb][r] = 0.f;
-    }
-
-    const int kend = CAUSAL ? min(N, q0 + K::BQ) : N;
-    const int nT = (kend + BK - 1) / BK;
-
-    // ---- block staging: global -> registers -> LDS.  Rows past N are clamped to row N-1; the
-    // keys they stand for are masked to -inf before the softmax, so their values never count.
-    u32x4 kraw[K::KIT], vraw[K::KIT];
-    u32x4 praw[K::PIT > 0 ? K::PIT : 1];
-
-    auto load_block = [&](int t) {
-        const int k0 = t * BK;
-#pragma unroll
-        for (int it = 0; it < K::KIT; it++) {
-            const int e = tid + it * kThreads;
-            if (K::KCH % kThreads == 0 || e < K::KCH) {
-                const int row = e / (C / 8), c8 = e % (C / 8);
-                const int j = min(k0 + row, N - 1);
-                kraw[it] = *(const u32x4*)(kg + (size_t)j * C + c8 * 8);
-                vraw[it] = *(const u32x4*)(vg + (size_t)j * C + c8 * 8);
-            }
-        }
-        if (RP > 0) {
-#pragma unroll
-            for (int it = 0; it < K::PIT; it++) {
-                const int e = tid + it * kThreads;
-                if (K::PCH % kThreads == 0 || e < K::PCH) {
-                    const int row = e / (RP / 8), c8 = e % (RP / 8);
-                    const int j = min(k0 + row, N - 1);
-                    praw[it] = phi_chunk_raw(pkg + (size_t)j * R * phi_esz, c8, R, phi_f32, true);
-                }
-            }
-        }
-    };
-
-    auto store_block = [&](int buf) {
-        bf16_t* kdst = kt + buf * K::KBLK;
-        bf16_t* vdst = vt + buf * K::VBLK;
-#pragma unroll
-        for (int it = 0; it < K::KIT; it++) {
-            const int e = tid + it * kThreads;
-            if (K::KCH % kThreads == 0 || e < K::KCH) {
-                const int row = e / (C / 8), c8 = e % (C / 8);
-                *(u32x4*)(kdst + row * K::KP + c8 * 8) = kraw[it];
-                *(u32x4*)(vdst + row * K::VP + c8 * 8) = vraw[it];
-            }
-        }
-        if (RP > 0) {
-#pragma unroll
-            for (int it = 0; it < K::PIT; it++) {
-                const int e = tid + it * kThreads;
-                if (K::PCH % kThreads == 0 || e < K::PCH) {
-                    const int row = e / (RP / 8), c8 = e % (RP / 8);
-                    *(u32x4*)(kdst + row * K::KP + C + c8 * 8) =
-                        as_uint4(phi_chunk_finish<false>(praw[it], c8, phi_f32));
-                }
-            }
-        }
-    };
-
-    // dense mode: this lane's bias values for block t, already in accumulator order: row
-    // qi, keys 8*g + 4*hf + 0..3 (8 bytes per g).  Chunks wholly above the diagonal or past
-    // the end are not read.
-    u32x2 braw[DENSE ? QB : 1][4];
-    const bool bias_fast = DENSE && ((N & 3) == 0);
-    auto load_bias = [&](int t) {
-        if (!DENSE) return;
-        const int k0 = t * BK;
-#pragma unroll
-        for (int qb = 0; qb < QB; qb++) {
-            const int qi = qw0 + qb * 32 + l32;
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const int j = k0 + 8 * g + 4 * hf;
-                u32x2 a = u32x2{0u, 0u};
-                if (qi < N && j < N && !(CAUSAL && j > qi)) {
-                    const bf16_t* src = bg + (size_t)qi * N + j;
-                    if (bias_fast) {
-                        a = *(const u32x2*)src;
-                    } else {
-                        bf16x4 tmp;
-#pragma unroll
-                        for (int x = 0; x < 4; x++) tmp[x] = (j + x < N) ? src[x] : (bf16_t)0.f;
-                        a = __builtin_bit_cast(u32x2, tmp);
-                    }
-                }
-                braw[qb][g] = a;
-            }
-        }
-    };
-
-    // ---- LDS operand reads ----
-    const int krow_off = l32 * K::KP + 8 * hf;
-    // lane -> (row group, column group) of the LDS transpose read: the 16-lane group
-    // blk = l32 / 16 covers channels 16*blk..+15, lane i = lane % 16 supplies row i/4, columns
-    // 4*(i%4)..+3; the half hf selects keys 4*hf..4*hf+3 (+8 for the high part), matching the
-    // keys of accumulator registers 0..3 / 4..7 of each 16-key group.
-    const int i16 = lane & 15, blk = l32 >> 4;
-    const int vlane_off = (4 * hf + (i16 >> 2)) * K::VP + 16 * blk + 4 * (i16 & 3);
-
-    bf16x8 ka[K::KS];
-    auto read_k = [&](int buf) {
-        const bf16_t* krow = kt + buf * K::KBLK + krow_off;
-#pragma unroll
-        for (int ks = 0; ks < K::KS; ks++) ka[ks] = as_bf16x8(*(const u32x4*)(krow + ks * 16));
-    };
-
-    // ---- prologue: blocks 0 and 1 into LDS, block 2 in flight, K operands of block 0 ----
-    load_block(0);
-    store_block(0);
-    load_block(1);
-    store_block(1);
-    load_block(2);
-    load_bias(0);
-    __syncthreads();
-    read_k(0);
-
-    int buf = 0;                 // t % NBUF
-    for (int t = 0; t < nT; t++) {
-        const int kb0 = t * BK;
-        const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;       // (t+1) % NBUF
-        const int buf2 = buf1 == NBUF - 1 ? 0 : buf1 + 1;     // (t+2) % NBUF
-        // wave-uniform: is this block wholly invisible to this wave (causal), or does it need masks?
-        const bool skip = CAUSAL && kb0 > qw0 + QB * 32 - 1;
-        const bool masked = (kb0 + BK > N) || (CAUSAL && kb0 + BK - 1 > qw0);
-
-        // ---- S^T = Kt . Qreg ----
-        f32x16 s[QB];
-#pragma unroll
-        for (int qb = 0; qb < QB; qb++) {
-            if (DENSE) {
-#pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    const bf16x4 bv = __builtin_bit_cast(bf16x4, braw[qb][g]);
-#pragma unroll
-                    for (int x = 0; x < 4; x++) s[qb][4 * g + x] = (float)bv[x];
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; r++) s[qb][r] = 0.f;
-            }
-        }
-        if (!skip) {
-#pragma unroll
-            for (int ks = 0; ks < K::KS; ks++)
-#pragma unroll
-                for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(ka[ks], qreg[qb][ks], s[qb]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- staging: block t+2 registers -> LDS, block t+3 global -> registers ----
-        store_block(buf2);
-        load_block(t + 3);
-        load_bias(t + 1);
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- issue the V operand reads now; they land while the softmax runs ----
-        bf16x8 va[C / 32][2];
-        {
-            const bf16_t* vbase = vt + buf * K::VBLK + vlane_off;
-#pragma unroll
-            for (int cb = 0; cb < C / 32; cb++)
-#pragma unroll
-                for (int kk = 0; kk < 2; kk++) {
-                    const bf16_t* vp = vbase + (kk * 16) * K::VP + cb * 32;
-                    va[cb][kk] = join_tr(lds_read_tr16(vp), lds_read_tr16(vp + 8 * K::VP));
-                }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- online softmax: a row lives in this lane and the one 32 away ----
-        bf16x8 pb[QB][2];
-#pragma unroll
-        for (int qb = 0; qb < QB; qb++) {
-            if (masked) {
-                const int qi = qw0 + qb * 32 + l32;
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const int key = kb0 + 8 * (r / 4) + 4 * hf + (r % 4);
-                    if (key >= N || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
-                }
-            }
-            float mx = fmaxf(s[qb][0], s[qb][1]);
-#pragma unroll
-            for (int r = 2; r < 16; r++) mx = fmaxf(mx, s[qb][r]);
-            mx = half_max(mx) * kLog2e;
-            if (__any(mx > mref[qb] + kRescaleTau)) {
-                const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
-                const float alpha = fast_exp2(mref[qb] - mnew);
-                mref[qb] = mnew;
-                lsum[qb] *= alpha;
-#pragma unroll
-                for (int cb = 0; cb < C / 32; cb++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) oacc[qb][cb][r] *= alpha;
-            }
-            const float nm = -mref[qb];
-            float ps = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const float pr = fast_exp2(fmaf(s[qb][r], kLog2e, nm));
-                ps += pr;
-                pb[qb][r / 8][r % 8] = (bf16_t)pr;
-            }
-            lsum[qb] += ps;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- K operands of the next block: in flight during the O chain ----
-        read_k(buf1);
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- O^T += V^T . P^T ----
-        if (!skip) {
-#pragma unroll
-            for (int cb = 0; cb < C / 32; cb++)
-#pragma unroll
-                for (int kk = 0; kk < 2; kk++)
-#pragma unroll
-                    for (int qb = 0; qb < QB; qb++) oacc[qb][cb] = mfma32(va[cb][kk], pb[qb][kk], oacc[qb][cb]);
-        }
-        __syncthreads();
-        buf = buf1;
-    }
-
-    // ---- epilogue: o = O / l, lse = m + ln l ----
-#pragma unroll
-    for (int qb = 0; qb < QB; qb++) {
-        const int qi = qw0 + qb * 32 + l32;
-        const float ltot = half_sum(lsum[qb]);
-        const float inv = 1.f / ltot;
-        if (qi < N) {
-            bf16_t* og = (bf16_t*)p.out + base + (size_t)qi * C;
-#pragma unroll
-            for (int cb = 0; cb < C / 32; cb++) {
-#pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    bf16x4 o4;
-#pragma unroll
-                    for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(oacc[qb][cb][4 * g + x] * inv);
-                    *(u32x2*)(og + cb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, o4);
-                }
-            }
-            if (hf == 0) p.lse[(size_t)bh * N + qi] = (mref[qb] + __log2f(ltot)) * kLn2;
-        }
-    }
-}
-
-template <int C, int RP, int QB, bool CAUSAL, bool DENSE>
-int launch(const FwdParams& pin, hipStream_t stream) {
-    using K = Cfg<C, RP, QB>;
-    auto kern = fwd_bf16_kernel<C, RP, QB, CAUSAL, DENSE>;
-    static bool attr_done = false;   // benign race: the call is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)K::kLds) != hipSuccess)
-            return 1;
-        attr_done = true;
-    }
-    FwdParams p = pin;
-    p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
-    p.total_tiles = p.B * p.H * p.n_qtiles;
-    p.tiles_per_xcd = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds, stream, p);
-    return hipGetLastError() == hipSuccess ? 0 : 1;
-}
-
-template <int C, int RP, int QB, bool DENSE>
-int dispatch_causal(const FwdParams& p, hipStream_t stream) {
-    if (p.causal) return launch<C, RP, QB, true, DENSE>(p, stream);
-    return launch<C, RP, QB, false, DENSE>(p, stream);
-}
-
-template <int C, int RP, bool DENSE>
-int dispatch_qb(const FwdParams& p, int qb, hipStream_t stream) {
-    if constexpr (C <= 64) {
-        if (qb == 2) return dispatch_causal<C, RP, 2, DENSE>(p, stream);
-    }
-    return dispatch_causal<C, RP, 1, DENSE>(p, stream);
-}
-
-template <int C>
-int dispatch_rp(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream) {
-    if (dense) return dispatch_qb<C, 0, true>(p, qb, stream);
-    switch (rp) {
-        case 0: return dispatch_qb<C, 0, false>(p, qb, stream);
-        case 16: return dispatch_qb<C, 16, false>(p, qb, stream);
-        case 32: return dispatch_qb<C, 32, false>(p, qb, stream);
-        case 48: return dispatch_qb<C, 48, false>(p, qb, stream);
-        case 64: return dispatch_qb<C, 64, false>(p, qb, stream);
-        default: return -1;
-    }
-}
-
-}  // namespace
-
-// rp: padded factor width (multiple of 16, <= 64); qb: 32-row query blocks per wave (1 or 2;
-// 2 exists for C <= 64 only and falls back to 1 otherwise).
-// Returns 0 on success, 1 on launch failure, -1 when no instantiation fits.
 int fb_launch_fwd_bf16(const FwdParams& p, int C, int rp, bool dense, int qb, hipStream_t stream) {
     switch (C) {
-        case 32: return dispatch_rp<32>(p, rp, dense, qb, stream);
-        case 64: return dispatch_rp<64>(p, rp, dense, qb, stream);
-        case 128: return dispatch_rp<128>(p, rp, dense, qb, stream);
+        case 32: return fb_launch_fwd_bf16_c32(p, rp, dense, qb, stream);
+        case 64: return fb_launch_fwd_bf16_c64(p, rp, dense, qb, stream);
+        case 128: return fb_launch_fwd_bf16_c128(p, rp, dense, qb, stream);
         default: return -1;
     }
 }
