@@ -29,17 +29,19 @@ int check_common(int B, int H, int N, int C, int R) {
     return FB_OK;
 }
 
-int pick_qb(int B, int H, int N, int C, int rp, bool dense) {
+int pick_qb(int B, int H, int N, int C, int rp, bool dense, bool causal) {
     const int forced = g_fwd_qb.load(std::memory_order_relaxed);
     if (forced == 1 || forced == 2 || forced == 8) return forced;
     (void)rp;
+    // Long non-causal C = 128 sequences: the eight-wave ping-pong kernel (256-row tiles).
+    if (C == 128 && !dense && !causal && N >= 8192) return 8;
     // Two query blocks per wave halve the LDS traffic per MFMA but double the accumulator
     // registers: they fit the 256-register budget (two waves per SIMD) only for C <= 64, and
     // only pay when 256-row tiles still leave every CU several workgroups.
     if (C == 128 || dense) return 1;
     if (N % 256 != 0 && N < 1024) return 1;
     const long long tiles256 = (long long)B * H * ((N + 255) / 256);
-    return tiles256 >= 1024 ? 2 : 1;
+    return tiles256 >= 2048 ? 2 : 1;
 }
 
 }  // namespace
@@ -98,7 +100,7 @@ int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int rc;
     if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, false, (hipStream_t)stream);
-    else rc = fb_launch_fwd_bf16(p, C, rp, false, pick_qb(B, H, N, C, rp, false), (hipStream_t)stream);
+    else rc = fb_launch_fwd_bf16(p, C, rp, false, pick_qb(B, H, N, C, rp, false, causal != 0), (hipStream_t)stream);
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
@@ -122,7 +124,7 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int rc;
     if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, true, (hipStream_t)stream);
-    else rc = fb_launch_fwd_bf16(p, C, 0, true, pick_qb(B, H, N, C, 0, true), (hipStream_t)stream);
+    else rc = fb_launch_fwd_bf16(p, C, 0, true, pick_qb(B, H, N, C, 0, true, causal != 0), (hipStream_t)stream);
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 

@@ -324,34 +324,34 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
                 for (int r = 0; r < 16; r++) s[qb][r] = 0.f;
             }
         }
-        if (!skip) {
+        // The V operand reads of this block are spread over the S chain (one transpose-read
+        // pair per MFMA) so they neither stall the wave in a burst nor wait for the softmax.
+        bf16x8 va[C / 32][2];
+        {
+            const bf16_t* vbase = vt + buf * K::VBLK + vlane_off;
+            constexpr int NV = (C / 32) * 2;
             __builtin_amdgcn_s_setprio(FB_PRIO_MFMA);
 #pragma unroll
-            for (int ks = 0; ks < K::KS; ks++)
+            for (int ks = 0; ks < K::KS; ks++) {
+                if (!skip) {
 #pragma unroll
-                for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(ka[ks], qreg[qb][ks], s[qb]);
+                    for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(ka[ks], qreg[qb][ks], s[qb]);
+                }
+                // distribute the NV reads over the KS steps
+#pragma unroll
+                for (int i = (ks * NV) / K::KS; i < ((ks + 1) * NV) / K::KS; i++) {
+                    const bf16_t* vp = vbase + ((i & 1) * 16) * K::VP + (i >> 1) * 32;
+                    va[i >> 1][i & 1] = join_tr(lds_read_tr16(vp), lds_read_tr16(vp + 8 * K::VP));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
             __builtin_amdgcn_s_setprio(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
 
         // ---- staging: block t+2 registers -> LDS, block t+3 global -> registers ----
         store_block(buf2, t + 2);
         load_block(t + 3);
         load_bias(t + 1);
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- issue the V operand reads now; they land while the softmax runs ----
-        bf16x8 va[C / 32][2];
-        {
-            const bf16_t* vbase = vt + buf * K::VBLK + vlane_off;
-#pragma unroll
-            for (int cb = 0; cb < C / 32; cb++)
-#pragma unroll
-                for (int kk = 0; kk < 2; kk++) {
-                    const bf16_t* vp = vbase + (kk * 16) * K::VP + cb * 32;
-                    va[cb][kk] = join_tr(lds_read_tr16(vp), lds_read_tr16(vp + 8 * K::VP));
-                }
-        }
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- online softmax: a row lives in this lane and the one 32 away ----
@@ -392,19 +392,23 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- K operands of the next block: in flight during the O chain ----
-        read_k(buf1);
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- O^T += V^T . P^T ----
-        if (!skip) {
+        // ---- O^T += V^T . P^T, each MFMA followed by a K operand read of the next block ----
+        {
+            const bf16_t* krow = kt + buf1 * K::KBLK + krow_off;
+            constexpr int NM = (C / 32) * 2;
             __builtin_amdgcn_s_setprio(FB_PRIO_MFMA);
 #pragma unroll
-            for (int cb = 0; cb < C / 32; cb++)
+            for (int i = 0; i < NM; i++) {
+                if (!skip) {
 #pragma unroll
-                for (int kk = 0; kk < 2; kk++)
+                    for (int qb = 0; qb < QB; qb++)
+                        oacc[qb][i >> 1] = mfma32(va[i >> 1][i & 1], pb[qb][i & 1], oacc[qb][i >> 1]);
+                }
 #pragma unroll
-                    for (int qb = 0; qb < QB; qb++) oacc[qb][cb] = mfma32(va[cb][kk], pb[qb][kk], oacc[qb][cb]);
+                for (int ks = (i * K::KS) / NM; ks < ((i + 1) * K::KS) / NM; ks++)
+                    ka[ks] = as_bf16x8(*(const u32x4*)(krow + ks * 16));
+                __builtin_amdgcn_sched_barrier(0);
+            }
             __builtin_amdgcn_s_setprio(0);
         }
         __syncthreads();
