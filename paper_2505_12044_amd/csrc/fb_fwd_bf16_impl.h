@@ -149,6 +149,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
 
     const int kend = CAUSAL ? min(N, q0 + K::BQ) : N;
     const int nT = (kend + BK - 1) / BK;
+    // Causal tiles walk the keys from the diagonal back to key 0: with a recency bias such as
+    // ALiBi the row maximum is then met in the first block and the accumulator is never
+    // rescaled again (in ascending order it would be rescaled in nearly every block).
+    auto blk_of = [&](int t) { return CAUSAL ? max(nT - 1 - t, 0) : t; };
 
     // ---- block staging: global -> registers -> LDS.  Rows past N are clamped to row N-1; the
     // keys they stand for are masked to -inf before the softmax, so their values never count.
@@ -166,7 +170,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     const unsigned char* vgb = (const unsigned char*)vg;
 
     auto load_block = [&](int t) {
-        const int k0 = t * BK;
+        const int k0 = blk_of(t) * BK;
         if (k0 + BK <= N) {   // whole block in range (wave-uniform): base + 32-bit offset
             const unsigned boff = (unsigned)k0 * (unsigned)(C * 2);
 #pragma unroll
@@ -241,7 +245,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     const bool bias_fast = DENSE && ((N & 3) == 0);
     auto load_bias = [&](int t) {
         if (!DENSE) return;
-        const int k0 = t * BK;
+        const int k0 = blk_of(t) * BK;
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) {
             const int qi = qw0 + qb * 32 + l32;
@@ -302,7 +306,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     // MFMA chains of a block no row of this wave can see; interior blocks carry none of that.
     auto body = [&](int t, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const int kb0 = t * BK;
+        const int kb0 = blk_of(t) * BK;
         const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;       // (t+1) % NBUF
         const int buf2 = buf1 == NBUF - 1 ? 0 : buf1 + 1;     // (t+2) % NBUF
         // wave-uniform: is this block wholly invisible to this wave (causal), or does it need masks?
@@ -380,7 +384,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
 #pragma unroll
                     for (int r = 0; r < 16; r++) oacc[qb][cb][r] *= alpha;
             }
-            const float nm = -mref[qb];
+            // a row that has not met a visible key yet (causal, reverse order) keeps p = 0
+            const float nm = mref[qb] == -INFINITY ? 0.f : -mref[qb];
             float ps = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; r++) {
@@ -419,9 +424,15 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     int t_plain = N / BK;
     if (CAUSAL) t_plain = min(t_plain, (qw0 + 1) / BK);
     t_plain = min(t_plain, nT);
-    int t = 0;
-    for (; t < t_plain; t++) body(t, std::false_type{});
-    for (; t < nT; t++) body(t, std::true_type{});
+    if (CAUSAL) {   // reverse order: the masked blocks (diagonal, sequence end) come first
+        int t = 0;
+        for (; t < nT - t_plain; t++) body(t, std::true_type{});
+        for (; t < nT; t++) body(t, std::false_type{});
+    } else {
+        int t = 0;
+        for (; t < t_plain; t++) body(t, std::false_type{});
+        for (; t < nT; t++) body(t, std::true_type{});
+    }
 
     // ---- epilogue: o = O / l, lse = m + ln l ----
 #pragma unroll
