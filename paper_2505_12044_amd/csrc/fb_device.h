@@ -90,6 +90,20 @@ FB_DEV bf16_t bf16_limb(float x, int n) {
 FB_DEV int q_limb_of_slot(int slot) { return (0x210100 >> (4 * slot)) & 0xF; }  // 0,0,1,0,1,2
 FB_DEV int k_limb_of_slot(int slot) { return (0x012010 >> (4 * slot)) & 0xF; }  // 0,1,0,2,1,0
 
+// Key-side product columns of one fp32 factor value: [b1, b2, b1, b3, b2, b1] (12 bytes at a
+// 4-byte aligned LDS address).
+FB_DEV void phi_item_store_k(bf16_t* dst, float x) {
+    const bf16_t l1 = (bf16_t)x;
+    const float r1 = x - (float)l1;
+    const bf16_t l2 = (bf16_t)r1;
+    const bf16_t l3 = (bf16_t)(r1 - (float)l2);
+    bf16x2 a = {l1, l2}, b = {l1, l3}, c = {l2, l1};
+    unsigned* d = (unsigned*)dst;
+    d[0] = __builtin_bit_cast(unsigned, a);
+    d[1] = __builtin_bit_cast(unsigned, b);
+    d[2] = __builtin_bit_cast(unsigned, c);
+}
+
 // Eight consecutive columns [8*c8, 8*c8+8) of a factor row widened to the padded layout.
 //   bf16 factors: column j holds phi[j] for j < R, else 0.
 //   fp32 factors: column j holds limb (slot j % 6) of phi[j / 6] for j / 6 < R, else 0.

@@ -66,13 +66,17 @@ struct Cfg {
     static constexpr int KIT = (KCH + kThreads - 1) / kThreads;   // per-thread chunks
     static constexpr int PCH = BK * RP / 8;           // chunks of the factor part
     static constexpr int PIT = (PCH + kThreads - 1) / kThreads;
+    static constexpr int FIT = (BK * (RP / 6) + kThreads - 1) / kThreads > 0
+                                   ? (BK * (RP / 6) + kThreads - 1) / kThreads : 1;   // fp32 (row, rank) items per thread
     static constexpr int KBLK = BK * KP;              // elements per K block buffer
     static constexpr int VBLK = BK * VP;
     static constexpr size_t kLds = (size_t)NBUF * (KBLK + VBLK) * 2;
     static_assert((C % 32) == 0 && (RP % 16) == 0, "shape granularity");
 };
 
-// PM (factor mode): 0 = no factors, 1 = bf16 factors with R % 8 == 0 (whole 16-byte chunks are
+// PM (factor mode): 3 = fp32 factors, one thread per (key, rank) item: three limbs -> six
+// product columns; otherwise:
+// 0 = no factors, 1 = bf16 factors with R % 8 == 0 (whole 16-byte chunks are
 // copied), 2 = general (bf16 factors of any R gathered element-wise, fp32 factors split into
 // limbs).
 template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE>
@@ -91,7 +95,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     if (CAUSAL) qt = p.n_qtiles - 1 - qt;
     const int b = bh / p.H, h = bh - b * p.H;
     const int N = p.N, R = p.R;
-    const bool phi_f32 = PM == 2 && p.phi_f32 != 0;
+    const bool phi_f32 = PM == 3;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -158,6 +162,27 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     // keys they stand for are masked to -inf before the softmax, so their values never count.
     u32x4 kraw[K::KIT], vraw[K::KIT];
     u32x4 praw[K::PIT > 0 ? K::PIT : 1];
+    // fp32 factors: item e = (key row, rank r) of a block, spread evenly over the four waves
+    float fraw[K::FIT];
+    int fitem_row[K::FIT], fitem_r[K::FIT];
+    bool fitem_ok[K::FIT];
+    const float* pkf = (const float*)pkg;
+    if (PM == 3) {
+#pragma unroll
+        for (int it = 0; it < K::FIT; it++) {
+            const int e = lane * kWaves + wave + it * kThreads;
+            fitem_ok[it] = e < BK * R;
+            fitem_row[it] = fitem_ok[it] ? e / R : 0;
+            fitem_r[it] = fitem_ok[it] ? e - fitem_row[it] * R : 0;
+            fraw[it] = 0.f;
+        }
+        // the columns past 6R of every ring slot stay zero for the whole kernel
+        for (int e = tid; e < NBUF * BK * (RP / 2); e += kThreads) {
+            const int row = e / (RP / 2), c2 = e % (RP / 2);
+            *(unsigned*)(kt + (size_t)row * K::KP + C + 2 * c2) = 0u;   // rows of all slots are contiguous
+        }
+        __syncthreads();   // before any thread writes item columns into the same rows
+    }
 
     // byte offsets of this thread's chunks inside a block (row-major rows of C elements)
     unsigned goff[K::KIT];
@@ -192,7 +217,11 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
                 }
             }
         }
-        if (PM != 0) {
+        if (PM == 3) {
+#pragma unroll
+            for (int it = 0; it < K::FIT; it++)
+                if (fitem_ok[it]) fraw[it] = pkf[(size_t)min(k0 + fitem_row[it], N - 1) * R + fitem_r[it]];
+        } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
                 // rotate the factor chunks over the waves from block to block so the
@@ -225,7 +254,11 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
                 *(u32x4*)(vdst + row * K::VP + c8 * 8) = vraw[it];
             }
         }
-        if (PM != 0) {
+        if (PM == 3) {
+#pragma unroll
+            for (int it = 0; it < K::FIT; it++)
+                if (fitem_ok[it]) phi_item_store_k(kdst + fitem_row[it] * K::KP + C + 6 * fitem_r[it], fraw[it]);
+        } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
                 const int e = ((tid + 64 * t) & (kThreads - 1)) + it * kThreads;
@@ -492,8 +525,8 @@ int dispatch_qb(const FwdParams& p, int qb, hipStream_t stream) {
 
 template <int C, int RP>
 int dispatch_pm(const FwdParams& p, int qb, hipStream_t stream) {
-    const bool vec = !p.phi_f32 && (p.R % 8) == 0;
-    if (vec) return dispatch_qb<C, RP, 1, false>(p, qb, stream);
+    if (p.phi_f32) return dispatch_qb<C, RP, 3, false>(p, qb, stream);
+    if ((p.R % 8) == 0) return dispatch_qb<C, RP, 1, false>(p, qb, stream);
     return dispatch_qb<C, RP, 2, false>(p, qb, stream);
 }
 
