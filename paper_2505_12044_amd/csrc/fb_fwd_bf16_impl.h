@@ -71,6 +71,7 @@ struct Cfg {
     static constexpr int KBLK = BK * KP;              // elements per K block buffer
     static constexpr int VBLK = BK * VP;
     static constexpr size_t kLds = (size_t)NBUF * (KBLK + VBLK) * 2;
+    static constexpr size_t kBiasLds = (size_t)kWaves * QB * 32 * (BK + 4) * 2;   // dense mode only
     static_assert((C % 32) == 0 && (RP % 16) == 0, "shape granularity");
 };
 
@@ -90,8 +91,19 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     // workgroups sharing one head's K/V also share one L2; causal tiles go heaviest first.
     const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
     if (L >= p.total_tiles) return;
-    const int bh = L / p.n_qtiles;
-    int qt = L - bh * p.n_qtiles;
+    int bh, qt;
+    if (DENSE && p.bias_bstride == 0) {
+        // bias shared over the batch: the B workgroups that read the same bias tile are
+        // neighbours in the launch order, so the tile is fetched from HBM once per XCD
+        const int rest = L / p.B;
+        const int bb = L - rest * p.B;
+        const int hh = rest / p.n_qtiles;
+        qt = rest - hh * p.n_qtiles;
+        bh = bb * p.H + hh;
+    } else {
+        bh = L / p.n_qtiles;
+        qt = L - bh * p.n_qtiles;
+    }
     if (CAUSAL) qt = p.n_qtiles - 1 - qt;
     const int b = bh / p.H, h = bh - b * p.H;
     const int N = p.N, R = p.R;
@@ -271,33 +283,53 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
         }
     };
 
-    // dense mode: this lane's bias values for block t, already in accumulator order: row
-    // qi, keys 8*g + 4*hf + 0..3 (8 bytes per g).  Chunks wholly above the diagonal or past
-    // the end are not read.
-    u32x2 braw[DENSE ? QB : 1][4];
-    const bool bias_fast = DENSE && ((N & 3) == 0);
+    // dense mode: each wave streams the [32*QB rows] x [32 keys] bias block of its own rows
+    // with coalesced 16-byte loads (four lanes per 64-byte row segment), one block ahead, into
+    // registers, parks it in a wave-private LDS tile and reads it back in accumulator order
+    // (row = lane % 32, keys 8*g + 4*hf + 0..3) as the initial value of the S chain.  Chunks
+    // wholly above the diagonal or past the end are never read.
+    constexpr int BP = BK + 4;                       // bias tile row pitch (elements): 72 bytes
+    bf16_t* const bt = vt + NBUF * K::VBLK + wave * (QB * 32 * BP);
+    u32x4 braw[DENSE ? QB : 1][2];
+    const bool bias_fast = DENSE && ((N & 7) == 0);
     auto load_bias = [&](int t) {
         if (!DENSE) return;
         const int k0 = blk_of(t) * BK;
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) {
-            const int qi = qw0 + qb * 32 + l32;
 #pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const int j = k0 + 8 * g + 4 * hf;
-                u32x2 a = u32x2{0u, 0u};
+            for (int i = 0; i < 2; i++) {
+                const int e = lane + 64 * i;
+                const int row = e >> 2, c = e & 3;
+                const int qi = qw0 + qb * 32 + row;
+                const int j = k0 + 8 * c;
+                u32x4 a = u32x4{0u, 0u, 0u, 0u};
                 if (qi < N && j < N && !(CAUSAL && j > qi)) {
                     const bf16_t* src = bg + (size_t)qi * N + j;
                     if (bias_fast) {
-                        a = *(const u32x2*)src;
+                        a = *(const u32x4*)src;
                     } else {
-                        bf16x4 tmp;
+                        bf16x8 tmp;
 #pragma unroll
-                        for (int x = 0; x < 4; x++) tmp[x] = (j + x < N) ? src[x] : (bf16_t)0.f;
-                        a = __builtin_bit_cast(u32x2, tmp);
+                        for (int x = 0; x < 8; x++) tmp[x] = (j + x < N) ? src[x] : (bf16_t)0.f;
+                        a = as_uint4(tmp);
                     }
                 }
-                braw[qb][g] = a;
+                braw[qb][i] = a;
+            }
+        }
+    };
+    auto stage_bias = [&]() {
+        if (!DENSE) return;
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) {
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                const int e = lane + 64 * i;
+                const int row = e >> 2, c = e & 3;
+                u32x2* d = (u32x2*)(bt + (qb * 32 + row) * BP + 8 * c);   // 8-byte aligned
+                d[0] = u32x2{braw[qb][i].x, braw[qb][i].y};
+                d[1] = u32x2{braw[qb][i].z, braw[qb][i].w};
             }
         }
     };
@@ -325,6 +357,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     store_block(1, 1);
     load_block(2);
     load_bias(0);
+    stage_bias();
+    load_bias(1);
     __syncthreads();
     read_k(0);
 
@@ -350,9 +384,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) {
             if (DENSE) {
+                const bf16_t* brow = bt + (qb * 32 + l32) * BP + 4 * hf;
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
-                    const bf16x4 bv = __builtin_bit_cast(bf16x4, braw[qb][g]);
+                    const bf16x4 bv = __builtin_bit_cast(bf16x4, *(const u32x2*)(brow + 8 * g));
 #pragma unroll
                     for (int x = 0; x < 4; x++) s[qb][4 * g + x] = (float)bv[x];
                 }
@@ -388,7 +423,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
         // ---- staging: block t+2 registers -> LDS, block t+3 global -> registers ----
         store_block(buf2, t + 2);
         load_block(t + 3);
-        load_bias(t + 1);
+        stage_bias();                   // block t+1 (loaded one iteration ago) -> wave-private LDS
+        load_bias(t + 2);
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- online softmax: a row lives in this lane and the one 32 away ----
@@ -497,7 +533,7 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     static bool attr_done = false;   // benign race: the call is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)K::kLds) != hipSuccess)
+                                (int)(K::kLds + (DENSE ? K::kBiasLds : 0))) != hipSuccess)
             return 1;
         attr_done = true;
     }
@@ -505,7 +541,7 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
     p.total_tiles = p.B * p.H * p.n_qtiles;
     p.tiles_per_xcd = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds, stream, p);
+    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds + (DENSE ? K::kBiasLds : 0), stream, p);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
