@@ -74,6 +74,15 @@ FB_DEV bf16x8 join_tr(s16x4 lo, s16x4 hi) {
 
 FB_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Maximum of the 16 accumulator registers as a shallow tree (three-input maxima, depth 3)
+// rather than a 15-deep dependent chain.
+FB_DEV float max3f(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+FB_DEV float max16(const f32x16& s) {
+    const float a = max3f(s[0], s[1], s[2]), b = max3f(s[3], s[4], s[5]), c = max3f(s[6], s[7], s[8]);
+    const float d = max3f(s[9], s[10], s[11]), e = max3f(s[12], s[13], s[14]);
+    return max3f(max3f(a, b, c), max3f(d, e, s[15]), a);
+}
+
 // ---- bf16 limbs of an fp32 value ----------------------------------------------------------
 // x = x1 + x2 + x3 (+ ~2^-24 |x|) with each limb a bf16 value.  For a product a*b the six
 // column pairs (a1,b1) (a1,b2) (a2,b1) (a1,b3) (a2,b2) (a3,b1) recover it to ~2^-24.

@@ -34,6 +34,7 @@
 #include <type_traits>
 
 #include "fb_device.h"
+#include "fb_fwd_bf16_il.h"
 #include "fb_fwd_bf16_pp.h"
 #include "fb_launch.h"
 #include "fb_params.h"
@@ -43,6 +44,14 @@
 #endif
 #ifndef FB_STAGGER
 #define FB_STAGGER 0
+#endif
+
+#ifdef FB_TRACE4
+__device__ long long fb_trace4_buf[4 * 64 * 8];
+#define FB_T4(slot)                                                                         \
+    if (blockIdx.x == FB_TRACE4 && lane == 0 && t < 64) fb_trace4_buf[(wave * 64 + t) * 8 + (slot)] = clock64();
+#else
+#define FB_T4(slot)
 #endif
 
 namespace {
@@ -373,6 +382,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     // MFMA chains of a block no row of this wave can see; interior blocks carry none of that.
     auto body = [&](int t, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        FB_T4(0)
         const int kb0 = blk_of(t) * BK;
         const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;       // (t+1) % NBUF
         const int buf2 = buf1 == NBUF - 1 ? 0 : buf1 + 1;     // (t+2) % NBUF
@@ -420,12 +430,14 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
             __builtin_amdgcn_s_setprio(0);
         }
 
+        FB_T4(1)
         // ---- staging: block t+2 registers -> LDS, block t+3 global -> registers ----
         store_block(buf2, t + 2);
         load_block(t + 3);
         stage_bias();                   // block t+1 (loaded one iteration ago) -> wave-private LDS
         load_bias(t + 2);
         __builtin_amdgcn_sched_barrier(0);
+        FB_T4(2)
 
         // ---- online softmax: a row lives in this lane and the one 32 away ----
         bf16x8 pb[QB][2];
@@ -439,10 +451,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
                     if (key >= N || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
                 }
             }
-            float mx = fmaxf(s[qb][0], s[qb][1]);
-#pragma unroll
-            for (int r = 2; r < 16; r++) mx = fmaxf(mx, s[qb][r]);
-            mx = half_max(mx) * kLog2e;
+            float mx = half_max(max16(s[qb])) * kLog2e;
             if (__any(mx > mref[qb] + kRescaleTau)) {
                 const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
                 const float alpha = fast_exp2(mref[qb] - mnew);
@@ -455,16 +464,17 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
             }
             // a row that has not met a visible key yet (causal, reverse order) keeps p = 0
             const float nm = mref[qb] == -INFINITY ? 0.f : -mref[qb];
-            float ps = 0.f;
+            float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
             for (int r = 0; r < 16; r++) {
                 const float pr = fast_exp2(fmaf(s[qb][r], kLog2e, nm));
-                ps += pr;
+                ps[r & 3] += pr;
                 pb[qb][r / 8][r % 8] = (bf16_t)pr;
             }
-            lsum[qb] += ps;
+            lsum[qb] += (ps[0] + ps[1]) + (ps[2] + ps[3]);
         }
         __builtin_amdgcn_sched_barrier(0);
+        FB_T4(3)
 
         // ---- O^T += V^T . P^T, each MFMA followed by a K operand read of the next block ----
         {
@@ -485,7 +495,9 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
             }
             __builtin_amdgcn_s_setprio(0);
         }
+        FB_T4(4)
         __syncthreads();
+        FB_T4(5)
         buf = buf1;
     };
 
@@ -533,7 +545,7 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     static bool attr_done = false;   // benign race: the call is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(K::kLds + (DENSE ? K::kBiasLds : 0))) != hipSuccess)
+                                (int)(K::kLds + (DENSE ? K::kBiasLds : 0) + 64 * 1024)) != hipSuccess)
             return 1;
         attr_done = true;
     }
@@ -541,7 +553,7 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
     p.total_tiles = p.B * p.H * p.n_qtiles;
     p.tiles_per_xcd = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds + (DENSE ? K::kBiasLds : 0), stream, p);
+    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds + (DENSE ? K::kBiasLds : 0) + fb_debug_lds_pad(), stream, p);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
@@ -573,6 +585,10 @@ int dispatch_pm(const FwdParams& p, int qb, hipStream_t stream) {
 template <int C>
 int fwd_bf16_dispatch(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream) {
     if (qb == 8) return fbpp::dispatch<C>(p, rp, dense, stream);
+    if (qb == 4) {
+        if (rp <= 32) return fbil::dispatch<C>(p, rp, dense, stream);
+        qb = 1;
+    }
     if (dense) return dispatch_qb<C, 0, 0, true>(p, qb, stream);
     switch (rp) {
         case 0: return dispatch_qb<C, 0, 0, false>(p, qb, stream);

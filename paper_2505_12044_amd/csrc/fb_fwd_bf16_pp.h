@@ -296,10 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
                 if (key >= N || (CAUSAL && key > qi)) s[r] = -INFINITY;
             }
         }
-        float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-        for (int r = 2; r < 16; r++) mx = fmaxf(mx, s[r]);
-        mx = half_max(mx) * kLog2e;
+        float mx = half_max(max16(s)) * kLog2e;
         if (__any(mx > mref + kRescaleTau)) {
             const float mnew = fmaxf(fmaxf(mref, mx), -1e30f);
             const float alpha = fast_exp2(mref - mnew);
@@ -313,14 +310,14 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
         bf16x8 pb[2];
         {
             const float nm = -mref;
-            float ps = 0.f;
+            float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
             for (int r = 0; r < 16; r++) {
                 const float pr = fast_exp2(fmaf(s[r], kLog2e, nm));
-                ps += pr;
+                ps[r & 3] += pr;
                 pb[r / 8][r % 8] = (bf16_t)pr;
             }
-            lsum += ps;
+            lsum += (ps[0] + ps[1]) + (ps[2] + ps[3]);
         }
         __builtin_amdgcn_sched_barrier(0);
         FB_T(2)

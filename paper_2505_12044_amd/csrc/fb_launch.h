@@ -12,4 +12,7 @@ int fb_launch_fwd_f32(const FwdParams& p, int C, bool dense, hipStream_t stream)
 int fb_launch_fwd_bf16(const FwdParams& p, int C, int rp, bool dense, int qb, hipStream_t stream);
 int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream);
 
+// Extra dynamic LDS bytes added to forward launches (experiments on occupancy; normally 0).
+size_t fb_debug_lds_pad();
+
 #endif
