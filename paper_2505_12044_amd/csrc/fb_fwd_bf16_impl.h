@@ -34,6 +34,7 @@
 #include <type_traits>
 
 #include "fb_device.h"
+#include "fb_fwd_bf16_dma.h"
 #include "fb_fwd_bf16_il.h"
 #include "fb_fwd_bf16_pp.h"
 #include "fb_launch.h"
@@ -585,6 +586,11 @@ int dispatch_pm(const FwdParams& p, int qb, hipStream_t stream) {
 template <int C>
 int fwd_bf16_dispatch(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream) {
     if (qb == 8) return fbpp::dispatch<C>(p, rp, dense, stream);
+    if (qb == 16) {
+        const int rc = fbdma::dispatch<C>(p, rp, dense, stream);
+        if (rc >= 0) return rc;
+        qb = 1;   // shapes the direct-to-LDS kernel does not take
+    }
     if (qb == 4) {
         if (rp <= 32) return fbil::dispatch<C>(p, rp, dense, stream);
         qb = 1;
