@@ -90,31 +90,12 @@ struct Cfg {
 // 0 = no factors, 1 = bf16 factors with R % 8 == 0 (whole 16-byte chunks are
 // copied), 2 = general (bf16 factors of any R gathered element-wise, fp32 factors split into
 // limbs).
+// One tile: the 128 * QB query rows [qt * BQ, (qt + 1) * BQ) of head bh against all keys they see.
 template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE>
-__global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
+FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, const int qt) {
     using K = Cfg<C, RP, QB>;
-    extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* const kt = (bf16_t*)smem;                 // [NBUF][BK][KP]
     bf16_t* const vt = kt + NBUF * K::KBLK;           // [NBUF][BK][VP]
-
-    // ---- which tile: contiguous runs of tiles per XCD (workgroup w lands on XCD w % 8), so the
-    // workgroups sharing one head's K/V also share one L2; causal tiles go heaviest first.
-    const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
-    if (L >= p.total_tiles) return;
-    int bh, qt;
-    if (DENSE && p.bias_bstride == 0) {
-        // bias shared over the batch: the B workgroups that read the same bias tile are
-        // neighbours in the launch order, so the tile is fetched from HBM once per XCD
-        const int rest = L / p.B;
-        const int bb = L - rest * p.B;
-        const int hh = rest / p.n_qtiles;
-        qt = rest - hh * p.n_qtiles;
-        bh = bb * p.H + hh;
-    } else {
-        bh = L / p.n_qtiles;
-        qt = L - bh * p.n_qtiles;
-    }
-    if (CAUSAL) qt = p.n_qtiles - 1 - qt;
     const int b = bh / p.H, h = bh - b * p.H;
     const int N = p.N, R = p.R;
     const bool phi_f32 = PM == 3;
@@ -539,6 +520,42 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     }
 }
 
+// Work units.  Non-causal: one tile per workgroup.  Causal: the tile qt sees 4 * QB * (qt + 1)
+// key blocks, so a workgroup takes the pair (n - 1 - u, u): every workgroup then walks the
+// same number of key blocks and the launch has no long tail of heavy tiles (with single
+// tiles per workgroup the heaviest tile alone lasts almost half of the whole launch at
+// N = 4096).  Units are numbered so that each XCD gets a contiguous run (workgroup w lands
+// on XCD w % 8): the workgroups sharing one head's K/V also share one L2.
+template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE>
+__global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+    if (L >= p.total_tiles) return;
+    int bh, u;
+    if (DENSE && p.bias_bstride == 0) {
+        // bias shared over the batch: the B workgroups that read the same bias tile are
+        // neighbours in the launch order, so the tile is fetched from HBM once per XCD
+        const int rest = L / p.B;
+        const int bb = L - rest * p.B;
+        const int hh = rest / p.n_units;
+        u = rest - hh * p.n_units;
+        bh = bb * p.H + hh;
+    } else {
+        bh = L / p.n_units;
+        u = L - bh * p.n_units;
+    }
+    if (CAUSAL) {
+        const int heavy = p.n_qtiles - 1 - u;
+        fwd_tile<C, RP, QB, PM, CAUSAL, DENSE>(p, smem, bh, heavy);
+        if (u != heavy) {
+            __syncthreads();   // the LDS ring is reused: every wave must have left the first tile
+            fwd_tile<C, RP, QB, PM, CAUSAL, DENSE>(p, smem, bh, u);
+        }
+    } else {
+        fwd_tile<C, RP, QB, PM, CAUSAL, DENSE>(p, smem, bh, u);
+    }
+}
+
 template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE>
 int launch(const FwdParams& pin, hipStream_t stream) {
     using K = Cfg<C, RP, QB>;
@@ -552,7 +569,8 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     }
     FwdParams p = pin;
     p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
-    p.total_tiles = p.B * p.H * p.n_qtiles;
+    p.n_units = CAUSAL ? (p.n_qtiles + 1) / 2 : p.n_qtiles;
+    p.total_tiles = p.B * p.H * p.n_units;
     p.tiles_per_xcd = (p.total_tiles + 7) / 8;
     hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds + (DENSE ? K::kBiasLds : 0) + fb_debug_lds_pad(), stream, p);
     return hipGetLastError() == hipSuccess ? 0 : 1;

@@ -21,7 +21,8 @@ struct FwdParams {
     long long bias_bstride;  // elements between batch items of bias (0 when shared)
     float scale;
     int n_qtiles;         // query tiles per (b,h)
-    int total_tiles;      // B*H*n_qtiles
+    int n_units;          // work units (workgroups) per (b,h): tiles, or tile pairs when causal
+    int total_tiles;      // B*H*n_units
     int tiles_per_xcd;    // ceil(total_tiles / 8)
 };
 
