@@ -110,7 +110,7 @@ FB_DEV void store_dphi(const f32x16* acc_phi /* [RP2/32] */, float* scratch /* w
 // dq kernel: lane = query
 // ------------------------------------------------------------------------------------------
 template <int C, int RP, bool CAUSAL>
-__global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     using K = BwdCfg<C, RP>;
     constexpr int BK = K::T, BQ = kWaves * 32;
     extern __shared__ __align__(16) unsigned char smem[];

@@ -1,0 +1,578 @@
+// bf16 MFMA backward of attention with a factorised bias, gfx950: streamed version.
+//
+// With Aq = [q*scale | phi_q], Ak = [k | phi_k] (FlashBias Eq. 3) and S = Aq Ak^T,
+// P = exp(S - lse), the chain rule for L = sum(dO * O) gives
+//   dV = P^T dO,  dP = dO V^T,  dS = P o (dP - D),  D_i = sum_c dO_ic O_ic,
+//   dAk = dS^T Aq  -> dK = dAk[:, :C],          dphi_k = dAk[:, C:],
+//   dAq = dS Ak    -> dQ = scale * dAq[:, :C],  dphi_q = dAq[:, C:].
+// The factor gradients are extra columns of the contractions that give dK and dQ; no N x N
+// gradient is ever written.  No atomics; results are deterministic.
+//
+// Kernels:
+//   prep  : writes the concatenated operands Aq = [q*scale | phi_q | 0], Ak = [k | phi_k | 0]
+//           (bf16, width W = C + 32 when R > 0; fp32 factors as three bf16 limbs, six product
+//           columns per rank as in the forward) into the workspace
+//   vec   : (lse * log2 e, D) per query row
+//   main<DKV = true>  : a lane owns a key;   streams 32-query blocks; accumulates dV^T, dAk^T
+//   main<DKV = false> : a lane owns a query; streams 32-key blocks;   accumulates dAq^T
+// Both main kernels recompute S and dP (7 contractions instead of 5, but no atomic dQ).  They
+// use the transposed orientation of the forward: the lane-side operands stay in registers,
+// score-shaped accumulators feed the next MFMA as its B operand without leaving registers,
+// and the transposed A operands come from the LDS transpose read.
+//
+// Streaming.  Because prep has already built the operand rows, a streamed block is a pure
+// copy, done with direct-to-LDS loads (global_load_lds_dwordx4 from inline assembly, see
+// fb_fwd_bf16_dma.h for why) into a ring of four block slots; nothing passes through
+// registers.  One barrier per iteration, in the middle:
+//     S, dP chains of block i | exp / dS | wait, barrier | issue block i+3 |
+//     output chains of block i, first operand reads of block i+1
+// A direct load writes 64 consecutive 16-byte pieces, so a 32-row tile of width W is kept as
+// W/64 panels [32][64] (and one [32][32] panel if W % 64), each unpadded with an XOR chunk
+// swizzle that makes both the row reads and the transpose reads bank-conflict free.
+#include <hip/hip_runtime.h>
+
+#include "fb_device.h"
+#include "fb_launch.h"
+#include "fb_params.h"
+
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+constexpr int BT = 32;       // streamed rows per block
+constexpr int NSLOT = 4;
+
+FB_DEV int swz64(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
+FB_DEV int swz32(int r) { return (r >> 2) & 3; }
+
+// s_waitcnt with only vmcnt constrained
+template <int N>
+FB_DEV void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+FB_DEV void wait_vmcnt_n(int n) {   // n is wave-uniform, 0..7
+    switch (n) {
+        case 0: wait_vmcnt<0>(); break;
+        case 1: wait_vmcnt<1>(); break;
+        case 2: wait_vmcnt<2>(); break;
+        case 3: wait_vmcnt<3>(); break;
+        case 4: wait_vmcnt<4>(); break;
+        case 5: wait_vmcnt<5>(); break;
+        case 6: wait_vmcnt<6>(); break;
+        default: wait_vmcnt<7>(); break;
+    }
+}
+
+// lane l reads sbase + voff (bytes); its 16 bytes land at LDS byte address lds_addr + 16 * l
+FB_DEV void dma16(const void* sbase, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+
+// 32-row tile of W bf16 columns stored as panels (see the header comment)
+template <int W>
+struct Tile {
+    static constexpr int NP64 = W / 64;
+    static constexpr bool HAS32 = (W % 64) != 0;
+    static constexpr int BYTES = W * 64;
+    static constexpr int NDMA = NP64 * 4 + (HAS32 ? 2 : 0);   // direct loads per tile
+    // direct load d of the tile: row and 16-byte source chunk fetched by `lane`, LDS offset of the load
+    FB_DEV static void dma_map(int d, int lane, int& row, int& chunk, int& dst) {
+        if (d < NP64 * 4) {
+            row = (d & 3) * 8 + (lane >> 3);
+            chunk = (d >> 2) * 8 + ((lane & 7) ^ swz64(row));
+            dst = (d >> 2) * 4096 + (d & 3) * 1024;
+        } else {
+            const int e = d - NP64 * 4;
+            row = e * 16 + (lane >> 2);
+            chunk = NP64 * 8 + ((lane & 3) ^ swz32(row));
+            dst = NP64 * 4096 + e * 1024;
+        }
+    }
+};
+
+template <int C, int RP>
+struct Cfg {
+    static constexpr int RP2 = RP > 0 ? 32 : 0;        // factor columns kept in the workspace rows
+    static constexpr int W = C + RP2;
+    static constexpr int KS = (C + RP) / 16;           // k-steps of the score contraction
+    static constexpr int CS = C / 16;                  // k-steps of the dP contraction
+    static constexpr int MB = W / 32;                  // 32-column blocks of dAq / dAk
+    static constexpr int MBC = C / 32;
+    using T1 = Tile<W>;
+    using T2 = Tile<C>;
+    static constexpr int kVecBytes = 1024;             // (lse2, D) of 32 rows in the first 256 bytes
+    static constexpr size_t kEpiLds = (size_t)kWaves * 32 * (RP2 + 1) * sizeof(float);
+};
+
+// ------------------------------------------------------------------------------------------
+// prep / vec
+// ------------------------------------------------------------------------------------------
+template <int C, int RP>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __restrict__ aq,
+                                                       bf16_t* __restrict__ ak) {
+    using K = Cfg<C, RP>;
+    constexpr int CPR = K::W / 8;
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long row = gid / CPR;                        // (b*H + h)*N + i
+    const int c = (int)(gid - row * CPR);
+    const long long rows = (long long)p.B * p.H * p.N;
+    if (row >= rows) return;
+    bf16x8 a, b;
+    if (c < C / 8) {
+        const bf16x8 x = as_bf16x8(*(const u32x4*)((const bf16_t*)p.q + row * C + c * 8));
+#pragma unroll
+        for (int e = 0; e < 8; e++) a[e] = (bf16_t)((float)x[e] * p.scale);
+        b = as_bf16x8(*(const u32x4*)((const bf16_t*)p.k + row * C + c * 8));
+    } else {
+        const bool f32 = p.phi_f32 != 0;
+        const size_t esz = f32 ? 4 : 2;
+        const long long bh = row / p.N;
+        const int i = (int)(row - bh * p.N);
+        const int bb = (int)(bh / p.H), h = (int)(bh - (long long)bb * p.H);
+        const size_t off = ((size_t)bb * p.phi_bstride + ((size_t)h * p.N + i) * p.R) * esz;
+        a = phi_chunk_gather<true>((const unsigned char*)p.phi_q + off, c - C / 8, p.R, f32);
+        b = phi_chunk_gather<false>((const unsigned char*)p.phi_k + off, c - C / 8, p.R, f32);
+    }
+    *(u32x4*)(aq + row * K::W + c * 8) = as_uint4(a);
+    *(u32x4*)(ak + row * K::W + c * 8) = as_uint4(b);
+}
+
+template <int C>
+__global__ __launch_bounds__(256) void bwd_vec_kernel(const bf16_t* __restrict__ out,
+                                                      const bf16_t* __restrict__ dout,
+                                                      const float* __restrict__ lse,
+                                                      float2* __restrict__ vec, long long rows) {
+    constexpr int LPR = C / 8;   // lanes per row, 16 bytes each
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long row = gid / LPR;
+    const int c8 = (int)(gid % LPR);
+    float acc = 0.f;
+    if (row < rows) {
+        const bf16x8 a = as_bf16x8(*(const u32x4*)(out + row * C + c8 * 8));
+        const bf16x8 b = as_bf16x8(*(const u32x4*)(dout + row * C + c8 * 8));
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc = fmaf((float)a[e], (float)b[e], acc);
+    }
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if (c8 == 0 && row < rows) vec[row] = make_float2(lse[row] * kLog2e, acc);
+}
+
+// Write one wave's factor-gradient columns to LDS scratch and reduce limb columns.
+// acc[mb] holds columns mb*32 + 8*g + 4*hf + x (register 4*g + x) for row l32.
+template <int RP2, bool QSIDE>
+FB_DEV void store_dphi(const f32x16* acc_phi /* [RP2/32] */, float* scratch /* wave-private [32][RP2+1] */,
+                       void* dst_row /* gradient row of this lane's token or null */, int R,
+                       bool f32, int l32, int hf) {
+#pragma unroll
+    for (int mb = 0; mb < RP2 / 32; mb++)
+#pragma unroll
+        for (int r = 0; r < 16; r++)
+            scratch[l32 * (RP2 + 1) + mb * 32 + 8 * (r / 4) + 4 * hf + (r % 4)] = acc_phi[mb][r];
+    __syncthreads();
+    if (dst_row != nullptr) {
+        for (int r = hf; r < R; r += 2) {
+            const float* s = scratch + l32 * (RP2 + 1);
+            if (f32) {
+                // distinct limbs on the other side: query side [a1,a1,a2,a1,a2,a3] -> slots 0,2,5
+                // multiply dphi_k; key side [b1,b2,b1,b3,b2,b1] -> slots 0,1,3 multiply dphi_q
+                const float val = QSIDE ? (s[6 * r] + s[6 * r + 1] + s[6 * r + 3])
+                                        : (s[6 * r] + s[6 * r + 2] + s[6 * r + 5]);
+                ((float*)dst_row)[r] = val;
+            } else {
+                ((bf16_t*)dst_row)[r] = (bf16_t)s[r];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// main kernel.  "lane side" = the 128 rows owned by the workgroup (keys when DKV, else
+// queries); "streamed side" = the other index, walked in blocks of 32 rows.
+//   T1 tile: rows of the streamed operand of S (Aq when DKV, else Ak), width W
+//   T2 tile: rows of the streamed operand of dP (dO when DKV, else V), width C
+// ------------------------------------------------------------------------------------------
+struct MainArgs {
+    const bf16_t* aq;     // [B*H*N][W]
+    const bf16_t* ak;     // [B*H*N][W]
+    const float2* vec;    // [B*H*N]  (lse * log2 e, D)
+};
+
+template <int C, int RP, bool CAUSAL, bool DKV>
+FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem, const int bh, const int tile) {
+    using K = Cfg<C, RP>;
+    using T1 = typename K::T1;
+    using T2 = typename K::T2;
+    constexpr int kSlotBytes = T1::BYTES + T2::BYTES + (DKV ? K::kVecBytes : 0);
+    constexpr int kOffT2 = T1::BYTES, kOffVec = T1::BYTES + T2::BYTES;
+    constexpr int ND = T1::NDMA + T2::NDMA + (DKV ? 1 : 0);       // direct loads per block
+    constexpr int NDW = (ND + kWaves - 1) / kWaves;               // ... per wave, at most
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+    const int N = p.N, R = p.R;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, hf = lane >> 5;
+    const int r0 = tile * 128;            // first lane-side row of the workgroup
+    const int rw0 = r0 + wave * 32;       // ... of this wave
+    const int ri = rw0 + l32;             // this lane's row
+    const int rc = min(ri, N - 1);        // rows past N compute on row N-1 and are not stored
+
+    const size_t rowbase = (size_t)bh * N;
+    const bf16_t* l1g = (DKV ? a.ak : a.aq) + rowbase * K::W;                       // lane-side operand of S
+    const bf16_t* l2g = (const bf16_t*)(DKV ? p.v : p.dout) + rowbase * C;          // lane-side operand of dP
+    const bf16_t* t1g = (DKV ? a.aq : a.ak) + rowbase * K::W;                       // streamed
+    const bf16_t* t2g = (const bf16_t*)(DKV ? p.dout : p.v) + rowbase * C;
+    const float2* vecg = a.vec + rowbase;
+
+    // ---- lane-side operands, loop invariant ----
+    bf16x8 l1reg[K::KS], l2reg[K::CS];
+#pragma unroll
+    for (int ks = 0; ks < K::KS; ks++)
+        l1reg[ks] = as_bf16x8(*(const u32x4*)(l1g + (size_t)rc * K::W + ks * 16 + 8 * hf));
+#pragma unroll
+    for (int cs = 0; cs < K::CS; cs++)
+        l2reg[cs] = as_bf16x8(*(const u32x4*)(l2g + (size_t)rc * C + cs * 16 + 8 * hf));
+    float my_lse2 = 0.f, my_d = 0.f;
+    if (!DKV) {
+        const float2 v2 = vecg[rc];
+        my_lse2 = v2.x;
+        my_d = v2.y;
+    }
+
+    f32x16 acc1[K::MB];                 // dAk^T or dAq^T
+    f32x16 acc2[DKV ? K::MBC : 1];      // dV^T
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+#pragma unroll
+        for (int mb = 0; mb < K::MB; mb++) acc1[mb][r] = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < (DKV ? K::MBC : 1); mb++) acc2[mb][r] = 0.f;
+    }
+
+    // ---- streamed block range ----
+    const int nblk_all = (N + BT - 1) / BT;
+    int b_begin = 0, b_end = nblk_all;
+    if (CAUSAL) {
+        if (DKV) b_begin = r0 / BT;                            // queries before the first key see nothing
+        else b_end = min(nblk_all, (min(N, r0 + 128) + BT - 1) / BT);
+    }
+    const int nIt = b_end - b_begin;
+    auto blk_of = [&](int i) __attribute__((always_inline)) { return min(b_begin + i, nblk_all - 1); };
+
+    // ---- this wave's share of a block's direct loads ----
+    int dma_row[NDW];
+    unsigned dma_col[NDW];      // byte offset inside the source row
+#pragma unroll
+    for (int j = 0; j < NDW; j++) {
+        const int d = wave + kWaves * j;
+        int row = 0, chunk = 0, dst = 0;
+        if (d < T1::NDMA) T1::dma_map(d, lane, row, chunk, dst);
+        else if (d < T1::NDMA + T2::NDMA) T2::dma_map(d - T1::NDMA, lane, row, chunk, dst);
+        else { row = 0; chunk = min(lane, 15); }               // vec: 32 rows x 8 bytes = 16 chunks
+        dma_row[j] = row;
+        dma_col[j] = (unsigned)chunk * 16u;
+    }
+    const int my_ndma = (ND - wave + kWaves - 1) / kWaves;     // wave-uniform
+    auto issue_block = [&](int i, int slot) __attribute__((always_inline)) {
+        const int blk = blk_of(i);
+        const int left = N - blk * BT - 1;                     // last valid row inside the block
+        const unsigned sbase = lds0 + slot * kSlotBytes;
+#pragma unroll
+        for (int j = 0; j < NDW; j++) {
+            const int d = wave + kWaves * j;                   // wave-uniform
+            if (d >= ND) break;
+            int row = 0, chunk = 0, dst = 0;
+            if (d < T1::NDMA) {
+                T1::dma_map(d, 0, row, chunk, dst);
+                const unsigned voff = (unsigned)(min(dma_row[j], left) * (K::W * 2)) + dma_col[j];
+                dma16(t1g + (size_t)blk * BT * K::W, voff, sbase + dst);
+            } else if (d < T1::NDMA + T2::NDMA) {
+                T2::dma_map(d - T1::NDMA, 0, row, chunk, dst);
+                const unsigned voff = (unsigned)(min(dma_row[j], left) * (C * 2)) + dma_col[j];
+                dma16(t2g + (size_t)blk * BT * C, voff, sbase + kOffT2 + dst);
+            } else {
+                // rows past N inside the block repeat earlier rows; they are masked by index
+                const unsigned voff = min(dma_col[j], (unsigned)(left >> 1) * 16u);
+                dma16(vecg + (size_t)blk * BT, voff, sbase + kOffVec);
+            }
+        }
+    };
+
+    // ---- per-lane LDS read offsets (bytes inside a panel) ----
+    int rb64[4], rb32[2];                 // row operand, k-step j of a panel: 16 bytes at row l32
+#pragma unroll
+    for (int j = 0; j < 4; j++) rb64[j] = l32 * 128 + (((2 * j + hf) ^ swz64(l32)) << 4);
+#pragma unroll
+    for (int j = 0; j < 2; j++) rb32[j] = l32 * 64 + (((2 * j + hf) ^ swz32(l32)) << 4);
+    const int i16 = lane & 15, blk16 = l32 >> 4;
+    int tr64[2][2], tr32[2];              // transpose reads: 32-column block m of a panel, half hi
+#pragma unroll
+    for (int hi = 0; hi < 2; hi++) {
+        const int row = 8 * hi + 4 * hf + (i16 >> 2);
+#pragma unroll
+        for (int m = 0; m < 2; m++)
+            tr64[m][hi] = row * 128 + (((m * 4 + 2 * blk16 + ((i16 & 3) >> 1)) ^ swz64(row)) << 4) + (i16 & 1) * 8;
+        tr32[hi] = row * 64 + (((2 * blk16 + ((i16 & 3) >> 1)) ^ swz32(row)) << 4) + (i16 & 1) * 8;
+    }
+    // operand n of a block, in consumption order:
+    //   [0, KS)            S   k-step n          row read of T1
+    //   [KS, KS+CS)        dP  k-step n-KS       row read of T2
+    //   then NO1 = 2*MB    output 1, (mb, kk)    transpose read of T1
+    //   then NO2 = 2*MBC   output 2 (DKV only)   transpose read of T2
+    constexpr int NO1 = 2 * K::MB, NO2 = DKV ? 2 * K::MBC : 0;
+    constexpr int NA = K::KS + K::CS;          // operands of the first half
+    constexpr int NOPS = NA + NO1 + NO2;
+    // LDS operand reads run LA MFMAs ahead of their use; the first half never reads past its own block
+    constexpr int LA = (NO1 + NO2) < 3 ? (NO1 + NO2) : 3;
+    bf16x8 opr[LA + 1];
+    auto row_read = [&](const unsigned char* tilep, int np64, int ks) __attribute__((always_inline)) {
+        if (ks < np64 * 4) return as_bf16x8(*(const u32x4*)(tilep + (ks >> 2) * 4096 + rb64[ks & 3]));
+        return as_bf16x8(*(const u32x4*)(tilep + np64 * 4096 + rb32[ks - np64 * 4]));
+    };
+    auto tr_read = [&](const unsigned char* tilep, int np64, int mb, int kk) __attribute__((always_inline)) {
+        if (mb < np64 * 2) {
+            const unsigned char* b = tilep + (mb >> 1) * 4096 + kk * 2048;
+            return join_tr(lds_read_tr16((const bf16_t*)(b + tr64[mb & 1][0])),
+                           lds_read_tr16((const bf16_t*)(b + tr64[mb & 1][1])));
+        }
+        const unsigned char* b = tilep + np64 * 4096 + kk * 1024;
+        return join_tr(lds_read_tr16((const bf16_t*)(b + tr32[0])), lds_read_tr16((const bf16_t*)(b + tr32[1])));
+    };
+    // operand n of the block in slot `slotp`; callers keep a rolling window opr[n % (LA + 1)]
+    auto read_op = [&](const unsigned char* slotp, int n) __attribute__((always_inline)) {
+        if (n < K::KS) return row_read(slotp, T1::NP64, n);
+        if (n < NA) return row_read(slotp + kOffT2, T2::NP64, n - K::KS);
+        if (n < NA + NO1) return tr_read(slotp, T1::NP64, (n - NA) >> 1, (n - NA) & 1);
+        return tr_read(slotp + kOffT2, T2::NP64, (n - NA - NO1) >> 1, (n - NA - NO1) & 1);
+    };
+
+    // ---- prologue: blocks 0..2 in flight, then the first operands of block 0 ----
+    issue_block(0, 0);
+    issue_block(1, 1);
+    issue_block(2, 2);
+    wait_vmcnt<0>();
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < LA; n++) opr[n] = read_op(smem, n);
+
+    for (int i = 0; i < nIt; i++) {
+        const int slot = i & (NSLOT - 1);
+        const unsigned char* slotp = smem + slot * kSlotBytes;
+        const unsigned char* nextp = smem + ((i + 1) & (NSLOT - 1)) * kSlotBytes;
+        const int sb0 = blk_of(i) * BT;      // first streamed row of the block
+
+        // ---------------- first half: S and dP chains ----------------
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int n = 0; n < NA; n++) {
+            opr[(n + LA) % (LA + 1)] = read_op(slotp, n + LA);   // n + LA < NOPS: the output operands follow
+            if (n < K::KS) s = mfma32(opr[n % (LA + 1)], l1reg[n], s);
+            else dp = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], dp);
+        }
+        // ---------------- P and dS in accumulator layout ----------------
+        // accumulator register r <-> streamed row sb0 + 8*(r/4) + 4*hf + (r%4), lane row ri
+        bf16x8 pb[2], dsb[2];
+        {
+            const bool need_mask = (sb0 + BT > N) ||
+                                   (CAUSAL && (DKV ? (sb0 < rw0 + 31) : (sb0 + BT - 1 > rw0)));
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                float lv[4], dv[4];
+                if (DKV) {
+                    const float4 x0 = *(const float4*)(slotp + kOffVec + (8 * g + 4 * hf) * 8);
+                    const float4 x1 = *(const float4*)(slotp + kOffVec + (8 * g + 4 * hf) * 8 + 16);
+                    lv[0] = x0.x; dv[0] = x0.y; lv[1] = x0.z; dv[1] = x0.w;
+                    lv[2] = x1.x; dv[2] = x1.y; lv[3] = x1.z; dv[3] = x1.w;
+                } else {
+#pragma unroll
+                    for (int x = 0; x < 4; x++) { lv[x] = my_lse2; dv[x] = my_d; }
+                }
+#pragma unroll
+                for (int x = 0; x < 4; x++) {
+                    const int r = 4 * g + x;
+                    float pr = fast_exp2(fmaf(s[r], kLog2e, -lv[x]));
+                    float ds = pr * (dp[r] - dv[x]);
+                    if (need_mask) {
+                        const int srow = sb0 + 8 * g + 4 * hf + x;
+                        const bool dead = srow >= N || (CAUSAL && (DKV ? (srow < ri) : (srow > ri)));
+                        if (dead) { pr = 0.f; ds = 0.f; }   // also discards the filler rows past N
+                    }
+                    if (DKV) pb[r / 8][r % 8] = (bf16_t)pr;
+                    dsb[r / 8][r % 8] = (bf16_t)ds;
+                }
+            }
+        }
+        // ---------------- block i+1 has landed; everyone has left block i-1 ----------------
+        wait_vmcnt_n(my_ndma);     // only the loads issued in the previous iteration may remain
+        __syncthreads();
+        issue_block(i + 3, (i + 3) & (NSLOT - 1));
+
+        // ---------------- second half: output chains ----------------
+        bf16x8 nxt[LA];      // first operands of block i+1 (the window restarts at 0 with every block)
+#pragma unroll
+        for (int n = NA; n < NOPS; n++) {
+            if (n + LA < NOPS) opr[(n + LA) % (LA + 1)] = read_op(slotp, n + LA);
+            else nxt[n + LA - NOPS] = read_op(nextp, n + LA - NOPS);
+            const int m = n - NA;
+            if (m < NO1) acc1[m >> 1] = mfma32(opr[n % (LA + 1)], dsb[m & 1], acc1[m >> 1]);
+            else acc2[(m - NO1) >> 1] = mfma32(opr[n % (LA + 1)], pb[(m - NO1) & 1], acc2[(m - NO1) >> 1]);
+        }
+#pragma unroll
+        for (int n = 0; n < LA; n++) opr[n] = nxt[n];
+    }
+    wait_vmcnt<0>();     // no direct load may outlive this tile's use of the ring
+    __syncthreads();
+
+    // ---- epilogue ----
+    const bool rok = ri < N;
+    const size_t base = (size_t)bh * N * C;
+    if (rok) {
+        if (DKV) {
+            bf16_t* dvg = (bf16_t*)p.dv + base + (size_t)ri * C;
+            bf16_t* dkg = (bf16_t*)p.dk + base + (size_t)ri * C;
+#pragma unroll
+            for (int mb = 0; mb < K::MBC; mb++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    bf16x4 a4, b4;
+#pragma unroll
+                    for (int x = 0; x < 4; x++) {
+                        a4[x] = (bf16_t)acc2[mb][4 * g + x];
+                        b4[x] = (bf16_t)acc1[mb][4 * g + x];
+                    }
+                    *(u32x2*)(dvg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, a4);
+                    *(u32x2*)(dkg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, b4);
+                }
+        } else {
+            bf16_t* dqg = (bf16_t*)p.dq + base + (size_t)ri * C;
+#pragma unroll
+            for (int mb = 0; mb < K::MBC; mb++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(acc1[mb][4 * g + x] * p.scale);
+                    *(u32x2*)(dqg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, o4);
+                }
+        }
+    }
+    if (RP > 0) {
+        const bool f32 = p.phi_f32 != 0;
+        const size_t esz = f32 ? 4 : 2;
+        float* scratch = (float*)smem + wave * 32 * (K::RP2 + 1);
+        unsigned char* dst = nullptr;
+        if (rok) dst = (unsigned char*)(DKV ? p.dphi_k : p.dphi_q) + ((size_t)bh * N + ri) * R * esz;
+        // the key-side limb order applies to the key's own gradient and vice versa
+        store_dphi<K::RP2, !DKV>(&acc1[K::MBC], scratch, dst, R, f32, l32, hf);
+    }
+}
+
+// Work units: one 128-row tile per workgroup, or when causal the tile pair (n-1-u, u), whose
+// streamed ranges add up to the same length for every u (no tail of heavy tiles).
+template <int C, int RP, bool CAUSAL, bool DKV>
+__global__ __launch_bounds__(kThreads, DKV ? 1 : 2) void bwd_main_kernel(BwdParams p, MainArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+    if (L >= p.total_tiles) return;
+    const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
+    const int bh = L / n_units;
+    const int u = L - bh * n_units;
+    if (CAUSAL) {
+        const int other = p.n_tiles - 1 - u;
+        // heavier tile first: high query tiles for dq, low key tiles for dkv
+        bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, DKV ? u : other);
+        if (u != other) {
+            __syncthreads();   // the epilogue's LDS scratch is reused as ring memory
+            bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, DKV ? other : u);
+        }
+    } else {
+        bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, u);
+    }
+}
+
+template <typename KernT>
+bool set_lds(KernT kern, size_t bytes, bool* done) {
+    if (*done) return true;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) !=
+        hipSuccess)
+        return false;
+    *done = true;
+    return true;
+}
+
+template <int C, int RP, bool CAUSAL>
+int launch(const BwdParams& pin, hipStream_t stream) {
+    using K = Cfg<C, RP>;
+    constexpr size_t ring_dq = (size_t)NSLOT * (K::T1::BYTES + K::T2::BYTES);
+    constexpr size_t ring_dkv = ring_dq + (size_t)NSLOT * K::kVecBytes;
+    constexpr size_t lds_dq = ring_dq > K::kEpiLds ? ring_dq : K::kEpiLds;
+    constexpr size_t lds_dkv = ring_dkv > K::kEpiLds ? ring_dkv : K::kEpiLds;
+    auto kdq = bwd_main_kernel<C, RP, CAUSAL, false>;
+    auto kdkv = bwd_main_kernel<C, RP, CAUSAL, true>;
+    static bool done_dq = false, done_dkv = false;
+    if (!set_lds(kdq, lds_dq, &done_dq) || !set_lds(kdkv, lds_dkv, &done_dkv)) return 1;
+
+    const long long rows = (long long)pin.B * pin.H * pin.N;
+    // workspace: vec [rows] float2 | Aq [rows][W] bf16 | Ak [rows][W] bf16  (each a multiple of 16 bytes)
+    unsigned char* ws = (unsigned char*)pin.delta;
+    MainArgs a;
+    a.vec = (const float2*)ws;
+    bf16_t* aq = (bf16_t*)(ws + (((size_t)rows * 8 + 15) & ~(size_t)15));
+    bf16_t* ak = aq + (size_t)rows * K::W;
+    a.aq = aq;
+    a.ak = ak;
+
+    const long long vthreads = rows * (C / 8);
+    hipLaunchKernelGGL((bwd_vec_kernel<C>), dim3((unsigned)((vthreads + 255) / 256)), dim3(256), 0, stream,
+                       (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
+    if (hipGetLastError() != hipSuccess) return 1;
+    const long long pthreads = rows * (K::W / 8);
+    hipLaunchKernelGGL((bwd_prep_kernel<C, RP>), dim3((unsigned)((pthreads + 255) / 256)), dim3(256), 0, stream,
+                       pin, aq, ak);
+    if (hipGetLastError() != hipSuccess) return 1;
+
+    BwdParams p = pin;
+    p.n_tiles = (p.N + 127) / 128;
+    const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
+    p.total_tiles = p.B * p.H * n_units;
+    p.tiles_per_xcd = (p.total_tiles + 7) / 8;
+    hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p, a);
+    if (hipGetLastError() != hipSuccess) return 1;
+    hipLaunchKernelGGL(kdq, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dq, stream, p, a);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+template <int C, int RP>
+int dispatch_causal(const BwdParams& p, hipStream_t stream) {
+    return p.causal ? launch<C, RP, true>(p, stream) : launch<C, RP, false>(p, stream);
+}
+
+template <int C>
+int dispatch_rp(const BwdParams& p, int rp, hipStream_t stream) {
+    switch (rp) {
+        case 0: return dispatch_causal<C, 0>(p, stream);
+        case 16: return dispatch_causal<C, 16>(p, stream);
+        case 32: return dispatch_causal<C, 32>(p, stream);
+        default: return -1;
+    }
+}
+
+}  // namespace
+
+size_t fb_bwd_stream_workspace_bytes(long long rows, int C, int R) {
+    const int w = C + (R > 0 ? 32 : 0);
+    return (((size_t)rows * 8 + 15) & ~(size_t)15) + (size_t)rows * w * 2 * 2;
+}
+
+int fb_launch_bwd_bf16_stream(const BwdParams& p, int C, int rp, hipStream_t stream) {
+    switch (C) {
+        case 32: return dispatch_rp<32>(p, rp, stream);
+        case 64: return dispatch_rp<64>(p, rp, stream);
+        case 128: return dispatch_rp<128>(p, rp, stream);
+        default: return -1;
+    }
+}

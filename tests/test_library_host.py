@@ -71,7 +71,8 @@ def test_dense_and_backward_argument_errors(lib):
     assert f(64, 64, 64, 64, 64, 64, 1, 1, 16, 96, 0, api.FB_BF16, 0, 0.0, None) == 3
     assert f(64, 64, 64, 68, 64, 64, 1, 1, 16, 64, 0, api.FB_BF16, 0, 0.0, None) == 4
     ws = lib.fb_lowrank_attn_bwd_workspace_bytes(2, 3, 100, 64, 8, api.FB_BF16)
-    assert ws == 2 * 3 * 100 * 4
+    # (lse, D) pairs plus the two concatenated operand copies of width C + 32
+    assert ws == 2 * 3 * 100 * 8 + 2 * (2 * 3 * 100) * (64 + 32) * 2
     assert lib.fb_lowrank_attn_bwd_workspace_bytes(0, 3, 100, 64, 8, api.FB_BF16) == 0
     g = lib.fb_lowrank_attn_bwd
     ptrs = [64] * 13
