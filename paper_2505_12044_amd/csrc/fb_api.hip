@@ -14,7 +14,6 @@ namespace {
 
 std::atomic<int> g_fwd_qb{0};   // 0 = choose automatically
 std::atomic<int> g_lds_pad{0};
-std::atomic<int> g_bwd_impl{1};  // 0 = tile-staged kernels, 1 = streamed kernels (default)
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -72,11 +71,6 @@ int fb_tune_set(const char* name, int value) {
     if (std::strcmp(name, "fwd_qb") == 0) {
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return FB_ERR_SHAPE;
         g_fwd_qb.store(value, std::memory_order_relaxed);
-        return FB_OK;
-    }
-    if (std::strcmp(name, "bwd_impl") == 0) {
-        if (value != 0 && value != 1) return FB_ERR_SHAPE;
-        g_bwd_impl.store(value, std::memory_order_relaxed);
         return FB_OK;
     }
     if (std::strcmp(name, "fwd_lds_pad") == 0) {
@@ -146,7 +140,7 @@ size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb
     (void)dtype;
     if (B <= 0 || H <= 0 || N <= 0) return 0;
     // (lse * log2 e, D) per row and the concatenated operand rows [q*scale | phi_q], [k | phi_k]
-    return fb_bwd_stream_workspace_bytes((long long)B * H * N, C, R);
+    return fb_bwd_workspace_bytes((long long)B * H * N, C, R);
 }
 
 int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
@@ -175,14 +169,12 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
     p.q = q; p.k = k; p.v = v; p.phi_q = phi_q; p.phi_k = phi_k;
     p.out = out; p.lse = lse; p.dout = dout;
     p.dq = dq; p.dk = dk; p.dv = dv; p.dphi_q = dphi_q; p.dphi_k = dphi_k;
-    p.delta = (float*)workspace;
+    p.workspace = workspace;
     p.B = B; p.H = H; p.N = N; p.R = R; p.causal = causal != 0;
     p.phi_f32 = phi_dtype == FB_F32;
     p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
-    const int rc = g_bwd_impl.load(std::memory_order_relaxed) == 1
-                       ? fb_launch_bwd_bf16_stream(p, C, rp, (hipStream_t)stream)
-                       : fb_launch_bwd_bf16(p, C, rp, (hipStream_t)stream);
+    const int rc = fb_launch_bwd_bf16(p, C, rp, (hipStream_t)stream);
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 

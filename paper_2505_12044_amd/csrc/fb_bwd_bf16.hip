@@ -5,25 +5,33 @@
 //   dV = P^T dO,  dP = dO V^T,  dS = P o (dP - D),  D_i = sum_c dO_ic O_ic,
 //   dAk = dS^T Aq  -> dK = dAk[:, :C],          dphi_k = dAk[:, C:],
 //   dAq = dS Ak    -> dQ = scale * dAq[:, :C],  dphi_q = dAq[:, C:].
-// The factor gradients are therefore extra columns of the contractions that give dK and
-// dQ; no N x N gradient is ever written.
+// The factor gradients are extra columns of the contractions that give dK and dQ; no N x N
+// gradient is ever written.  No atomics; results are deterministic.
 //
-// Three kernels, no atomics, deterministic:
-//   delta : D = rowsum(dO o O)
-//   dkv   : one workgroup per 128 keys (a key is a lane); loops over query tiles staged in
-//           LDS; recomputes S and dP, accumulates dV^T and dAk^T in registers
-//   dq    : one workgroup per 128 queries (a query is a lane); loops over key tiles staged
-//           in LDS; recomputes S and dP, accumulates dAq^T in registers
-// Both main kernels use the transposed orientation of the forward kernel: the
-// loop-invariant operand sits in registers, score-shaped accumulators feed the next MFMA
-// as its B operand without leaving registers, and the transposed A operands come from the
-// LDS transpose read.  Recomputing S and dP in both kernels costs 7 contractions instead
-// of 5 but needs no atomic accumulation of dQ.
+// Kernels:
+//   prep  : writes the concatenated operands Aq = [q*scale | phi_q | 0], Ak = [k | phi_k | 0]
+//           (bf16, width W = C + 32 when R > 0; fp32 factors as three bf16 limbs, six product
+//           columns per rank as in the forward) into the workspace
+//   vec   : (lse * log2 e, D) per query row
+//   main<DKV = true>  : a lane owns a key;   streams 32-query blocks; accumulates dV^T, dAk^T
+//   main<DKV = false> : a lane owns a query; streams 32-key blocks;   accumulates dAq^T
+// Both main kernels recompute S and dP (7 contractions instead of 5, but no atomic dQ).  They
+// use the transposed orientation of the forward: the lane-side operands stay in registers,
+// score-shaped accumulators feed the next MFMA as its B operand without leaving registers,
+// and the transposed A operands come from the LDS transpose read.
 //
-// fp32 factors are handled as in the forward (three bf16 limbs, six product columns per
-// rank); the gradient of a factor is the sum of the accumulator columns that multiply its
-// distinct limbs on the other side.
+// Streaming.  Because prep has already built the operand rows, a streamed block is a pure
+// copy, done with direct-to-LDS loads (global_load_lds_dwordx4 from inline assembly, see
+// fb_fwd_bf16_dma.h for why) into a ring of four block slots; nothing passes through
+// registers.  One barrier per iteration, in the middle:
+//     S, dP chains of block i | exp / dS | wait, barrier | issue block i+3 |
+//     output chains of block i, first operand reads of block i+1
+// A direct load writes 64 consecutive 16-byte pieces, so a 32-row tile of width W is kept as
+// W/64 panels [32][64] (and one [32][32] panel if W % 64), each unpadded with an XOR chunk
+// swizzle that makes both the row reads and the transpose reads bank-conflict free.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "fb_device.h"
 #include "fb_launch.h"
@@ -33,14 +41,111 @@ namespace {
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
+constexpr int BT = 32;       // streamed rows per block
+constexpr int NSLOT = 4;       // ring slots of the dq kernel
+constexpr int NSLOT_DKV = 5;   // ring slots of the dkv kernel (a block is used in two iterations)
+
+FB_DEV int swz64(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
+FB_DEV int swz32(int r) { return (r >> 2) & 3; }
+
+// s_waitcnt with only vmcnt constrained
+template <int N>
+FB_DEV void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+FB_DEV void wait_vmcnt_n(int n) {   // n is wave-uniform, 0..7
+    switch (n) {
+        case 0: wait_vmcnt<0>(); break;
+        case 1: wait_vmcnt<1>(); break;
+        case 2: wait_vmcnt<2>(); break;
+        case 3: wait_vmcnt<3>(); break;
+        case 4: wait_vmcnt<4>(); break;
+        case 5: wait_vmcnt<5>(); break;
+        case 6: wait_vmcnt<6>(); break;
+        default: wait_vmcnt<7>(); break;
+    }
+}
+
+// lane l reads sbase + voff (bytes); its 16 bytes land at LDS byte address lds_addr + 16 * l
+FB_DEV void dma16(const void* sbase, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+
+// 32-row tile of W bf16 columns stored as panels (see the header comment)
+template <int W>
+struct Tile {
+    static constexpr int NP64 = W / 64;
+    static constexpr bool HAS32 = (W % 64) != 0;
+    static constexpr int BYTES = W * 64;
+    static constexpr int NDMA = NP64 * 4 + (HAS32 ? 2 : 0);   // direct loads per tile
+    // direct load d of the tile: row and 16-byte source chunk fetched by `lane`, LDS offset of the load
+    FB_DEV static void dma_map(int d, int lane, int& row, int& chunk, int& dst) {
+        if (d < NP64 * 4) {
+            row = (d & 3) * 8 + (lane >> 3);
+            chunk = (d >> 2) * 8 + ((lane & 7) ^ swz64(row));
+            dst = (d >> 2) * 4096 + (d & 3) * 1024;
+        } else {
+            const int e = d - NP64 * 4;
+            row = e * 16 + (lane >> 2);
+            chunk = NP64 * 8 + ((lane & 3) ^ swz32(row));
+            dst = NP64 * 4096 + e * 1024;
+        }
+    }
+};
+
+template <int C, int RP>
+struct Cfg {
+    static constexpr int RP2 = RP > 0 ? 32 : 0;        // factor columns kept in the workspace rows
+    static constexpr int W = C + RP2;
+    static constexpr int KS = (C + RP) / 16;           // k-steps of the score contraction
+    static constexpr int CS = C / 16;                  // k-steps of the dP contraction
+    static constexpr int MB = W / 32;                  // 32-column blocks of dAq / dAk
+    static constexpr int MBC = C / 32;
+    using T1 = Tile<W>;
+    using T2 = Tile<C>;
+    static constexpr int kVecBytes = 1024;             // (lse2, D) of 32 rows in the first 256 bytes
+    static constexpr size_t kEpiLds = (size_t)kWaves * 32 * (RP2 + 1) * sizeof(float);
+};
 
 // ------------------------------------------------------------------------------------------
-// delta
+// prep / vec
 // ------------------------------------------------------------------------------------------
+template <int C, int RP>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __restrict__ aq,
+                                                       bf16_t* __restrict__ ak) {
+    using K = Cfg<C, RP>;
+    constexpr int CPR = K::W / 8;
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long row = gid / CPR;                        // (b*H + h)*N + i
+    const int c = (int)(gid - row * CPR);
+    const long long rows = (long long)p.B * p.H * p.N;
+    if (row >= rows) return;
+    bf16x8 a, b;
+    if (c < C / 8) {
+        const bf16x8 x = as_bf16x8(*(const u32x4*)((const bf16_t*)p.q + row * C + c * 8));
+#pragma unroll
+        for (int e = 0; e < 8; e++) a[e] = (bf16_t)((float)x[e] * p.scale);
+        b = as_bf16x8(*(const u32x4*)((const bf16_t*)p.k + row * C + c * 8));
+    } else {
+        const bool f32 = p.phi_f32 != 0;
+        const size_t esz = f32 ? 4 : 2;
+        const long long bh = row / p.N;
+        const int i = (int)(row - bh * p.N);
+        const int bb = (int)(bh / p.H), h = (int)(bh - (long long)bb * p.H);
+        const size_t off = ((size_t)bb * p.phi_bstride + ((size_t)h * p.N + i) * p.R) * esz;
+        a = phi_chunk_gather<true>((const unsigned char*)p.phi_q + off, c - C / 8, p.R, f32);
+        b = phi_chunk_gather<false>((const unsigned char*)p.phi_k + off, c - C / 8, p.R, f32);
+    }
+    *(u32x4*)(aq + row * K::W + c * 8) = as_uint4(a);
+    *(u32x4*)(ak + row * K::W + c * 8) = as_uint4(b);
+}
+
 template <int C>
-__global__ __launch_bounds__(256) void bwd_delta_kernel(const bf16_t* __restrict__ out,
-                                                        const bf16_t* __restrict__ dout,
-                                                        float* __restrict__ delta, long long rows) {
+__global__ __launch_bounds__(256) void bwd_vec_kernel(const bf16_t* __restrict__ out,
+                                                      const bf16_t* __restrict__ dout,
+                                                      const float* __restrict__ lse,
+                                                      float2* __restrict__ vec, long long rows) {
     constexpr int LPR = C / 8;   // lanes per row, 16 bytes each
     const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
     const long long row = gid / LPR;
@@ -54,36 +159,15 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const bf16_t* __restrict
     }
 #pragma unroll
     for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-    if (c8 == 0 && row < rows) delta[row] = acc;
+    if (c8 == 0 && row < rows) vec[row] = make_float2(lse[row] * kLog2e, acc);
 }
-
-template <int C, int RP>
-struct BwdCfg {
-    static constexpr int RP2 = (RP + 31) / 32 * 32;   // factor width padded to whole 32-row MFMA blocks
-    static constexpr int KS = (C + RP) / 16;          // k-steps of the score contraction
-    static constexpr int W2 = C + RP2;
-    static constexpr int MB = W2 / 32;                // 32-column blocks of dAq / dAk
-    static constexpr int MBC = C / 32;
-    static constexpr int AP = W2 + 8;                 // pitch of the [x | phi] tile
-    static constexpr int DP = C + 8;                  // pitch of the plain tile (V or dO)
-    static constexpr int T = 64;                      // rows per streamed LDS tile
-    static constexpr int XCH = T * C / 8;
-    static constexpr int XIT = XCH / kThreads;
-    static constexpr int PCH = T * RP2 / 8;
-    static constexpr int PIT = (PCH + kThreads - 1) / kThreads;
-    static constexpr size_t kTileLds = (size_t)2 * T * (AP + DP) * 2;
-    static constexpr size_t kVecLds = (size_t)2 * 2 * T * sizeof(float);   // dkv: lse, D per tile
-    static constexpr size_t kEpiLds = (size_t)kWaves * 32 * (RP2 + 1) * sizeof(float);
-    static_assert(XCH % kThreads == 0, "tile must split evenly");
-};
 
 // Write one wave's factor-gradient columns to LDS scratch and reduce limb columns.
 // acc[mb] holds columns mb*32 + 8*g + 4*hf + x (register 4*g + x) for row l32.
-template <int C, int RP, bool QSIDE>
+template <int RP2, bool QSIDE>
 FB_DEV void store_dphi(const f32x16* acc_phi /* [RP2/32] */, float* scratch /* wave-private [32][RP2+1] */,
                        void* dst_row /* gradient row of this lane's token or null */, int R,
                        bool f32, int l32, int hf) {
-    constexpr int RP2 = BwdCfg<C, RP>::RP2;
 #pragma unroll
     for (int mb = 0; mb < RP2 / 32; mb++)
 #pragma unroll
@@ -107,457 +191,459 @@ FB_DEV void store_dphi(const f32x16* acc_phi /* [RP2/32] */, float* scratch /* w
 }
 
 // ------------------------------------------------------------------------------------------
-// dq kernel: lane = query
+// main kernel.  "lane side" = the 128 rows owned by the workgroup (keys when DKV, else
+// queries); "streamed side" = the other index, walked in blocks of 32 rows.
+//   T1 tile: rows of the streamed operand of S (Aq when DKV, else Ak), width W
+//   T2 tile: rows of the streamed operand of dP (dO when DKV, else V), width C
 // ------------------------------------------------------------------------------------------
-template <int C, int RP, bool CAUSAL>
-__global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
-    using K = BwdCfg<C, RP>;
-    constexpr int BK = K::T, BQ = kWaves * 32;
-    extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t* const kt = (bf16_t*)smem;            // [2][BK][AP]  = [k | phi_k | 0]
-    bf16_t* const vt = kt + 2 * BK * K::AP;      // [2][BK][DP]
+struct MainArgs {
+    const bf16_t* aq;     // [B*H*N][W]
+    const bf16_t* ak;     // [B*H*N][W]
+    const float2* vec;    // [B*H*N]  (lse * log2 e, D)
+};
 
-    const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
-    if (L >= p.total_tiles) return;
-    const int bh = L / p.n_tiles;
-    int qt = L - bh * p.n_tiles;
-    if (CAUSAL) qt = p.n_tiles - 1 - qt;
-    const int b = bh / p.H, h = bh - b * p.H;
+template <int C, int RP, bool CAUSAL, bool DKV>
+FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem, const int bh, const int tile) {
+    using K = Cfg<C, RP>;
+    using T1 = typename K::T1;
+    using T2 = typename K::T2;
+    constexpr int kSlotBytes = T1::BYTES + T2::BYTES + (DKV ? K::kVecBytes : 0);
+    constexpr int kOffT2 = T1::BYTES, kOffVec = T1::BYTES + T2::BYTES;
+    constexpr int ND = T1::NDMA + T2::NDMA + (DKV ? 1 : 0);       // direct loads per block
+    constexpr int NDW = (ND + kWaves - 1) / kWaves;               // ... per wave, at most
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
     const int N = p.N, R = p.R;
-    const bool phi_f32 = p.phi_f32 != 0;
-    const size_t phi_esz = phi_f32 ? 4 : 2;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hf = lane >> 5;
-    const int q0 = qt * BQ;
-    const int qi = q0 + wave * 32 + l32;
-    const bool qok = qi < N;
+    const int r0 = tile * 128;            // first lane-side row of the workgroup
+    const int rw0 = r0 + wave * 32;       // ... of this wave
+    const int ri = rw0 + l32;             // this lane's row
+    const int rc = min(ri, N - 1);        // rows past N compute on row N-1 and are not stored
 
-    const size_t base = (size_t)bh * N * C;
-    const bf16_t* qg = (const bf16_t*)p.q + base;
-    const bf16_t* kg = (const bf16_t*)p.k + base;
-    const bf16_t* vg = (const bf16_t*)p.v + base;
-    const bf16_t* dog = (const bf16_t*)p.dout + base;
-    const unsigned char* pqg = nullptr;
-    const unsigned char* pkg = nullptr;
-    if (RP > 0) {
-        const size_t pbase = ((size_t)b * p.phi_bstride + (size_t)h * N * R) * phi_esz;
-        pqg = (const unsigned char*)p.phi_q + pbase;
-        pkg = (const unsigned char*)p.phi_k + pbase;
+    const size_t rowbase = (size_t)bh * N;
+    const bf16_t* l1g = (DKV ? a.ak : a.aq) + rowbase * K::W;                       // lane-side operand of S
+    const bf16_t* l2g = (const bf16_t*)(DKV ? p.v : p.dout) + rowbase * C;          // lane-side operand of dP
+    const bf16_t* t1g = (DKV ? a.aq : a.ak) + rowbase * K::W;                       // streamed
+    const bf16_t* t2g = (const bf16_t*)(DKV ? p.dout : p.v) + rowbase * C;
+    const float2* vecg = a.vec + rowbase;
+
+    // ---- lane-side operands, loop invariant ----
+    bf16x8 l1reg[K::KS], l2reg[K::CS];
+#pragma unroll
+    for (int ks = 0; ks < K::KS; ks++)
+        l1reg[ks] = as_bf16x8(*(const u32x4*)(l1g + (size_t)rc * K::W + ks * 16 + 8 * hf));
+#pragma unroll
+    for (int cs = 0; cs < K::CS; cs++)
+        l2reg[cs] = as_bf16x8(*(const u32x4*)(l2g + (size_t)rc * C + cs * 16 + 8 * hf));
+    float my_lse2 = 0.f, my_d = 0.f;
+    if (!DKV) {
+        const float2 v2 = vecg[rc];
+        my_lse2 = v2.x;
+        my_d = v2.y;
     }
 
-    // loop-invariant operands of this lane's query
-    bf16x8 qreg[K::KS], doreg[C / 16];
-#pragma unroll
-    for (int ks = 0; ks < K::KS; ks++) {
-        bf16x8 val;
-        if (ks < C / 16) {
-            u32x4 raw = u32x4{0u, 0u, 0u, 0u};
-            if (qok) raw = *(const u32x4*)(qg + (size_t)qi * C + ks * 16 + 8 * hf);
-            const bf16x8 x = as_bf16x8(raw);
-#pragma unroll
-            for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
-        } else {
-            const int c8 = (ks - C / 16) * 2 + hf;
-            if (qok) {
-                val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
-            }
-        }
-        qreg[ks] = val;
-    }
-#pragma unroll
-    for (int cs = 0; cs < C / 16; cs++) {
-        u32x4 raw = u32x4{0u, 0u, 0u, 0u};
-        if (qok) raw = *(const u32x4*)(dog + (size_t)qi * C + cs * 16 + 8 * hf);
-        doreg[cs] = as_bf16x8(raw);
-    }
-    const float lse2 = qok ? p.lse[(size_t)bh * N + qi] * kLog2e : INFINITY;
-    const float dlt = qok ? p.delta[(size_t)bh * N + qi] : 0.f;
-
-    f32x16 dacc[K::MB];
-#pragma unroll
-    for (int mb = 0; mb < K::MB; mb++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) dacc[mb][r] = 0.f;
-
-    const int kend = CAUSAL ? min(N, q0 + BQ) : N;
-    const int nT = (kend + BK - 1) / BK;
-
-    u32x4 kraw[K::XIT], vraw[K::XIT];
-    u32x4 praw[K::PIT > 0 ? K::PIT : 1];
-
-    auto load_tile = [&](int t) {
-        const int k0 = t * BK;
-#pragma unroll
-        for (int it = 0; it < K::XIT; it++) {
-            const int e = tid + it * kThreads;
-            const int row = e / (C / 8), c8 = e % (C / 8);
-            const int j = k0 + row;
-            u32x4 a = u32x4{0u, 0u, 0u, 0u}, bb = a;
-            if (j < N) {
-                a = *(const u32x4*)(kg + (size_t)j * C + c8 * 8);
-                bb = *(const u32x4*)(vg + (size_t)j * C + c8 * 8);
-            }
-            kraw[it] = a;
-            vraw[it] = bb;
-        }
-        if (RP > 0) {
-#pragma unroll
-            for (int it = 0; it < K::PIT; it++) {
-                const int e = tid + it * kThreads;
-                if (e < K::PCH) {
-                    const int row = e / (K::RP2 / 8), c8 = e % (K::RP2 / 8);
-                    const int j = k0 + row;
-                    praw[it] = phi_chunk_raw(pkg + (size_t)j * R * phi_esz, c8, R, phi_f32, j < N);
-                }
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        bf16_t* kdst = kt + buf * BK * K::AP;
-        bf16_t* vdst = vt + buf * BK * K::DP;
-#pragma unroll
-        for (int it = 0; it < K::XIT; it++) {
-            const int e = tid + it * kThreads;
-            const int row = e / (C / 8), c8 = e % (C / 8);
-            *(u32x4*)(kdst + row * K::AP + c8 * 8) = kraw[it];
-            *(u32x4*)(vdst + row * K::DP + c8 * 8) = vraw[it];
-        }
-        if (RP > 0) {
-#pragma unroll
-            for (int it = 0; it < K::PIT; it++) {
-                const int e = tid + it * kThreads;
-                if (e < K::PCH) {
-                    const int row = e / (K::RP2 / 8), c8 = e % (K::RP2 / 8);
-                    *(u32x4*)(kdst + row * K::AP + C + c8 * 8) =
-                        as_uint4(phi_chunk_finish<false>(praw[it], c8, phi_f32));
-                }
-            }
-        }
-    };
-
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    const int i16 = lane & 15, blk = l32 >> 4;
-    for (int t = 0; t < nT; t++) {
-        const bool more = t + 1 < nT;
-        if (more) load_tile(t + 1);
-        const bf16_t* ksrc = kt + (t & 1) * BK * K::AP;
-        const bf16_t* vsrc = vt + (t & 1) * BK * K::DP;
-        const int k0 = t * BK;
-#pragma unroll
-        for (int kb = 0; kb < BK / 32; kb++) {
-            const int kb0 = k0 + kb * 32;
-            if (CAUSAL && kb0 > q0 + wave * 32 + 31) continue;
-            f32x16 s, dp;
-#pragma unroll
-            for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
-            const bf16_t* krow = ksrc + (kb * 32 + l32) * K::AP + 8 * hf;
-            const bf16_t* vrow = vsrc + (kb * 32 + l32) * K::DP + 8 * hf;
-#pragma unroll
-            for (int ks = 0; ks < K::KS; ks++)
-                s = mfma32(as_bf16x8(*(const u32x4*)(krow + ks * 16)), qreg[ks], s);
-#pragma unroll
-            for (int cs = 0; cs < C / 16; cs++)
-                dp = mfma32(as_bf16x8(*(const u32x4*)(vrow + cs * 16)), doreg[cs], dp);
-
-            bf16x8 dsb[2];
-            const bool need_mask = (CAUSAL && kb0 + 31 > q0 + wave * 32) || kb0 + 32 > N;
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                float pr = fast_exp2(fmaf(s[r], kLog2e, -lse2));
-                if (need_mask) {
-                    const int key = kb0 + 8 * (r / 4) + 4 * hf + (r % 4);
-                    if (key >= N || (CAUSAL && key > qi)) pr = 0.f;
-                }
-                dsb[r / 8][r % 8] = (bf16_t)(pr * (dp[r] - dlt));
-            }
-            // dAq^T[col][query] += Ak^T[col][key] dS^T[key][query]
-            const bf16_t* kbase = ksrc + (kb * 32 + 4 * hf + (i16 >> 2)) * K::AP + 16 * blk + 4 * (i16 & 3);
-#pragma unroll
-            for (int mb = 0; mb < K::MB; mb++) {
-#pragma unroll
-                for (int kk = 0; kk < 2; kk++) {
-                    const bf16_t* ap = kbase + (kk * 16) * K::AP + mb * 32;
-                    const bf16x8 a = join_tr(lds_read_tr16(ap), lds_read_tr16(ap + 8 * K::AP));
-                    dacc[mb] = mfma32(a, dsb[kk], dacc[mb]);
-                }
-            }
-        }
-        if (more) store_tile((t + 1) & 1);
-        __syncthreads();
-    }
-
-    // dQ = scale * dAq[:, :C]
-    if (qok) {
-        bf16_t* dqg = (bf16_t*)p.dq + base + (size_t)qi * C;
-#pragma unroll
-        for (int mb = 0; mb < K::MBC; mb++)
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                bf16x4 o4;
-#pragma unroll
-                for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(dacc[mb][4 * g + x] * p.scale);
-                *(u32x2*)(dqg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, o4);
-            }
-    }
-    if (RP > 0) {
-        float* scratch = (float*)smem + wave * 32 * (K::RP2 + 1);
-        unsigned char* dst = nullptr;
-        if (qok) dst = (unsigned char*)p.dphi_q + ((size_t)bh * N + qi) * R * phi_esz;
-        store_dphi<C, RP, true>(&dacc[K::MBC], scratch, dst, R, phi_f32, l32, hf);
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// dkv kernel: lane = key
-// ------------------------------------------------------------------------------------------
-template <int C, int RP, bool CAUSAL>
-__global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdParams p) {
-    using K = BwdCfg<C, RP>;
-    constexpr int BQ = K::T, BKW = kWaves * 32;
-    extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t* const at = (bf16_t*)smem;             // [2][BQ][AP] = [q*scale | phi_q | 0]
-    bf16_t* const dt = at + 2 * BQ * K::AP;       // [2][BQ][DP] = dO
-    float* const vec = (float*)(dt + 2 * BQ * K::DP);   // [2][2][BQ]: lse*log2e, D
-
-    const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
-    if (L >= p.total_tiles) return;
-    const int bh = L / p.n_tiles;
-    const int kt_idx = L - bh * p.n_tiles;        // causal: small key index = most work, first
-    const int b = bh / p.H, h = bh - b * p.H;
-    const int N = p.N, R = p.R;
-    const bool phi_f32 = p.phi_f32 != 0;
-    const size_t phi_esz = phi_f32 ? 4 : 2;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hf = lane >> 5;
-    const int k0 = kt_idx * BKW;
-    const int kw0 = k0 + wave * 32;
-    const int ki = kw0 + l32;
-    const bool kok = ki < N;
-
-    const size_t base = (size_t)bh * N * C;
-    const bf16_t* qg = (const bf16_t*)p.q + base;
-    const bf16_t* kg = (const bf16_t*)p.k + base;
-    const bf16_t* vg = (const bf16_t*)p.v + base;
-    const bf16_t* dog = (const bf16_t*)p.dout + base;
-    const float* lseg = p.lse + (size_t)bh * N;
-    const float* dltg = p.delta + (size_t)bh * N;
-    const unsigned char* pqg = nullptr;
-    const unsigned char* pkg = nullptr;
-    if (RP > 0) {
-        const size_t pbase = ((size_t)b * p.phi_bstride + (size_t)h * N * R) * phi_esz;
-        pqg = (const unsigned char*)p.phi_q + pbase;
-        pkg = (const unsigned char*)p.phi_k + pbase;
-    }
-
-    bf16x8 akreg[K::KS], vreg[C / 16];
-#pragma unroll
-    for (int ks = 0; ks < K::KS; ks++) {
-        bf16x8 val;
-        if (ks < C / 16) {
-            u32x4 raw = u32x4{0u, 0u, 0u, 0u};
-            if (kok) raw = *(const u32x4*)(kg + (size_t)ki * C + ks * 16 + 8 * hf);
-            val = as_bf16x8(raw);
-        } else {
-            const int c8 = (ks - C / 16) * 2 + hf;
-            if (kok) {
-                val = phi_chunk_gather<false>(pkg + (size_t)ki * R * phi_esz, c8, R, phi_f32);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
-            }
-        }
-        akreg[ks] = val;
-    }
-#pragma unroll
-    for (int cs = 0; cs < C / 16; cs++) {
-        u32x4 raw = u32x4{0u, 0u, 0u, 0u};
-        if (kok) raw = *(const u32x4*)(vg + (size_t)ki * C + cs * 16 + 8 * hf);
-        vreg[cs] = as_bf16x8(raw);
-    }
-
-    f32x16 dvacc[K::MBC], dkacc[K::MB];
+    f32x16 acc1[K::MB];                 // dAk^T or dAq^T
+    f32x16 acc2[DKV ? K::MBC : 1];      // dV^T
 #pragma unroll
     for (int r = 0; r < 16; r++) {
 #pragma unroll
-        for (int mb = 0; mb < K::MBC; mb++) dvacc[mb][r] = 0.f;
+        for (int mb = 0; mb < K::MB; mb++) acc1[mb][r] = 0.f;
 #pragma unroll
-        for (int mb = 0; mb < K::MB; mb++) dkacc[mb][r] = 0.f;
+        for (int mb = 0; mb < (DKV ? K::MBC : 1); mb++) acc2[mb][r] = 0.f;
     }
 
-    const int nQT = (N + BQ - 1) / BQ;
-    const int t0 = CAUSAL ? k0 / BQ : 0;
-
-    u32x4 qraw[K::XIT], draw[K::XIT];
-    u32x4 praw[K::PIT > 0 ? K::PIT : 1];
-    float vecraw = 0.f;
-
-    auto load_tile = [&](int t) {
-        const int r0 = t * BQ;
-#pragma unroll
-        for (int it = 0; it < K::XIT; it++) {
-            const int e = tid + it * kThreads;
-            const int row = e / (C / 8), c8 = e % (C / 8);
-            const int i = r0 + row;
-            u32x4 a = u32x4{0u, 0u, 0u, 0u}, bb = a;
-            if (i < N) {
-                a = *(const u32x4*)(qg + (size_t)i * C + c8 * 8);
-                bb = *(const u32x4*)(dog + (size_t)i * C + c8 * 8);
-            }
-            qraw[it] = a;
-            draw[it] = bb;
-        }
-        if (RP > 0) {
-#pragma unroll
-            for (int it = 0; it < K::PIT; it++) {
-                const int e = tid + it * kThreads;
-                if (e < K::PCH) {
-                    const int row = e / (K::RP2 / 8), c8 = e % (K::RP2 / 8);
-                    const int i = r0 + row;
-                    praw[it] = phi_chunk_raw(pqg + (size_t)i * R * phi_esz, c8, R, phi_f32, i < N);
-                }
-            }
-        }
-        if (tid < 2 * BQ) {
-            const int i = r0 + (tid & (BQ - 1));
-            if (tid < BQ) vecraw = i < N ? lseg[i] : INFINITY;   // rows past N get P = 0
-            else vecraw = i < N ? dltg[i] : 0.f;
-        }
-    };
-    auto store_tile = [&](int buf) {
-        bf16_t* adst = at + buf * BQ * K::AP;
-        bf16_t* ddst = dt + buf * BQ * K::DP;
-#pragma unroll
-        for (int it = 0; it < K::XIT; it++) {
-            const int e = tid + it * kThreads;
-            const int row = e / (C / 8), c8 = e % (C / 8);
-            const bf16x8 x = as_bf16x8(qraw[it]);
-            bf16x8 y;
-#pragma unroll
-            for (int z = 0; z < 8; z++) y[z] = (bf16_t)((float)x[z] * p.scale);
-            *(u32x4*)(adst + row * K::AP + c8 * 8) = as_uint4(y);
-            *(u32x4*)(ddst + row * K::DP + c8 * 8) = draw[it];
-        }
-        if (RP > 0) {
-#pragma unroll
-            for (int it = 0; it < K::PIT; it++) {
-                const int e = tid + it * kThreads;
-                if (e < K::PCH) {
-                    const int row = e / (K::RP2 / 8), c8 = e % (K::RP2 / 8);
-                    *(u32x4*)(adst + row * K::AP + C + c8 * 8) =
-                        as_uint4(phi_chunk_finish<true>(praw[it], c8, phi_f32));
-                }
-            }
-        }
-        if (tid < 2 * BQ) {
-            float* d = vec + buf * 2 * BQ + tid;      // [0,BQ): lse*log2e, [BQ,2BQ): D
-            *d = tid < BQ ? vecraw * kLog2e : vecraw;
-        }
-    };
-
-    if (t0 < nQT) {
-        load_tile(t0);
-        store_tile(t0 & 1);
+    // ---- streamed block range ----
+    const int nblk_all = (N + BT - 1) / BT;
+    int b_begin = 0, b_end = nblk_all;
+    if (CAUSAL) {
+        if (DKV) b_begin = r0 / BT;                            // queries before the first key see nothing
+        else b_end = min(nblk_all, (min(N, r0 + 128) + BT - 1) / BT);
     }
-    __syncthreads();
+    const int nIt = b_end - b_begin;
+    auto blk_of = [&](int i) __attribute__((always_inline)) { return min(b_begin + i, nblk_all - 1); };
 
-    const int i16 = lane & 15, blk = l32 >> 4;
-    for (int t = t0; t < nQT; t++) {
-        const bool more = t + 1 < nQT;
-        if (more) load_tile(t + 1);
-        const bf16_t* asrc = at + (t & 1) * BQ * K::AP;
-        const bf16_t* dsrc = dt + (t & 1) * BQ * K::DP;
-        const float* lsrc = vec + (t & 1) * 2 * BQ;
-        const float* esrc = lsrc + BQ;
+    // ---- this wave's share of a block's direct loads: load d = wave + 4*j, j < my_ndma ----
+    // wave-uniform per load: source array, bytes per block and per row, LDS offset inside a slot;
+    // per lane: source row (a chunk index for the vec rows) and byte offset inside the row
+    int dma_row[NDW];
+    unsigned dma_col[NDW];
+    const unsigned char* dma_src[NDW];
+    int dma_bstride[NDW], dma_pitch[NDW], dma_lshift[NDW], dma_dst[NDW];
 #pragma unroll
-        for (int qb = 0; qb < BQ / 32; qb++) {
-            const int qb0 = t * BQ + qb * 32;
-            if (CAUSAL && qb0 + 31 < kw0) continue;    // every query of the block precedes this wave's keys
+    for (int j = 0; j < NDW; j++) {
+        const int d = wave + kWaves * j;
+        int row = 0, chunk = 0, dst = 0;
+        if (d < T1::NDMA) {
+            T1::dma_map(d, lane, row, chunk, dst);
+            dma_src[j] = (const unsigned char*)t1g;
+            dma_bstride[j] = BT * K::W * 2; dma_pitch[j] = K::W * 2; dma_lshift[j] = 0;
+            dma_col[j] = (unsigned)chunk * 16u;
+            dma_dst[j] = dst;
+        } else if (d < T1::NDMA + T2::NDMA) {
+            T2::dma_map(d - T1::NDMA, lane, row, chunk, dst);
+            dma_src[j] = (const unsigned char*)t2g;
+            dma_bstride[j] = BT * C * 2; dma_pitch[j] = C * 2; dma_lshift[j] = 0;
+            dma_col[j] = (unsigned)chunk * 16u;
+            dma_dst[j] = kOffT2 + dst;
+        } else {
+            // vec: 32 rows x 8 bytes = 16 chunks of two rows; the other lanes repeat chunk 15
+            row = min(lane, 15);
+            dma_src[j] = (const unsigned char*)vecg;
+            dma_bstride[j] = BT * 8; dma_pitch[j] = 16; dma_lshift[j] = 1;
+            dma_col[j] = 0u;
+            dma_dst[j] = kOffVec;
+        }
+        dma_row[j] = row;
+    }
+    const int my_ndma = (ND - wave + kWaves - 1) / kWaves;     // wave-uniform: NDW or NDW - 1
+    auto issue_block = [&](int i, int slot) __attribute__((always_inline)) {
+        const int blk = blk_of(i);
+        const int left = N - blk * BT - 1;     // last valid row inside the block; rows past it repeat it
+        const unsigned sbase = lds0 + slot * kSlotBytes;
+#pragma unroll
+        for (int j = 0; j < NDW; j++) {
+            if (j < my_ndma) {
+                const unsigned voff = (unsigned)(min(dma_row[j], left >> dma_lshift[j]) * dma_pitch[j]) + dma_col[j];
+                dma16(dma_src[j] + (size_t)blk * dma_bstride[j], voff, sbase + dma_dst[j]);
+            }
+        }
+    };
+    auto wait_prev_loads = [&]() __attribute__((always_inline)) {   // all but the newest block's loads
+        if (my_ndma == NDW) wait_vmcnt<NDW>();
+        else wait_vmcnt<NDW - 1>();
+    };
+
+    // ---- per-lane LDS read offsets (bytes inside a panel) ----
+    int rb64[4], rb32[2];                 // row operand, k-step j of a panel: 16 bytes at row l32
+#pragma unroll
+    for (int j = 0; j < 4; j++) rb64[j] = l32 * 128 + (((2 * j + hf) ^ swz64(l32)) << 4);
+#pragma unroll
+    for (int j = 0; j < 2; j++) rb32[j] = l32 * 64 + (((2 * j + hf) ^ swz32(l32)) << 4);
+    const int i16 = lane & 15, blk16 = l32 >> 4;
+    int tr64[2][2], tr32[2];              // transpose reads: 32-column block m of a panel, half hi
+#pragma unroll
+    for (int hi = 0; hi < 2; hi++) {
+        const int row = 8 * hi + 4 * hf + (i16 >> 2);
+#pragma unroll
+        for (int m = 0; m < 2; m++)
+            tr64[m][hi] = row * 128 + (((m * 4 + 2 * blk16 + ((i16 & 3) >> 1)) ^ swz64(row)) << 4) + (i16 & 1) * 8;
+        tr32[hi] = row * 64 + (((2 * blk16 + ((i16 & 3) >> 1)) ^ swz32(row)) << 4) + (i16 & 1) * 8;
+    }
+    // The same offsets with a slot's byte offset added, built once per block instead of once per
+    // read (the slot is a run-time value, the rest of a read's address is an immediate).
+    constexpr bool ANY64 = T1::NP64 > 0 || T2::NP64 > 0;
+    constexpr bool ANY32 = T1::HAS32 || T2::HAS32;
+    struct RowBase { int b64[4]; int b32[2]; };
+    struct TrBase { int t64[2][2]; int t32[2]; };
+    auto mk_row = [&](int off) __attribute__((always_inline)) {
+        RowBase r;
+#pragma unroll
+        for (int j = 0; j < 4; j++) r.b64[j] = ANY64 ? rb64[j] + off : 0;
+#pragma unroll
+        for (int j = 0; j < 2; j++) r.b32[j] = ANY32 ? rb32[j] + off : 0;
+        return r;
+    };
+    auto mk_tr = [&](int off) __attribute__((always_inline)) {
+        TrBase t;
+#pragma unroll
+        for (int hi = 0; hi < 2; hi++) {
+#pragma unroll
+            for (int m = 0; m < 2; m++) t.t64[m][hi] = ANY64 ? tr64[m][hi] + off : 0;
+            t.t32[hi] = ANY32 ? tr32[hi] + off : 0;
+        }
+        return t;
+    };
+    // operand n of a block, in consumption order:
+    //   [0, KS)            S   k-step n          row read of T1
+    //   [KS, KS+CS)        dP  k-step n-KS       row read of T2
+    //   then NO1 = 2*MB    output 1, (mb, kk)    transpose read of T1
+    //   then NO2 = 2*MBC   output 2 (DKV only)   transpose read of T2
+    constexpr int NO1 = 2 * K::MB, NO2 = DKV ? 2 * K::MBC : 0;
+    constexpr int NA = K::KS + K::CS;          // operands of the first half
+    constexpr int NOPS = NA + NO1 + NO2;
+    // LDS operand reads run LA MFMAs ahead of their use; the first half never reads past its own block
+    // (measured: look-ahead 2..4 for dq and 5..12 for dkv all run within 1 %)
+    constexpr int LA_WANT = DKV ? 6 : 3;
+    constexpr int LA_CAP = (NO1 + NO2) < NA ? (NO1 + NO2) : NA;
+    constexpr int LA = LA_CAP < LA_WANT ? LA_CAP : LA_WANT;
+    bf16x8 opr[LA + 1];
+    auto row_read = [&](const RowBase& rb, int toff, int np64, int ks) __attribute__((always_inline)) {
+        if (ks < np64 * 4) return as_bf16x8(*(const u32x4*)(smem + rb.b64[ks & 3] + (toff + (ks >> 2) * 4096)));
+        return as_bf16x8(*(const u32x4*)(smem + rb.b32[ks - np64 * 4] + (toff + np64 * 4096)));
+    };
+    auto tr_read = [&](const TrBase& tb, int toff, int np64, int mb, int kk) __attribute__((always_inline)) {
+        if (mb < np64 * 2) {
+            const int imm = toff + (mb >> 1) * 4096 + kk * 2048;
+            return join_tr(lds_read_tr16((const bf16_t*)(smem + tb.t64[mb & 1][0] + imm)),
+                           lds_read_tr16((const bf16_t*)(smem + tb.t64[mb & 1][1] + imm)));
+        }
+        const int imm = toff + np64 * 4096 + kk * 1024;
+        return join_tr(lds_read_tr16((const bf16_t*)(smem + tb.t32[0] + imm)),
+                       lds_read_tr16((const bf16_t*)(smem + tb.t32[1] + imm)));
+    };
+    // operand n of a block whose slot offset is folded into rb (row reads) / tb (transpose reads);
+    // callers keep a rolling window opr[n % (LA + 1)]
+    auto read_op = [&](const RowBase& rb, const TrBase& tb, int n) __attribute__((always_inline)) {
+        if (n < K::KS) return row_read(rb, 0, T1::NP64, n);
+        if (n < NA) return row_read(rb, kOffT2, T2::NP64, n - K::KS);
+        if (n < NA + NO1) return tr_read(tb, 0, T1::NP64, (n - NA) >> 1, (n - NA) & 1);
+        return tr_read(tb, kOffT2, T2::NP64, (n - NA - NO1) >> 1, (n - NA - NO1) & 1);
+    };
+
+    // P and dS of one accumulator element r (streamed row sb0 + 8*(r/4) + 4*hf + (r%4), lane row ri)
+    auto elem = [&](int r, const f32x16& s, const f32x16& dp, float lvx, float dvx, bool need_mask, int sb0,
+                    bf16x8 (&pb)[2], bf16x8 (&dsb)[2]) __attribute__((always_inline)) {
+        float pr = fast_exp2(fmaf(s[r], kLog2e, -lvx));
+        float ds = pr * (dp[r] - dvx);
+        if (need_mask) {
+            const int srow = sb0 + 8 * (r / 4) + 4 * hf + (r % 4);
+            const bool dead = srow >= N || (CAUSAL && (DKV ? (srow < ri) : (srow > ri)));
+            if (dead) { pr = 0.f; ds = 0.f; }   // also discards the filler rows past N
+        }
+        if (DKV) pb[r / 8][r % 8] = (bf16_t)pr;
+        dsb[r / 8][r % 8] = (bf16_t)ds;
+    };
+
+    if constexpr (DKV) {
+        // One wave per SIMD (the accumulators alone take 144 registers), so the overlap of
+        // matrix and vector work is written into the instruction stream: while the S and dP
+        // chains of block i+1 run, the exponentials and dS of block i are computed, one
+        // accumulator element per MFMA.  Iteration i:
+        //     S, dP chains of block i+1  ||  P, dS of block i
+        //     wait, barrier, issue block i+4
+        //     output chains of block i, first operand reads of block i+2, (lse2, D) of block i+1
+        // Ring of five slots: blocks i (transpose reads), i+1 (row reads), i+2 (prefetch),
+        // i+3 (landing), i+4 (being issued).
+        static_assert(NSLOT_DKV == 5, "slot arithmetic below assumes five slots");
+        issue_block(0, 0);
+        issue_block(1, 1);
+        issue_block(2, 2);
+        issue_block(3, 3);
+        wait_vmcnt<0>();
+        __syncthreads();
+        f32x16 sA, dA, sB, dB;
+        {
+            const RowBase r0 = mk_row(0);
+            const TrBase t0 = mk_tr(0);
+#pragma unroll
+            for (int r = 0; r < 16; r++) { sA[r] = 0.f; dA[r] = 0.f; }
+#pragma unroll
+            for (int n = 0; n < NA; n++) {
+                const bf16x8 o = read_op(r0, t0, n);
+                if (n < K::KS) sA = mfma32(o, l1reg[n], sA);
+                else dA = mfma32(o, l2reg[n - K::KS], dA);
+            }
+        }
+        RowBase rb1 = mk_row(kSlotBytes);     // rows of block i+1
+#pragma unroll
+        for (int n = 0; n < LA; n++) opr[n] = read_op(rb1, TrBase{}, n);
+        // (lse2, D) of the 16 streamed rows this lane's accumulator registers belong to, one block ahead
+        float vq[4][4], vd[4][4];
+        const int vlane = kOffVec + 32 * hf;
+        auto read_vec = [&](int off) __attribute__((always_inline)) {
+            const unsigned char* vp = smem + (vlane + off);
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                const float4 x0 = *(const float4*)(vp + 64 * g);
+                const float4 x1 = *(const float4*)(vp + 64 * g + 16);
+                vq[g][0] = x0.x; vd[g][0] = x0.y; vq[g][1] = x0.z; vd[g][1] = x0.w;
+                vq[g][2] = x1.x; vd[g][2] = x1.y; vq[g][3] = x1.z; vd[g][3] = x1.w;
+            }
+        };
+        read_vec(0);
+        int sl = 0;   // slot of block i
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        auto body = [&](int i, const f32x16& sc, const f32x16& dc, f32x16& sn, f32x16& dn)
+                        __attribute__((always_inline)) {
+            const int sl1 = sl + 1 >= NSLOT_DKV ? sl + 1 - NSLOT_DKV : sl + 1;
+            const int sl2 = sl + 2 >= NSLOT_DKV ? sl + 2 - NSLOT_DKV : sl + 2;
+            const int sl4 = sl == 0 ? NSLOT_DKV - 1 : sl - 1;
+            const TrBase tb0 = mk_tr(sl * kSlotBytes);          // transpose reads of block i
+            const RowBase rb2 = mk_row(sl2 * kSlotBytes);       // rows of block i+2
+            const int sb0 = blk_of(i) * BT;
+            const bool need_mask = (sb0 + BT > N) || (CAUSAL && sb0 < rw0 + 31);
+            bf16x8 pb[2], dsb[2];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int n = 0; n < NA; n++) {
+                opr[(n + LA) % (LA + 1)] = read_op(rb1, tb0, n + LA);   // past NA: output operands of block i
+                if (n < K::KS) sn = mfma32(opr[n % (LA + 1)], l1reg[n], n == 0 ? zero : sn);
+                else dn = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], n == K::KS ? zero : dn);
+#pragma unroll
+                for (int e = (n * 16) / NA; e < ((n + 1) * 16) / NA; e++)
+                    elem(e, sc, dc, vq[e >> 2][e & 3], vd[e >> 2][e & 3], false, sb0, pb, dsb);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (need_mask) {
+                // rare (diagonal blocks, sequence end): zero the dead elements afterwards, behind a real
+                // branch, so the common path carries no compares and selects.  NaNs from filler rows
+                // past N are discarded here as well.
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int srow = sb0 + 8 * (r / 4) + 4 * hf + (r % 4);
+                    if (srow >= N || (CAUSAL && srow < ri)) {
+                        pb[r / 8][r % 8] = (bf16_t)0.f;
+                        dsb[r / 8][r % 8] = (bf16_t)0.f;
+                    }
+                }
+            }
+            // block i+2 has landed; everyone has left block i-1
+            wait_prev_loads();
+            __syncthreads();
+            issue_block(i + 4, sl4);
+            bf16x8 nxt[LA];
+#pragma unroll
+            for (int n = NA; n < NOPS; n++) {
+                if (n + LA < NOPS) opr[(n + LA) % (LA + 1)] = read_op(rb1, tb0, n + LA);
+                else nxt[n + LA - NOPS] = read_op(rb2, tb0, n + LA - NOPS);   // row operands of block i+2
+                const int m = n - NA;
+                if (m < NO1) acc1[m >> 1] = mfma32(opr[n % (LA + 1)], dsb[m & 1], acc1[m >> 1]);
+                else acc2[(m - NO1) >> 1] = mfma32(opr[n % (LA + 1)], pb[(m - NO1) & 1], acc2[(m - NO1) >> 1]);
+            }
+#pragma unroll
+            for (int n = 0; n < LA; n++) opr[n] = nxt[n];
+            read_vec(sl1 * kSlotBytes);
+            rb1 = rb2;
+            sl = sl1;
+        };
+        // (unrolling by two to swap the score buffers without copies makes the register
+        // allocator shuffle all accumulators between VGPRs and AGPRs; the 32 copies are cheaper)
+        for (int i = 0; i < nIt; i++) {
+            body(i, sA, dA, sB, dB);
+            sA = sB;
+            dA = dB;
+        }
+    } else {
+        // Two waves per SIMD: the other workgroup's wave fills the gaps.  Iteration i:
+        //     S, dP chains of block i | P, dS | wait, barrier | issue block i+3 |
+        //     output chains of block i, first operand reads of block i+1
+        issue_block(0, 0);
+        issue_block(1, 1);
+        issue_block(2, 2);
+        wait_vmcnt<0>();
+        __syncthreads();
+        RowBase rb0 = mk_row(0);
+#pragma unroll
+        for (int n = 0; n < LA; n++) opr[n] = read_op(rb0, TrBase{}, n);
+
+        for (int i = 0; i < nIt; i++) {
+            const int slot = i & (NSLOT - 1);
+            const TrBase tb0 = mk_tr(slot * kSlotBytes);
+            const RowBase rbn = mk_row(((i + 1) & (NSLOT - 1)) * kSlotBytes);
+            const int sb0 = blk_of(i) * BT;      // first streamed row of the block
+
+            // ---------------- first half: S and dP chains ----------------
             f32x16 s, dp;
 #pragma unroll
             for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
-            const bf16_t* arow = asrc + (qb * 32 + l32) * K::AP + 8 * hf;
-            const bf16_t* drow = dsrc + (qb * 32 + l32) * K::DP + 8 * hf;
 #pragma unroll
-            for (int ks = 0; ks < K::KS; ks++)
-                s = mfma32(as_bf16x8(*(const u32x4*)(arow + ks * 16)), akreg[ks], s);
-#pragma unroll
-            for (int cs = 0; cs < C / 16; cs++)
-                dp = mfma32(as_bf16x8(*(const u32x4*)(drow + cs * 16)), vreg[cs], dp);
-
+            for (int n = 0; n < NA; n++) {
+                opr[(n + LA) % (LA + 1)] = read_op(rb0, tb0, n + LA);   // n + LA < NOPS: the output operands follow
+                if (n < K::KS) s = mfma32(opr[n % (LA + 1)], l1reg[n], s);
+                else dp = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], dp);
+            }
+            // ---------------- P and dS in accumulator layout ----------------
             bf16x8 pb[2], dsb[2];
-            const bool need_mask = CAUSAL && qb0 < kw0 + 31;
 #pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const float4 l4 = *(const float4*)(lsrc + qb * 32 + 8 * g + 4 * hf);
-                const float4 d4 = *(const float4*)(esrc + qb * 32 + 8 * g + 4 * hf);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-                const float dv[4] = {d4.x, d4.y, d4.z, d4.w};
+            for (int r = 0; r < 16; r++) elem(r, s, dp, my_lse2, my_d, false, sb0, pb, dsb);
+            if ((sb0 + BT > N) || (CAUSAL && sb0 + BT - 1 > rw0)) {
+                // rare (diagonal blocks, sequence end): zero the dead elements behind a real branch
+                asm volatile("" ::: "memory");
 #pragma unroll
-                for (int x = 0; x < 4; x++) {
-                    const int r = 4 * g + x;
-                    float pr = fast_exp2(fmaf(s[r], kLog2e, -lv[x]));
-                    if (need_mask) {
-                        const int query = qb0 + 8 * g + 4 * hf + x;
-                        if (query < ki) pr = 0.f;
-                    }
-                    pb[r / 8][r % 8] = (bf16_t)pr;
-                    dsb[r / 8][r % 8] = (bf16_t)(pr * (dp[r] - dv[x]));
+                for (int r = 0; r < 16; r++) {
+                    const int srow = sb0 + 8 * (r / 4) + 4 * hf + (r % 4);
+                    if (srow >= N || (CAUSAL && srow > ri)) dsb[r / 8][r % 8] = (bf16_t)0.f;
                 }
             }
-            // dV^T[c][key] += dO^T[c][query] P[query][key];  dAk^T[col][key] += Aq^T[col][query] dS[query][key]
-            const int rowoff = qb * 32 + 4 * hf + (i16 >> 2);
-            const bf16_t* dbase = dsrc + rowoff * K::DP + 16 * blk + 4 * (i16 & 3);
-            const bf16_t* abase = asrc + rowoff * K::AP + 16 * blk + 4 * (i16 & 3);
-#pragma unroll
-            for (int kk = 0; kk < 2; kk++) {
-#pragma unroll
-                for (int mb = 0; mb < K::MBC; mb++) {
-                    const bf16_t* ap = dbase + (kk * 16) * K::DP + mb * 32;
-                    const bf16x8 a = join_tr(lds_read_tr16(ap), lds_read_tr16(ap + 8 * K::DP));
-                    dvacc[mb] = mfma32(a, pb[kk], dvacc[mb]);
-                }
-#pragma unroll
-                for (int mb = 0; mb < K::MB; mb++) {
-                    const bf16_t* ap = abase + (kk * 16) * K::AP + mb * 32;
-                    const bf16x8 a = join_tr(lds_read_tr16(ap), lds_read_tr16(ap + 8 * K::AP));
-                    dkacc[mb] = mfma32(a, dsb[kk], dkacc[mb]);
-                }
-            }
-        }
-        if (more) store_tile((t + 1) & 1);
-        __syncthreads();
-    }
+            // ---------------- block i+1 has landed; everyone has left block i-1 ----------------
+            wait_prev_loads();
+            __syncthreads();
+            issue_block(i + 3, (i + 3) & (NSLOT - 1));
 
-    if (kok) {
-        bf16_t* dvg = (bf16_t*)p.dv + base + (size_t)ki * C;
-        bf16_t* dkg = (bf16_t*)p.dk + base + (size_t)ki * C;
+            // ---------------- second half: output chains ----------------
+            bf16x8 nxt[LA];      // first operands of block i+1 (the window restarts at 0 with every block)
 #pragma unroll
-        for (int mb = 0; mb < K::MBC; mb++)
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                bf16x4 a4, b4;
-#pragma unroll
-                for (int x = 0; x < 4; x++) {
-                    a4[x] = (bf16_t)dvacc[mb][4 * g + x];
-                    b4[x] = (bf16_t)dkacc[mb][4 * g + x];
-                }
-                *(u32x2*)(dvg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, a4);
-                *(u32x2*)(dkg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, b4);
+            for (int n = NA; n < NOPS; n++) {
+                if (n + LA < NOPS) opr[(n + LA) % (LA + 1)] = read_op(rb0, tb0, n + LA);
+                else nxt[n + LA - NOPS] = read_op(rbn, tb0, n + LA - NOPS);
+                const int m = n - NA;
+                acc1[m >> 1] = mfma32(opr[n % (LA + 1)], dsb[m & 1], acc1[m >> 1]);
             }
+#pragma unroll
+            for (int n = 0; n < LA; n++) opr[n] = nxt[n];
+            rb0 = rbn;
+        }
+    }
+    wait_vmcnt<0>();     // no direct load may outlive this tile's use of the ring
+    __syncthreads();
+
+    // ---- epilogue ----
+    const bool rok = ri < N;
+    const size_t base = (size_t)bh * N * C;
+    if (rok) {
+        if (DKV) {
+            bf16_t* dvg = (bf16_t*)p.dv + base + (size_t)ri * C;
+            bf16_t* dkg = (bf16_t*)p.dk + base + (size_t)ri * C;
+#pragma unroll
+            for (int mb = 0; mb < K::MBC; mb++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    bf16x4 a4, b4;
+#pragma unroll
+                    for (int x = 0; x < 4; x++) {
+                        a4[x] = (bf16_t)acc2[mb][4 * g + x];
+                        b4[x] = (bf16_t)acc1[mb][4 * g + x];
+                    }
+                    *(u32x2*)(dvg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, a4);
+                    *(u32x2*)(dkg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, b4);
+                }
+        } else {
+            bf16_t* dqg = (bf16_t*)p.dq + base + (size_t)ri * C;
+#pragma unroll
+            for (int mb = 0; mb < K::MBC; mb++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(acc1[mb][4 * g + x] * p.scale);
+                    *(u32x2*)(dqg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, o4);
+                }
+        }
     }
     if (RP > 0) {
+        const bool f32 = p.phi_f32 != 0;
+        const size_t esz = f32 ? 4 : 2;
         float* scratch = (float*)smem + wave * 32 * (K::RP2 + 1);
         unsigned char* dst = nullptr;
-        if (kok) dst = (unsigned char*)p.dphi_k + ((size_t)bh * N + ki) * R * phi_esz;
-        store_dphi<C, RP, false>(&dkacc[K::MBC], scratch, dst, R, phi_f32, l32, hf);
+        if (rok) dst = (unsigned char*)(DKV ? p.dphi_k : p.dphi_q) + ((size_t)bh * N + ri) * R * esz;
+        // the key-side limb order applies to the key's own gradient and vice versa
+        store_dphi<K::RP2, !DKV>(&acc1[K::MBC], scratch, dst, R, f32, l32, hf);
+    }
+}
+
+// Work units: one 128-row tile per workgroup, or when causal the tile pair (n-1-u, u), whose
+// streamed ranges add up to the same length for every u (no tail of heavy tiles).
+template <int C, int RP, bool CAUSAL, bool DKV>
+__global__ __launch_bounds__(kThreads, DKV ? 1 : 2) void bwd_main_kernel(BwdParams p, MainArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+    if (L >= p.total_tiles) return;
+    const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
+    const int bh = L / n_units;
+    const int u = L - bh * n_units;
+    if (CAUSAL) {
+        const int other = p.n_tiles - 1 - u;
+        // heavier tile first: high query tiles for dq, low key tiles for dkv
+        bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, DKV ? u : other);
+        if (u != other) {
+            __syncthreads();   // the epilogue's LDS scratch is reused as ring memory
+            bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, DKV ? other : u);
+        }
+    } else {
+        bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, u);
     }
 }
 
@@ -573,27 +659,43 @@ bool set_lds(KernT kern, size_t bytes, bool* done) {
 
 template <int C, int RP, bool CAUSAL>
 int launch(const BwdParams& pin, hipStream_t stream) {
-    using K = BwdCfg<C, RP>;
-    const size_t lds_dq = K::kTileLds > K::kEpiLds ? K::kTileLds : K::kEpiLds;
-    const size_t lds_dkv = K::kTileLds + K::kVecLds;
-    auto kdq = bwd_dq_kernel<C, RP, CAUSAL>;
-    auto kdkv = bwd_dkv_kernel<C, RP, CAUSAL>;
+    using K = Cfg<C, RP>;
+    constexpr size_t ring_dq = (size_t)NSLOT * (K::T1::BYTES + K::T2::BYTES);
+    constexpr size_t ring_dkv = (size_t)NSLOT_DKV * (K::T1::BYTES + K::T2::BYTES + K::kVecBytes);
+    constexpr size_t lds_dq = ring_dq > K::kEpiLds ? ring_dq : K::kEpiLds;
+    constexpr size_t lds_dkv = ring_dkv > K::kEpiLds ? ring_dkv : K::kEpiLds;
+    auto kdq = bwd_main_kernel<C, RP, CAUSAL, false>;
+    auto kdkv = bwd_main_kernel<C, RP, CAUSAL, true>;
     static bool done_dq = false, done_dkv = false;
     if (!set_lds(kdq, lds_dq, &done_dq) || !set_lds(kdkv, lds_dkv, &done_dkv)) return 1;
 
     const long long rows = (long long)pin.B * pin.H * pin.N;
-    const long long dthreads = rows * (C / 8);
-    hipLaunchKernelGGL((bwd_delta_kernel<C>), dim3((unsigned)((dthreads + 255) / 256)), dim3(256), 0, stream,
-                       (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.delta, rows);
+    // workspace: vec [rows] float2 | Aq [rows][W] bf16 | Ak [rows][W] bf16  (each a multiple of 16 bytes)
+    unsigned char* ws = (unsigned char*)pin.workspace;
+    MainArgs a;
+    a.vec = (const float2*)ws;
+    bf16_t* aq = (bf16_t*)(ws + (((size_t)rows * 8 + 15) & ~(size_t)15));
+    bf16_t* ak = aq + (size_t)rows * K::W;
+    a.aq = aq;
+    a.ak = ak;
+
+    const long long vthreads = rows * (C / 8);
+    hipLaunchKernelGGL((bwd_vec_kernel<C>), dim3((unsigned)((vthreads + 255) / 256)), dim3(256), 0, stream,
+                       (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
+    if (hipGetLastError() != hipSuccess) return 1;
+    const long long pthreads = rows * (K::W / 8);
+    hipLaunchKernelGGL((bwd_prep_kernel<C, RP>), dim3((unsigned)((pthreads + 255) / 256)), dim3(256), 0, stream,
+                       pin, aq, ak);
     if (hipGetLastError() != hipSuccess) return 1;
 
     BwdParams p = pin;
     p.n_tiles = (p.N + 127) / 128;
-    p.total_tiles = p.B * p.H * p.n_tiles;
+    const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
+    p.total_tiles = p.B * p.H * n_units;
     p.tiles_per_xcd = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p);
+    hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p, a);
     if (hipGetLastError() != hipSuccess) return 1;
-    hipLaunchKernelGGL(kdq, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dq, stream, p);
+    hipLaunchKernelGGL(kdq, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dq, stream, p, a);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
@@ -613,6 +715,11 @@ int dispatch_rp(const BwdParams& p, int rp, hipStream_t stream) {
 }
 
 }  // namespace
+
+size_t fb_bwd_workspace_bytes(long long rows, int C, int R) {
+    const int w = C + (R > 0 ? 32 : 0);
+    return (((size_t)rows * 8 + 15) & ~(size_t)15) + (size_t)rows * w * 2 * 2;
+}
 
 int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream) {
     switch (C) {

@@ -10,11 +10,9 @@
 
 int fb_launch_fwd_f32(const FwdParams& p, int C, bool dense, hipStream_t stream);
 int fb_launch_fwd_bf16(const FwdParams& p, int C, int rp, bool dense, int qb, hipStream_t stream);
+// p.workspace points at fb_bwd_workspace_bytes(B*H*N, C, R) bytes of device scratch.
 int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream);
-// Streamed backward (operand rows prepared in the workspace, direct-to-LDS block copies);
-// p.delta points at a workspace of fb_bwd_stream_workspace_bytes(B*H*N, C, R) bytes.
-int fb_launch_bwd_bf16_stream(const BwdParams& p, int C, int rp, hipStream_t stream);
-size_t fb_bwd_stream_workspace_bytes(long long rows, int C, int R);
+size_t fb_bwd_workspace_bytes(long long rows, int C, int R);
 
 // Extra dynamic LDS bytes added to forward launches (experiments on occupancy; normally 0).
 size_t fb_debug_lds_pad();

@@ -31,7 +31,7 @@ struct BwdParams {
     const void* phi_q; const void* phi_k;
     const void* out; const float* lse; const void* dout;
     void* dq; void* dk; void* dv; void* dphi_q; void* dphi_k;
-    float* delta;         // [B,H,N] workspace: rowsum(dout * out)
+    void* workspace;      // device scratch: (lse2, D) rows and the concatenated operand rows
     int B, H, N, R;
     int causal;
     int phi_f32;

@@ -21,14 +21,6 @@ pytestmark = pytest.mark.gpu
 NAMES = ("dq", "dk", "dv", "dphi_q", "dphi_k")
 
 
-@pytest.fixture(params=[0, 1], ids=["staged", "streamed"], autouse=True)
-def bwd_impl(request):
-    """Every test runs against both backward implementations."""
-    api.fb_tune_set("bwd_impl", request.param)
-    yield request.param
-    api.fb_tune_set("bwd_impl", 1)
-
-
 def _run_bwd(w):
     d = workload_to_device(w)
     out, lse = api.fb_lowrank_attn_fwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], causal=w.causal)
