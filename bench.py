@@ -160,7 +160,7 @@ def main() -> int:
                    "flop_per_pair": 2 * (2 * w.C + w.R), "pairs": w.pairs},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {
-            "kernel": "low-rank bf16 forward (fwd_bf16_kernel / fwd_bf16_pp_kernel)",
+            "kernel": "low-rank bf16 forward (fwd_bf16_kernel; fwd_bf16_pp_kernel for long non-causal sequences)",
             "bound": "mfma",
             "achieved": round(kern_tflops, 2),
             "peak": PEAK_BF16_TFLOPS,

@@ -65,11 +65,16 @@ int fb_version(void);
 const char* fb_status_string(int status);
 
 /*
- * Process-wide tuning knob for experiments (benchmarks sweep it; results never depend on
- * it).  name = "fwd_qb": bf16 forward kernel variant: 1 or 2 = four-wave kernel with that many
- * 32-row query blocks per wave, 8 = eight-wave ping-pong kernel (0 restores the automatic
- * choice).  Returns FB_OK, FB_ERR_NULL, FB_ERR_SHAPE (value out
- * of range) or FB_ERR_UNSUPPORTED (unknown name).  Not synchronised with concurrent calls.
+ * Process-wide tuning knobs for experiments (benchmarks sweep them; results never depend on
+ * them).  Returns FB_OK, FB_ERR_NULL, FB_ERR_SHAPE (value out of range) or
+ * FB_ERR_UNSUPPORTED (unknown name).  Not synchronised with concurrent calls.
+ *   "fwd_qb"      bf16 forward kernel variant; 0 restores the automatic choice.
+ *                 1, 2 = four-wave kernel with that many 32-row query blocks per wave
+ *                 4    = in-wave interleaved kernel (falls back to 1 for padded rank > 32)
+ *                 8    = eight-wave ping-pong kernel
+ *                 16   = direct-to-LDS kernel (falls back to 1 for shapes it does not take)
+ *   "fwd_lds_pad" extra dynamic LDS bytes per workgroup of the four-wave kernel
+ *                 (0 .. 102400), to study occupancy; 0 by default.
  */
 int fb_tune_set(const char* name, int value);
 
@@ -103,7 +108,11 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
  * (Sec. 3.2 "Speed up training"; Sec. 4.1 "Implementation choices").
  * `out` and `lse` are the forward's results.  Needs dtype = FB_BF16.
  * workspace: device scratch of at least fb_lowrank_attn_bwd_workspace_bytes(...) bytes,
- * 16-byte aligned, owned by the caller; its contents on entry are ignored.
+ * 16-byte aligned, owned by the caller; its contents on entry are ignored and it may be
+ * reused as soon as the call's work on `stream` has finished.  It receives, per (b, h, i):
+ * (lse * log2 e, D_i = sum_c dout * out) and the concatenated bf16 operand rows
+ * [q*scale | phi_q | 0] and [k | phi_k | 0] that the two main kernels stream
+ * (8 + 4 * (C + 32) bytes per row when R > 0, 8 + 4 * C otherwise).
  * Results are deterministic (no floating-point atomics).
  */
 size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype);

@@ -31,7 +31,6 @@
 #include "fb_launch.h"
 #include "fb_params.h"
 
-// Timing experiments only (each breaks correctness): FB_X_NOBARRIER, FB_X_NOSTAGE, FB_X_NORESCALE
 namespace fbil {
 
 constexpr int kWaves = 4;
@@ -311,11 +310,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_il_kernel(FwdParams p) {
         // ---- lazy rescale (rare): raise the reference maximum of rows that outgrew it ----
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) {
-#ifdef FB_X_NORESCALE
-            if (t == 0) {
-#else
             if (__builtin_expect(__any(mx2[qb] > mref[qb] + kRescaleTau), 0)) {
-#endif
                 const float mnew = fmaxf(fmaxf(mref[qb], mx2[qb]), -1e30f);
                 const float alpha = fast_exp2(mref[qb] - mnew);
                 mref[qb] = mnew;
@@ -379,14 +374,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_il_kernel(FwdParams p) {
         }
 
         // ================= region 2: O chain | maxima of S_{t+1} | K_{t+2} reads | staging ======
-#ifndef FB_X_NOSTAGE
-#ifndef FB_X_NOSTORE
         store_block(buf3, t + 3);
-#endif
-#ifndef FB_X_NOLOAD
         load_block(t + 4);
-#endif
-#endif
         load_bias(t + 2);
         __builtin_amdgcn_sched_barrier(0);
         {
@@ -437,9 +426,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_il_kernel(FwdParams p) {
 #pragma unroll
             for (int qb = 0; qb < QB; qb++) mx2[qb] = half_max(m[qb]) * kLog2e;
         }
-#ifndef FB_X_NOBARRIER
         __syncthreads();
-#endif
         buf = buf1;
         (void)kb0;
     };

@@ -43,9 +43,6 @@
 #ifndef FB_PRIO_MFMA
 #define FB_PRIO_MFMA 2
 #endif
-#ifndef FB_STAGGER
-#define FB_STAGGER 0
-#endif
 
 #ifdef FB_TRACE4
 __device__ long long fb_trace4_buf[4 * 64 * 8];
@@ -353,12 +350,6 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     __syncthreads();
     read_k(0);
 
-#if FB_STAGGER
-    {   // desynchronise the two waves sharing a SIMD: the odd hardware wave slot starts late
-        const unsigned hwid = __builtin_amdgcn_s_getreg((4) | (0 << 6) | ((4 - 1) << 11));  // HW_ID[3:0]
-        if (hwid & 1) __builtin_amdgcn_s_sleep(FB_STAGGER);
-    }
-#endif
     int buf = 0;                 // t % NBUF
     // One block.  MASKED instances apply the causal / sequence-end masks and may skip the
     // MFMA chains of a block no row of this wave can see; interior blocks carry none of that.
