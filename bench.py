@@ -188,6 +188,21 @@ def main() -> int:
         d.pop("bias", None)
         torch.cuda.empty_cache()
 
+        if w.name == "alibi_causal":
+            # the same bias generated inside the kernel from the head slopes (no factor loads)
+            from paper_2505_12044_amd.workloads import alibi_slopes_f32
+            slopes = torch.from_numpy(alibi_slopes_f32(w.H)).cuda()
+
+            def jit():
+                api.fb_alibi_attn_fwd(d["q"], d["k"], d["v"], slopes, out=d["out"], lse=d["lse"],
+                                      causal=w.causal, stream=stream)
+            _, jit_ms = time_calls(jit, n, 3)
+            result["alibi_in_kernel"] = {
+                "ms": round(jit_ms, 5),
+                "TFLOPs": round(flops / (jit_ms * 1e-3) / 1e12, 2),
+                "vs_factor_tensors": round(kern_ms / jit_ms, 3),
+            }
+
         ws = torch.empty(max(16, api.fb_lowrank_attn_bwd_workspace_bytes(w.B, w.H, w.N, w.C, w.R)),
                          dtype=torch.uint8, device="cuda")
         grads = (torch.empty_like(d["q"]), torch.empty_like(d["q"]), torch.empty_like(d["q"]),

@@ -91,6 +91,19 @@ int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
                         float scale, void* stream);
 
 /*
+ * Forward with the ALiBi bias b_ij = -m_h (i - j) (0-based positions, every (i, j); the
+ * causal mask is separate) generated inside the kernel from the per-head slopes: the rank-2
+ * factors of Example 3.4 are computed from tile indices, so no factor tensor is read
+ * (App. D, "decomposition in JIT").  Positions are measured from the tile's first query row
+ * and carried as fp32 (three bf16 limbs), so the bias is exact to fp32 rounding at any N.
+ *   slopes [H] float, device memory, 4-byte aligned.  Needs dtype = FB_BF16.
+ * Same result as fb_lowrank_attn_fwd with phi_q(i) = [-m_h i, m_h], phi_k(j) = [1, j] in fp32.
+ */
+int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* slopes,
+                      void* out, float* lse, int B, int H, int N, int C, int causal,
+                      fb_dtype dtype, float scale, void* stream);
+
+/*
  * Forward with a dense bias streamed from device memory (the baseline of Example 3.9:
  * HBM traffic Theta(N M C^2 / S + N M)).  bias has the storage type `dtype`.
  */

@@ -21,7 +21,8 @@ _lib_handle = None
 
 EXPORTS = (
     "fb_version", "fb_status_string", "fb_tune_set", "fb_lowrank_attn_fwd",
-    "fb_dense_bias_attn_fwd", "fb_lowrank_attn_bwd_workspace_bytes", "fb_lowrank_attn_bwd",
+    "fb_alibi_attn_fwd", "fb_dense_bias_attn_fwd", "fb_lowrank_attn_bwd_workspace_bytes",
+    "fb_lowrank_attn_bwd",
 )
 
 
@@ -49,6 +50,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_tune_set.argtypes = [ctypes.c_char_p, ci]
     lib.fb_lowrank_attn_fwd.restype = ci
     lib.fb_lowrank_attn_fwd.argtypes = [vp] * 7 + [ci] * 6 + [ci, ci, ci, cf, vp]
+    lib.fb_alibi_attn_fwd.restype = ci
+    lib.fb_alibi_attn_fwd.argtypes = [vp] * 6 + [ci] * 5 + [ci, cf, vp]
     lib.fb_dense_bias_attn_fwd.restype = ci
     lib.fb_dense_bias_attn_fwd.argtypes = [vp] * 6 + [ci] * 5 + [ci, ci, cf, vp]
     lib.fb_lowrank_attn_bwd_workspace_bytes.restype = sz
@@ -117,6 +120,25 @@ def fb_lowrank_attn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, causal=False,
                                  phi_code, int(bool(phi_batch_broadcast)), float(scale),
                                  _stream(stream))
     _check(st, "fb_lowrank_attn_fwd")
+    return out, lse
+
+
+def fb_alibi_attn_fwd(q, k, v, slopes, out=None, lse=None, causal=False, scale: float = 0.0,
+                      stream=None):
+    """out, lse = attention(q, k, v) with the bias -slopes[h] * (i - j) generated in the kernel.
+    slopes: [H] float32 CUDA tensor."""
+    lib = load_library()
+    B, H, N, C = q.shape
+    if slopes.dtype != torch.float32 or slopes.numel() != H:
+        raise FlashBiasError("slopes must be a float32 tensor with one entry per head")
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    st = lib.fb_alibi_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(slopes), _ptr(out), _ptr(lse),
+                               B, H, N, C, int(bool(causal)), _dtype_code(q), float(scale),
+                               _stream(stream))
+    _check(st, "fb_alibi_attn_fwd")
     return out, lse
 
 

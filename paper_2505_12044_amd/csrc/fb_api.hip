@@ -136,6 +136,30 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
+int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* slopes,
+                      void* out, float* lse, int B, int H, int N, int C, int causal,
+                      fb_dtype dtype, float scale, void* stream) {
+    if (!q || !k || !v || !slopes || !out || !lse) return FB_ERR_NULL;
+    if (int st = check_common(B, H, N, C, 2)) return st;
+    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
+        return FB_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(slopes) & 3u) != 0) return FB_ERR_ALIGN;
+
+    FwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.phi_q = nullptr; p.phi_k = nullptr; p.slopes = slopes;
+    p.bias = nullptr; p.out = out; p.lse = lse;
+    p.B = B; p.H = H; p.N = N; p.R = 2; p.causal = causal != 0;
+    p.phi_f32 = 1;
+    p.phi_bstride = 0;
+    p.bias_bstride = 0;
+    p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    int qb = pick_qb(B, H, N, C, 16, false, causal != 0);
+    if (qb != 2) qb = 1;     // only the four-wave kernel generates factors
+    const int rc = fb_launch_fwd_bf16_alibi(p, C, qb, (hipStream_t)stream);
+    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
 size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype) {
     (void)dtype;
     if (B <= 0 || H <= 0 || N <= 0) return 0;

@@ -174,4 +174,18 @@ FB_DEV bf16x8 phi_chunk_finish(u32x4 raw, int c8, bool f32) {
     return out;
 }
 
+// Query-side columns [8*c8, 8*c8+8) of the padded limb layout for two fp32 factor values
+// (x0, x1) computed in the kernel instead of read from memory: column j holds limb
+// (slot j % 6) of x_{j / 6} for j < 12, else 0.
+FB_DEV bf16x8 phi_chunk_from_pair(int c8, float x0, float x1) {
+    bf16x8 out;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        const int j = c8 * 8 + e;
+        const int r = j / 6, slot = j - 6 * r;
+        out[e] = r < 2 ? bf16_limb(r == 0 ? x0 : x1, q_limb_of_slot(slot)) : (bf16_t)0.f;
+    }
+    return out;
+}
+
 #endif

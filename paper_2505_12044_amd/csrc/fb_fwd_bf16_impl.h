@@ -87,6 +87,11 @@ struct Cfg {
 // 0 = no factors, 1 = bf16 factors with R % 8 == 0 (whole 16-byte chunks are
 // copied), 2 = general (bf16 factors of any R gathered element-wise, fp32 factors split into
 // limbs).
+// 4 = ALiBi factors generated in the kernel from the head's slope m (App. D, "decomposition
+// in JIT"): phi_q(i) = [-m (i - q0), m], phi_k(j) = [1, j - q0] as fp32 items (R = 2), where q0
+// is the tile's first query row.  The product is -m (i - j) for every tile origin; measuring
+// positions from q0 keeps the operands small near the diagonal, where the bias matters, so
+// the result does not degrade with N.  No factor memory is read.
 // One tile: the 128 * QB query rows [qt * BQ, (qt + 1) * BQ) of head bh against all keys they see.
 template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE>
 FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, const int qt) {
@@ -94,8 +99,10 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     bf16_t* const kt = (bf16_t*)smem;                 // [NBUF][BK][KP]
     bf16_t* const vt = kt + NBUF * K::KBLK;           // [NBUF][BK][VP]
     const int b = bh / p.H, h = bh - b * p.H;
-    const int N = p.N, R = p.R;
-    const bool phi_f32 = PM == 3;
+    const int N = p.N, R = PM == 4 ? 2 : p.R;
+    const bool phi_f32 = PM == 3 || PM == 4;
+    const bool ITEMS = PM == 3 || PM == 4;     // key-side factors handled as (key, rank) items
+    const float slope = PM == 4 ? p.slopes[h] : 0.f;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -133,7 +140,8 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
             } else {
                 const int c8 = (ks - C / 16) * 2 + hf;
-                val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
+                if (PM == 4) val = phi_chunk_from_pair(c8, -slope * (float)(qi - q0), slope);
+                else val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
             }
             qreg[qb][ks] = val;
         }
@@ -167,7 +175,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     int fitem_row[K::FIT], fitem_r[K::FIT];
     bool fitem_ok[K::FIT];
     const float* pkf = (const float*)pkg;
-    if (PM == 3) {
+    if (ITEMS) {
 #pragma unroll
         for (int it = 0; it < K::FIT; it++) {
             const int e = lane * kWaves + wave + it * kThreads;
@@ -221,6 +229,10 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
                 if (fitem_ok[it]) fraw[it] = pkf[(size_t)min(k0 + fitem_row[it], N - 1) * R + fitem_r[it]];
+        } else if (PM == 4) {
+#pragma unroll
+            for (int it = 0; it < K::FIT; it++)
+                fraw[it] = fitem_r[it] == 0 ? 1.f : (float)(k0 + fitem_row[it] - q0);
         } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
@@ -254,7 +266,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 *(u32x4*)(vdst + row * K::VP + c8 * 8) = vraw[it];
             }
         }
-        if (PM == 3) {
+        if (ITEMS) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
                 if (fitem_ok[it]) phi_item_store_k(kdst + fitem_row[it] * K::KP + C + 6 * fitem_r[it], fraw[it]);

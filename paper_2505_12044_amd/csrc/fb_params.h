@@ -11,6 +11,7 @@ struct FwdParams {
     const void* v;
     const void* phi_q;    // [Bp,H,N,R] or null
     const void* phi_k;
+    const float* slopes;  // [H] per-head ALiBi slopes (in-kernel factor generation only)
     const void* bias;     // [Bb,H,N,N] or null (dense-bias mode)
     void* out;            // [B,H,N,C]
     float* lse;           // [B,H,N]

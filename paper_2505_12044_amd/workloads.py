@@ -58,6 +58,12 @@ def _store(x, dtype: str) -> np.ndarray:
 # ---------------------------------------------------------------------------------
 # bias sources
 # ---------------------------------------------------------------------------------
+def alibi_slopes_f32(num_heads: int):
+    """Head slopes m_h = 2^(-8 (h+1) / num_heads) of the decoder workload, float32 [H]."""
+    h = np.arange(num_heads, dtype=np.float64)
+    return (2.0 ** (-8.0 * (h + 1.0) / num_heads)).astype(np.float32)
+
+
 def alibi_factors(num_heads: int, n: int):
     """Exact rank-2 factors of the ALiBi bias -m_h (i - j) (Example 3.4, with the slope and
     sign of the decoder workload): phi_q(i) = [-m_h i, m_h], phi_k(j) = [1, j], 0-based,

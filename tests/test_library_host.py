@@ -70,6 +70,11 @@ def test_dense_and_backward_argument_errors(lib):
     assert f(64, 64, 64, None, 64, 64, 1, 1, 16, 64, 0, api.FB_BF16, 0, 0.0, None) == 1
     assert f(64, 64, 64, 64, 64, 64, 1, 1, 16, 96, 0, api.FB_BF16, 0, 0.0, None) == 3
     assert f(64, 64, 64, 68, 64, 64, 1, 1, 16, 64, 0, api.FB_BF16, 0, 0.0, None) == 4
+    a = lib.fb_alibi_attn_fwd
+    assert a(64, 64, 64, None, 64, 64, 1, 1, 16, 64, 1, api.FB_BF16, 0.0, None) == 1      # slopes NULL
+    assert a(64, 64, 64, 64, 64, 64, 1, 1, 16, 64, 1, api.FB_F32, 0.0, None) == 3         # bf16 only
+    assert a(64, 64, 64, 66, 64, 64, 1, 1, 16, 64, 1, api.FB_BF16, 0.0, None) == 4        # slopes not 4-byte aligned
+    assert a(64, 64, 64, 64, 64, 64, 1, 1, 0, 64, 1, api.FB_BF16, 0.0, None) == 2
     ws = lib.fb_lowrank_attn_bwd_workspace_bytes(2, 3, 100, 64, 8, api.FB_BF16)
     # (lse, D) pairs plus the two concatenated operand copies of width C + 32
     assert ws == 2 * 3 * 100 * 8 + 2 * (2 * 3 * 100) * (64 + 32) * 2
