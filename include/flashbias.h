@@ -125,7 +125,7 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
  * reused as soon as the call's work on `stream` has finished.  It receives, per (b, h, i):
  * (lse * log2 e, D_i = sum_c dout * out) and the concatenated bf16 operand rows
  * [q*scale | phi_q | 0] and [k | phi_k | 0] that the two main kernels stream
- * (8 + 4 * (C + 32) bytes per row when R > 0, 8 + 4 * C otherwise).
+ * (8 + 4 * (C + 64) bytes per row when R > 0, 8 + 4 * C otherwise).
  * Results are deterministic (no floating-point atomics).
  */
 size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype);

@@ -184,7 +184,7 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
     if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k) || !aligned16(dphi_q) || !aligned16(dphi_k)))
         return FB_ERR_ALIGN;
     const int rp = padded_rank(R, dtype, phi_dtype);
-    if (rp > 32) return FB_ERR_UNSUPPORTED;
+    if (rp > 64) return FB_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, R, dtype))
         return FB_ERR_WORKSPACE;
     if (!aligned16(workspace)) return FB_ERR_ALIGN;

@@ -10,7 +10,7 @@
 //
 // Kernels:
 //   prep  : writes the concatenated operands Aq = [q*scale | phi_q | 0], Ak = [k | phi_k | 0]
-//           (bf16, width W = C + 32 when R > 0; fp32 factors as three bf16 limbs, six product
+//           (bf16, width W = C + 32 or C + 64 when R > 0; fp32 factors as three bf16 limbs, six product
 //           columns per rank as in the forward) into the workspace
 //   vec   : (lse * log2 e, D) per query row
 //   main<DKV = true>  : a lane owns a key;   streams 32-query blocks; accumulates dV^T, dAk^T
@@ -96,7 +96,7 @@ struct Tile {
 
 template <int C, int RP>
 struct Cfg {
-    static constexpr int RP2 = RP > 0 ? 32 : 0;        // factor columns kept in the workspace rows
+    static constexpr int RP2 = (RP + 31) / 32 * 32;    // factor columns kept in the workspace rows (0, 32 or 64)
     static constexpr int W = C + RP2;
     static constexpr int KS = (C + RP) / 16;           // k-steps of the score contraction
     static constexpr int CS = C / 16;                  // k-steps of the dP contraction
@@ -627,7 +627,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 // Work units: one 128-row tile per workgroup, or when causal the tile pair (n-1-u, u), whose
 // streamed ranges add up to the same length for every u (no tail of heavy tiles).
 template <int C, int RP, bool CAUSAL, bool DKV>
-__global__ __launch_bounds__(kThreads, DKV ? 1 : 2) void bwd_main_kernel(BwdParams p, MainArgs a) {
+__global__ __launch_bounds__(kThreads, (DKV || (C == 128 && RP > 32)) ? 1 : 2) void bwd_main_kernel(BwdParams p, MainArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
     if (L >= p.total_tiles) return;
@@ -710,6 +710,8 @@ int dispatch_rp(const BwdParams& p, int rp, hipStream_t stream) {
         case 0: return dispatch_causal<C, 0>(p, stream);
         case 16: return dispatch_causal<C, 16>(p, stream);
         case 32: return dispatch_causal<C, 32>(p, stream);
+        case 48: return dispatch_causal<C, 48>(p, stream);
+        case 64: return dispatch_causal<C, 64>(p, stream);
         default: return -1;
     }
 }
@@ -717,7 +719,8 @@ int dispatch_rp(const BwdParams& p, int rp, hipStream_t stream) {
 }  // namespace
 
 size_t fb_bwd_workspace_bytes(long long rows, int C, int R) {
-    const int w = C + (R > 0 ? 32 : 0);
+    // R alone does not say whether the factors are fp32 (6 R columns): size for the widest rows
+    const int w = C + (R > 0 ? 64 : 0);
     return (((size_t)rows * 8 + 15) & ~(size_t)15) + (size_t)rows * w * 2 * 2;
 }
 

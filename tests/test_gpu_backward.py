@@ -62,6 +62,10 @@ CASES = [
     ("vision_relpos", dict(B=2, H=2, N=256)),                     # factors shared over the batch
     ("pairformer", dict(B=3, N=384)),
     ("long_train", dict(B=1, H=2, N=300, R=3, phi_dtype="f32")),  # fp32 factors, limb-split
+    ("long_train", dict(B=1, H=2, N=300, R=9, phi_dtype="f32")),  # 54 limb columns -> padded width 64
+    ("long_train", dict(B=1, H=1, N=260, R=64)),                  # widest bf16 factors, C = 128
+    ("long_train", dict(B=1, H=2, N=200, C=32, R=40, causal=True)),
+    ("long_train", dict(B=1, H=2, N=256, C=64, R=48)),
 ]
 
 

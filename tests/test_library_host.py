@@ -76,8 +76,8 @@ def test_dense_and_backward_argument_errors(lib):
     assert a(64, 64, 64, 66, 64, 64, 1, 1, 16, 64, 1, api.FB_BF16, 0.0, None) == 4        # slopes not 4-byte aligned
     assert a(64, 64, 64, 64, 64, 64, 1, 1, 0, 64, 1, api.FB_BF16, 0.0, None) == 2
     ws = lib.fb_lowrank_attn_bwd_workspace_bytes(2, 3, 100, 64, 8, api.FB_BF16)
-    # (lse, D) pairs plus the two concatenated operand copies of width C + 32
-    assert ws == 2 * 3 * 100 * 8 + 2 * (2 * 3 * 100) * (64 + 32) * 2
+    # (lse, D) pairs plus the two concatenated operand copies of width up to C + 64
+    assert ws == 2 * 3 * 100 * 8 + 2 * (2 * 3 * 100) * (64 + 64) * 2
     assert lib.fb_lowrank_attn_bwd_workspace_bytes(0, 3, 100, 64, 8, api.FB_BF16) == 0
     g = lib.fb_lowrank_attn_bwd
     ptrs = [64] * 13
@@ -87,7 +87,7 @@ def test_dense_and_backward_argument_errors(lib):
 
     assert bwd(ptrs=[None] + [64] * 12) == 1
     assert bwd(dtype=api.FB_F32) == 3
-    assert bwd(R=40) == 3                      # padded width > 32 in the backward
+    assert bwd(R=70) == 3                      # padded width > 64
     assert bwd(w=None) == 5
     assert bwd(wb=ws - 1) == 5
     assert bwd(w=72) == 4
