@@ -91,6 +91,17 @@ int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
                         float scale, void* stream);
 
 /*
+ * Cross-attention form of fb_lowrank_attn_fwd (Eq. 1 with N queries and M keys): q, out
+ * [B,H,N,C], k, v [B,H,M,C], phi_q [Bp,H,N,R], phi_k [Bp,H,M,R], lse [B,H,N].  No causal mask
+ * (its alignment is undefined for N != M).  Needs dtype = FB_BF16 when N != M.
+ */
+int fb_lowrank_xattn_fwd(const void* q, const void* k, const void* v,
+                         const void* phi_q, const void* phi_k, void* out, float* lse,
+                         int B, int H, int N, int M, int C, int R,
+                         fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                         float scale, void* stream);
+
+/*
  * Forward with the ALiBi bias b_ij = -m_h (i - j) (0-based positions, every (i, j); the
  * causal mask is separate) generated inside the kernel from the per-head slopes: the rank-2
  * factors of Example 3.4 are computed from tile indices, so no factor tensor is read
@@ -137,6 +148,21 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
                         int B, int H, int N, int C, int R, int causal,
                         fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
                         float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Cross-attention form of fb_lowrank_attn_bwd: q, out, dout, dq [B,H,N,C]; k, v, dk, dv
+ * [B,H,M,C]; phi_q, dphi_q [.,H,N,R]; phi_k, dphi_k [.,H,M,R]; lse [B,H,N].  No causal mask.
+ * Workspace as for fb_lowrank_attn_bwd, sized by the query below.
+ */
+size_t fb_lowrank_xattn_bwd_workspace_bytes(int B, int H, int N, int M, int C, int R, fb_dtype dtype);
+
+int fb_lowrank_xattn_bwd(const void* q, const void* k, const void* v,
+                         const void* phi_q, const void* phi_k,
+                         const void* out, const float* lse, const void* dout,
+                         void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                         int B, int H, int N, int M, int C, int R,
+                         fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                         float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -20,9 +20,9 @@ FB_F32, FB_BF16 = 0, 1
 _lib_handle = None
 
 EXPORTS = (
-    "fb_version", "fb_status_string", "fb_tune_set", "fb_lowrank_attn_fwd",
+    "fb_version", "fb_status_string", "fb_tune_set", "fb_lowrank_attn_fwd", "fb_lowrank_xattn_fwd",
     "fb_alibi_attn_fwd", "fb_dense_bias_attn_fwd", "fb_lowrank_attn_bwd_workspace_bytes",
-    "fb_lowrank_attn_bwd",
+    "fb_lowrank_attn_bwd", "fb_lowrank_xattn_bwd_workspace_bytes", "fb_lowrank_xattn_bwd",
 )
 
 
@@ -50,6 +50,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_tune_set.argtypes = [ctypes.c_char_p, ci]
     lib.fb_lowrank_attn_fwd.restype = ci
     lib.fb_lowrank_attn_fwd.argtypes = [vp] * 7 + [ci] * 6 + [ci, ci, ci, cf, vp]
+    lib.fb_lowrank_xattn_fwd.restype = ci
+    lib.fb_lowrank_xattn_fwd.argtypes = [vp] * 7 + [ci] * 6 + [ci, ci, ci, cf, vp]
     lib.fb_alibi_attn_fwd.restype = ci
     lib.fb_alibi_attn_fwd.argtypes = [vp] * 6 + [ci] * 5 + [ci, cf, vp]
     lib.fb_dense_bias_attn_fwd.restype = ci
@@ -58,6 +60,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_lowrank_attn_bwd_workspace_bytes.argtypes = [ci] * 5 + [ci]
     lib.fb_lowrank_attn_bwd.restype = ci
     lib.fb_lowrank_attn_bwd.argtypes = [vp] * 13 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
+    lib.fb_lowrank_xattn_bwd_workspace_bytes.restype = sz
+    lib.fb_lowrank_xattn_bwd_workspace_bytes.argtypes = [ci] * 6 + [ci]
+    lib.fb_lowrank_xattn_bwd.restype = ci
+    lib.fb_lowrank_xattn_bwd.argtypes = [vp] * 13 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
     if path is None:
         _lib_handle = lib
     return lib
@@ -120,6 +126,27 @@ def fb_lowrank_attn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, causal=False,
                                  phi_code, int(bool(phi_batch_broadcast)), float(scale),
                                  _stream(stream))
     _check(st, "fb_lowrank_attn_fwd")
+    return out, lse
+
+
+def fb_lowrank_xattn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, scale: float = 0.0,
+                         phi_batch_broadcast: Optional[bool] = None, stream=None):
+    """Cross-attention: q [B,H,N,C], k, v [B,H,M,C], phi_q [B or 1,H,N,R], phi_k [B or 1,H,M,R]."""
+    lib = load_library()
+    B, H, N, C = q.shape
+    M = k.shape[2]
+    R = 0 if phi_q is None else phi_q.shape[-1]
+    if phi_batch_broadcast is None:
+        phi_batch_broadcast = phi_q is not None and phi_q.shape[0] == 1 and B > 1
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    phi_code = _dtype_code(phi_q) if phi_q is not None else _dtype_code(q)
+    st = lib.fb_lowrank_xattn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(phi_q), _ptr(phi_k), _ptr(out),
+                                  _ptr(lse), B, H, N, M, C, R, _dtype_code(q), phi_code,
+                                  int(bool(phi_batch_broadcast)), float(scale), _stream(stream))
+    _check(st, "fb_lowrank_xattn_fwd")
     return out, lse
 
 
@@ -195,4 +222,32 @@ def fb_lowrank_attn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, causal=False, sca
                                  _ptr(workspace), workspace.numel() * workspace.element_size(),
                                  _stream(stream))
     _check(st, "fb_lowrank_attn_bwd")
+    return dq, dk, dv, dpq, dpk
+
+
+def fb_lowrank_xattn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, scale: float = 0.0,
+                         phi_batch_broadcast: Optional[bool] = None, workspace=None, stream=None):
+    """Cross-attention backward: returns dq [B,H,N,C], dk, dv [B,H,M,C], dphi_q [B,H,N,R],
+    dphi_k [B,H,M,R] (None when R = 0)."""
+    lib = load_library()
+    B, H, N, C = q.shape
+    M = k.shape[2]
+    R = 0 if phi_q is None else phi_q.shape[-1]
+    if phi_batch_broadcast is None:
+        phi_batch_broadcast = phi_q is not None and phi_q.shape[0] == 1 and B > 1
+    phi_code = _dtype_code(phi_q) if phi_q is not None else _dtype_code(q)
+    need = int(lib.fb_lowrank_xattn_bwd_workspace_bytes(B, H, N, M, C, R, _dtype_code(q)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    dpq = dpk = None
+    if R:
+        dpq = torch.empty((B, H, N, R), dtype=phi_q.dtype, device=q.device)
+        dpk = torch.empty((B, H, M, R), dtype=phi_q.dtype, device=q.device)
+    st = lib.fb_lowrank_xattn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(phi_q), _ptr(phi_k), _ptr(out),
+                                  _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dpq),
+                                  _ptr(dpk), B, H, N, M, C, R, _dtype_code(q), phi_code,
+                                  int(bool(phi_batch_broadcast)), float(scale), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "fb_lowrank_xattn_bwd")
     return dq, dk, dv, dpq, dpk

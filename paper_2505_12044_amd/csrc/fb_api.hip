@@ -81,17 +81,20 @@ int fb_tune_set(const char* name, int value) {
     return FB_ERR_UNSUPPORTED;
 }
 
-int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
-                        const void* phi_q, const void* phi_k, void* out, float* lse,
-                        int B, int H, int N, int C, int R, int causal,
-                        fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
-                        float scale, void* stream) {
+// Shared by the self-attention (M = N) and cross-attention entry points.
+static int lowrank_fwd_impl(const void* q, const void* k, const void* v,
+                            const void* phi_q, const void* phi_k, void* out, float* lse,
+                            int B, int H, int N, int M, int C, int R, int causal,
+                            fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                            float scale, void* stream) {
     if (!q || !k || !v || !out || !lse) return FB_ERR_NULL;
-    if (int st = check_common(B, H, N, C, R)) return st;
+    if (int st = check_common(B, H, N > M ? N : M, C, R)) return st;
+    if (N <= 0 || M <= 0) return FB_ERR_SHAPE;
     if (R > 0 && (!phi_q || !phi_k)) return FB_ERR_NULL;
     if (dtype != FB_F32 && dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (dtype == FB_F32 && R > 0 && phi_dtype != FB_F32) return FB_ERR_UNSUPPORTED;
+    if (N != M && (causal || dtype != FB_BF16)) return FB_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
         return FB_ERR_ALIGN;
     if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k))) return FB_ERR_ALIGN;
@@ -101,15 +104,39 @@ int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
     FwdParams p{};
     p.q = q; p.k = k; p.v = v; p.phi_q = phi_q; p.phi_k = phi_k; p.bias = nullptr;
     p.out = out; p.lse = lse;
-    p.B = B; p.H = H; p.N = N; p.R = R; p.causal = causal != 0;
+    p.B = B; p.H = H; p.N = N; p.M = M; p.R = R; p.causal = causal != 0;
     p.phi_f32 = phi_dtype == FB_F32;
     p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
+    p.phik_bstride = phi_batch_broadcast ? 0 : (long long)H * M * R;
     p.bias_bstride = 0;
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int rc;
-    if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, false, (hipStream_t)stream);
-    else rc = fb_launch_fwd_bf16(p, C, rp, false, pick_qb(B, H, N, C, rp, false, causal != 0), (hipStream_t)stream);
+    if (dtype == FB_F32) {
+        rc = fb_launch_fwd_f32(p, C, false, (hipStream_t)stream);
+    } else {
+        int qb = pick_qb(B, H, N, C, rp, false, causal != 0);
+        if (N != M && qb != 2) qb = 1;     // only the four-wave kernel takes N != M
+        rc = fb_launch_fwd_bf16(p, C, rp, false, qb, (hipStream_t)stream);
+    }
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
+int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
+                        const void* phi_q, const void* phi_k, void* out, float* lse,
+                        int B, int H, int N, int C, int R, int causal,
+                        fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                        float scale, void* stream) {
+    return lowrank_fwd_impl(q, k, v, phi_q, phi_k, out, lse, B, H, N, N, C, R, causal, dtype, phi_dtype,
+                            phi_batch_broadcast, scale, stream);
+}
+
+int fb_lowrank_xattn_fwd(const void* q, const void* k, const void* v,
+                         const void* phi_q, const void* phi_k, void* out, float* lse,
+                         int B, int H, int N, int M, int C, int R,
+                         fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                         float scale, void* stream) {
+    return lowrank_fwd_impl(q, k, v, phi_q, phi_k, out, lse, B, H, N, M, C, R, 0, dtype, phi_dtype,
+                            phi_batch_broadcast, scale, stream);
 }
 
 int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const void* bias,
@@ -125,9 +152,10 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
     FwdParams p{};
     p.q = q; p.k = k; p.v = v; p.phi_q = nullptr; p.phi_k = nullptr; p.bias = bias;
     p.out = out; p.lse = lse;
-    p.B = B; p.H = H; p.N = N; p.R = 0; p.causal = causal != 0;
+    p.B = B; p.H = H; p.N = N; p.M = N; p.R = 0; p.causal = causal != 0;
     p.phi_f32 = 0;
     p.phi_bstride = 0;
+    p.phik_bstride = 0;
     p.bias_bstride = bias_batch_broadcast ? 0 : (long long)H * N * N;
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int rc;
@@ -149,9 +177,10 @@ int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* 
     FwdParams p{};
     p.q = q; p.k = k; p.v = v; p.phi_q = nullptr; p.phi_k = nullptr; p.slopes = slopes;
     p.bias = nullptr; p.out = out; p.lse = lse;
-    p.B = B; p.H = H; p.N = N; p.R = 2; p.causal = causal != 0;
+    p.B = B; p.H = H; p.N = N; p.M = N; p.R = 2; p.causal = causal != 0;
     p.phi_f32 = 1;
     p.phi_bstride = 0;
+    p.phik_bstride = 0;
     p.bias_bstride = 0;
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int qb = pick_qb(B, H, N, C, 16, false, causal != 0);
@@ -160,11 +189,57 @@ int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* 
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
+static size_t bwd_ws_impl(int B, int H, int N, int M, int C, int R) {
+    if (B <= 0 || H <= 0 || N <= 0 || M <= 0) return 0;
+    // (lse * log2 e, D) per query row and the concatenated operand rows [q*scale | phi_q], [k | phi_k]
+    return fb_bwd_workspace_bytes((long long)B * H * N, (long long)B * H * M, C, R);
+}
+
+static int lowrank_bwd_impl(const void* q, const void* k, const void* v,
+                            const void* phi_q, const void* phi_k,
+                            const void* out, const float* lse, const void* dout,
+                            void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                            int B, int H, int N, int M, int C, int R, int causal,
+                            fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                            float scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return FB_ERR_NULL;
+    if (int st = check_common(B, H, N > M ? N : M, C, R)) return st;
+    if (N <= 0 || M <= 0) return FB_ERR_SHAPE;
+    if (R > 0 && (!phi_q || !phi_k || !dphi_q || !dphi_k)) return FB_ERR_NULL;
+    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (N != M && causal) return FB_ERR_UNSUPPORTED;
+    const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
+    for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
+    if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k) || !aligned16(dphi_q) || !aligned16(dphi_k)))
+        return FB_ERR_ALIGN;
+    const int rp = padded_rank(R, dtype, phi_dtype);
+    if (rp > 64) return FB_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < bwd_ws_impl(B, H, N, M, C, R)) return FB_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FB_ERR_ALIGN;
+
+    BwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.phi_q = phi_q; p.phi_k = phi_k;
+    p.out = out; p.lse = lse; p.dout = dout;
+    p.dq = dq; p.dk = dk; p.dv = dv; p.dphi_q = dphi_q; p.dphi_k = dphi_k;
+    p.workspace = workspace;
+    p.B = B; p.H = H; p.N = N; p.M = M; p.R = R; p.causal = causal != 0;
+    p.phi_f32 = phi_dtype == FB_F32;
+    p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
+    p.phik_bstride = phi_batch_broadcast ? 0 : (long long)H * M * R;
+    p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    const int rc = fb_launch_bwd_bf16(p, C, rp, (hipStream_t)stream);
+    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
 size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype) {
     (void)dtype;
-    if (B <= 0 || H <= 0 || N <= 0) return 0;
-    // (lse * log2 e, D) per row and the concatenated operand rows [q*scale | phi_q], [k | phi_k]
-    return fb_bwd_workspace_bytes((long long)B * H * N, C, R);
+    return bwd_ws_impl(B, H, N, N, C, R);
+}
+
+size_t fb_lowrank_xattn_bwd_workspace_bytes(int B, int H, int N, int M, int C, int R, fb_dtype dtype) {
+    (void)dtype;
+    return bwd_ws_impl(B, H, N, M, C, R);
 }
 
 int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
@@ -174,32 +249,21 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
                         int B, int H, int N, int C, int R, int causal,
                         fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
                         float scale, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return FB_ERR_NULL;
-    if (int st = check_common(B, H, N, C, R)) return st;
-    if (R > 0 && (!phi_q || !phi_k || !dphi_q || !dphi_k)) return FB_ERR_NULL;
-    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
-    if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
-    const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
-    for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
-    if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k) || !aligned16(dphi_q) || !aligned16(dphi_k)))
-        return FB_ERR_ALIGN;
-    const int rp = padded_rank(R, dtype, phi_dtype);
-    if (rp > 64) return FB_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, R, dtype))
-        return FB_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return FB_ERR_ALIGN;
+    return lowrank_bwd_impl(q, k, v, phi_q, phi_k, out, lse, dout, dq, dk, dv, dphi_q, dphi_k, B, H, N, N, C, R,
+                            causal, dtype, phi_dtype, phi_batch_broadcast, scale, workspace, workspace_bytes,
+                            stream);
+}
 
-    BwdParams p{};
-    p.q = q; p.k = k; p.v = v; p.phi_q = phi_q; p.phi_k = phi_k;
-    p.out = out; p.lse = lse; p.dout = dout;
-    p.dq = dq; p.dk = dk; p.dv = dv; p.dphi_q = dphi_q; p.dphi_k = dphi_k;
-    p.workspace = workspace;
-    p.B = B; p.H = H; p.N = N; p.R = R; p.causal = causal != 0;
-    p.phi_f32 = phi_dtype == FB_F32;
-    p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
-    p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
-    const int rc = fb_launch_bwd_bf16(p, C, rp, (hipStream_t)stream);
-    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+int fb_lowrank_xattn_bwd(const void* q, const void* k, const void* v,
+                         const void* phi_q, const void* phi_k,
+                         const void* out, const float* lse, const void* dout,
+                         void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                         int B, int H, int N, int M, int C, int R,
+                         fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                         float scale, void* workspace, size_t workspace_bytes, void* stream) {
+    return lowrank_bwd_impl(q, k, v, phi_q, phi_k, out, lse, dout, dq, dk, dv, dphi_q, dphi_k, B, H, N, M, C, R,
+                            0, dtype, phi_dtype, phi_batch_broadcast, scale, workspace, workspace_bytes,
+                            stream);
 }
 
 }  // extern "C"

@@ -111,34 +111,37 @@ struct Cfg {
 // ------------------------------------------------------------------------------------------
 // prep / vec
 // ------------------------------------------------------------------------------------------
-template <int C, int RP>
-__global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __restrict__ aq,
-                                                       bf16_t* __restrict__ ak) {
+// One side per launch: QSIDE writes Aq = [q*scale | phi_q | 0] for the B*H*N query rows,
+// otherwise Ak = [k | phi_k | 0] for the B*H*M key rows.
+template <int C, int RP, bool QSIDE>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __restrict__ dst) {
     using K = Cfg<C, RP>;
     constexpr int CPR = K::W / 8;
+    const int len = QSIDE ? p.N : p.M;
     const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
-    const long long row = gid / CPR;                        // (b*H + h)*N + i
+    const long long row = gid / CPR;                        // (b*H + h)*len + i
     const int c = (int)(gid - row * CPR);
-    const long long rows = (long long)p.B * p.H * p.N;
+    const long long rows = (long long)p.B * p.H * len;
     if (row >= rows) return;
-    bf16x8 a, b;
+    bf16x8 a;
     if (c < C / 8) {
-        const bf16x8 x = as_bf16x8(*(const u32x4*)((const bf16_t*)p.q + row * C + c * 8));
+        const bf16x8 x = as_bf16x8(*(const u32x4*)((const bf16_t*)(QSIDE ? p.q : p.k) + row * C + c * 8));
+        if (QSIDE) {
 #pragma unroll
-        for (int e = 0; e < 8; e++) a[e] = (bf16_t)((float)x[e] * p.scale);
-        b = as_bf16x8(*(const u32x4*)((const bf16_t*)p.k + row * C + c * 8));
+            for (int e = 0; e < 8; e++) a[e] = (bf16_t)((float)x[e] * p.scale);
+        } else {
+            a = x;
+        }
     } else {
         const bool f32 = p.phi_f32 != 0;
         const size_t esz = f32 ? 4 : 2;
-        const long long bh = row / p.N;
-        const int i = (int)(row - bh * p.N);
+        const long long bh = row / len;
+        const int i = (int)(row - bh * len);
         const int bb = (int)(bh / p.H), h = (int)(bh - (long long)bb * p.H);
-        const size_t off = ((size_t)bb * p.phi_bstride + ((size_t)h * p.N + i) * p.R) * esz;
-        a = phi_chunk_gather<true>((const unsigned char*)p.phi_q + off, c - C / 8, p.R, f32);
-        b = phi_chunk_gather<false>((const unsigned char*)p.phi_k + off, c - C / 8, p.R, f32);
+        const size_t off = ((size_t)bb * (QSIDE ? p.phi_bstride : p.phik_bstride) + ((size_t)h * len + i) * p.R) * esz;
+        a = phi_chunk_gather<QSIDE>((const unsigned char*)(QSIDE ? p.phi_q : p.phi_k) + off, c - C / 8, p.R, f32);
     }
-    *(u32x4*)(aq + row * K::W + c * 8) = as_uint4(a);
-    *(u32x4*)(ak + row * K::W + c * 8) = as_uint4(b);
+    *(u32x4*)(dst + row * K::W + c * 8) = as_uint4(a);
 }
 
 template <int C>
@@ -213,21 +216,22 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     constexpr int NDW = (ND + kWaves - 1) / kWaves;               // ... per wave, at most
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-    const int N = p.N, R = p.R;
+    // NL rows on the lane side (keys when DKV, else queries), NS rows on the streamed side
+    const int NL = DKV ? p.M : p.N, NS = DKV ? p.N : p.M, R = p.R;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hf = lane >> 5;
     const int r0 = tile * 128;            // first lane-side row of the workgroup
     const int rw0 = r0 + wave * 32;       // ... of this wave
     const int ri = rw0 + l32;             // this lane's row
-    const int rc = min(ri, N - 1);        // rows past N compute on row N-1 and are not stored
+    const int rc = min(ri, NL - 1);       // rows past the end compute on the last row and are not stored
 
-    const size_t rowbase = (size_t)bh * N;
-    const bf16_t* l1g = (DKV ? a.ak : a.aq) + rowbase * K::W;                       // lane-side operand of S
-    const bf16_t* l2g = (const bf16_t*)(DKV ? p.v : p.dout) + rowbase * C;          // lane-side operand of dP
-    const bf16_t* t1g = (DKV ? a.aq : a.ak) + rowbase * K::W;                       // streamed
-    const bf16_t* t2g = (const bf16_t*)(DKV ? p.dout : p.v) + rowbase * C;
-    const float2* vecg = a.vec + rowbase;
+    const size_t lbase = (size_t)bh * NL, sbase_rows = (size_t)bh * NS;
+    const bf16_t* l1g = (DKV ? a.ak : a.aq) + lbase * K::W;                         // lane-side operand of S
+    const bf16_t* l2g = (const bf16_t*)(DKV ? p.v : p.dout) + lbase * C;            // lane-side operand of dP
+    const bf16_t* t1g = (DKV ? a.aq : a.ak) + sbase_rows * K::W;                    // streamed
+    const bf16_t* t2g = (const bf16_t*)(DKV ? p.dout : p.v) + sbase_rows * C;
+    const float2* vecg = a.vec + (size_t)bh * p.N;                                  // per query row
 
     // ---- lane-side operands, loop invariant ----
     bf16x8 l1reg[K::KS], l2reg[K::CS];
@@ -255,11 +259,11 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     }
 
     // ---- streamed block range ----
-    const int nblk_all = (N + BT - 1) / BT;
+    const int nblk_all = (NS + BT - 1) / BT;
     int b_begin = 0, b_end = nblk_all;
     if (CAUSAL) {
         if (DKV) b_begin = r0 / BT;                            // queries before the first key see nothing
-        else b_end = min(nblk_all, (min(N, r0 + 128) + BT - 1) / BT);
+        else b_end = min(nblk_all, (min(NS, r0 + 128) + BT - 1) / BT);
     }
     const int nIt = b_end - b_begin;
     auto blk_of = [&](int i) __attribute__((always_inline)) { return min(b_begin + i, nblk_all - 1); };
@@ -300,7 +304,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     const int my_ndma = (ND - wave + kWaves - 1) / kWaves;     // wave-uniform: NDW or NDW - 1
     auto issue_block = [&](int i, int slot) __attribute__((always_inline)) {
         const int blk = blk_of(i);
-        const int left = N - blk * BT - 1;     // last valid row inside the block; rows past it repeat it
+        const int left = NS - blk * BT - 1;    // last valid row inside the block; rows past it repeat it
         const unsigned sbase = lds0 + slot * kSlotBytes;
 #pragma unroll
         for (int j = 0; j < NDW; j++) {
@@ -399,7 +403,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         float ds = pr * (dp[r] - dvx);
         if (need_mask) {
             const int srow = sb0 + 8 * (r / 4) + 4 * hf + (r % 4);
-            const bool dead = srow >= N || (CAUSAL && (DKV ? (srow < ri) : (srow > ri)));
+            const bool dead = srow >= NS || (CAUSAL && (DKV ? (srow < ri) : (srow > ri)));
             if (dead) { pr = 0.f; ds = 0.f; }   // also discards the filler rows past N
         }
         if (DKV) pb[r / 8][r % 8] = (bf16_t)pr;
@@ -463,7 +467,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             const TrBase tb0 = mk_tr(sl * kSlotBytes);          // transpose reads of block i
             const RowBase rb2 = mk_row(sl2 * kSlotBytes);       // rows of block i+2
             const int sb0 = blk_of(i) * BT;
-            const bool need_mask = (sb0 + BT > N) || (CAUSAL && sb0 < rw0 + 31);
+            const bool need_mask = (sb0 + BT > NS) || (CAUSAL && sb0 < rw0 + 31);
             bf16x8 pb[2], dsb[2];
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -484,7 +488,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int srow = sb0 + 8 * (r / 4) + 4 * hf + (r % 4);
-                    if (srow >= N || (CAUSAL && srow < ri)) {
+                    if (srow >= NS || (CAUSAL && srow < ri)) {
                         pb[r / 8][r % 8] = (bf16_t)0.f;
                         dsb[r / 8][r % 8] = (bf16_t)0.f;
                     }
@@ -549,13 +553,13 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             bf16x8 pb[2], dsb[2];
 #pragma unroll
             for (int r = 0; r < 16; r++) elem(r, s, dp, my_lse2, my_d, false, sb0, pb, dsb);
-            if ((sb0 + BT > N) || (CAUSAL && sb0 + BT - 1 > rw0)) {
+            if ((sb0 + BT > NS) || (CAUSAL && sb0 + BT - 1 > rw0)) {
                 // rare (diagonal blocks, sequence end): zero the dead elements behind a real branch
                 asm volatile("" ::: "memory");
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int srow = sb0 + 8 * (r / 4) + 4 * hf + (r % 4);
-                    if (srow >= N || (CAUSAL && srow > ri)) dsb[r / 8][r % 8] = (bf16_t)0.f;
+                    if (srow >= NS || (CAUSAL && srow > ri)) dsb[r / 8][r % 8] = (bf16_t)0.f;
                 }
             }
             // ---------------- block i+1 has landed; everyone has left block i-1 ----------------
@@ -581,8 +585,8 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     __syncthreads();
 
     // ---- epilogue ----
-    const bool rok = ri < N;
-    const size_t base = (size_t)bh * N * C;
+    const bool rok = ri < NL;
+    const size_t base = (size_t)bh * NL * C;
     if (rok) {
         if (DKV) {
             bf16_t* dvg = (bf16_t*)p.dv + base + (size_t)ri * C;
@@ -618,7 +622,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         const size_t esz = f32 ? 4 : 2;
         float* scratch = (float*)smem + wave * 32 * (K::RP2 + 1);
         unsigned char* dst = nullptr;
-        if (rok) dst = (unsigned char*)(DKV ? p.dphi_k : p.dphi_q) + ((size_t)bh * N + ri) * R * esz;
+        if (rok) dst = (unsigned char*)(DKV ? p.dphi_k : p.dphi_q) + ((size_t)bh * NL + ri) * R * esz;
         // the key-side limb order applies to the key's own gradient and vice versa
         store_dphi<K::RP2, !DKV>(&acc1[K::MBC], scratch, dst, R, f32, l32, hf);
     }
@@ -631,7 +635,7 @@ __global__ __launch_bounds__(kThreads, (DKV || (C == 128 && RP > 32)) ? 1 : 2) v
     extern __shared__ __align__(16) unsigned char smem[];
     const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
     if (L >= p.total_tiles) return;
-    const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
+    const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;   // p.n_tiles: 128-row tiles of the lane side
     const int bh = L / n_units;
     const int u = L - bh * n_units;
     if (CAUSAL) {
@@ -669,8 +673,9 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     static bool done_dq = false, done_dkv = false;
     if (!set_lds(kdq, lds_dq, &done_dq) || !set_lds(kdkv, lds_dkv, &done_dkv)) return 1;
 
-    const long long rows = (long long)pin.B * pin.H * pin.N;
-    // workspace: vec [rows] float2 | Aq [rows][W] bf16 | Ak [rows][W] bf16  (each a multiple of 16 bytes)
+    const long long rows = (long long)pin.B * pin.H * pin.N;      // query rows
+    const long long rowsk = (long long)pin.B * pin.H * pin.M;     // key rows
+    // workspace: vec [rows] float2 | Aq [rows][W] bf16 | Ak [rowsk][W] bf16  (each a multiple of 16 bytes)
     unsigned char* ws = (unsigned char*)pin.workspace;
     MainArgs a;
     a.vec = (const float2*)ws;
@@ -683,18 +688,24 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     hipLaunchKernelGGL((bwd_vec_kernel<C>), dim3((unsigned)((vthreads + 255) / 256)), dim3(256), 0, stream,
                        (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
     if (hipGetLastError() != hipSuccess) return 1;
-    const long long pthreads = rows * (K::W / 8);
-    hipLaunchKernelGGL((bwd_prep_kernel<C, RP>), dim3((unsigned)((pthreads + 255) / 256)), dim3(256), 0, stream,
-                       pin, aq, ak);
+    hipLaunchKernelGGL((bwd_prep_kernel<C, RP, true>), dim3((unsigned)((rows * (K::W / 8) + 255) / 256)),
+                       dim3(256), 0, stream, pin, aq);
+    if (hipGetLastError() != hipSuccess) return 1;
+    hipLaunchKernelGGL((bwd_prep_kernel<C, RP, false>), dim3((unsigned)((rowsk * (K::W / 8) + 255) / 256)),
+                       dim3(256), 0, stream, pin, ak);
     if (hipGetLastError() != hipSuccess) return 1;
 
+    auto set_tiles = [](BwdParams& p, int lane_rows) {
+        p.n_tiles = (lane_rows + 127) / 128;
+        const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
+        p.total_tiles = p.B * p.H * n_units;
+        p.tiles_per_xcd = (p.total_tiles + 7) / 8;
+    };
     BwdParams p = pin;
-    p.n_tiles = (p.N + 127) / 128;
-    const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
-    p.total_tiles = p.B * p.H * n_units;
-    p.tiles_per_xcd = (p.total_tiles + 7) / 8;
+    set_tiles(p, p.M);
     hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p, a);
     if (hipGetLastError() != hipSuccess) return 1;
+    set_tiles(p, p.N);
     hipLaunchKernelGGL(kdq, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dq, stream, p, a);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
@@ -718,10 +729,10 @@ int dispatch_rp(const BwdParams& p, int rp, hipStream_t stream) {
 
 }  // namespace
 
-size_t fb_bwd_workspace_bytes(long long rows, int C, int R) {
+size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R) {
     // R alone does not say whether the factors are fp32 (6 R columns): size for the widest rows
     const int w = C + (R > 0 ? 64 : 0);
-    return (((size_t)rows * 8 + 15) & ~(size_t)15) + (size_t)rows * w * 2 * 2;
+    return (((size_t)rows_q * 8 + 15) & ~(size_t)15) + (size_t)(rows_q + rows_k) * w * 2;
 }
 
 int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream) {

@@ -99,7 +99,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     bf16_t* const kt = (bf16_t*)smem;                 // [NBUF][BK][KP]
     bf16_t* const vt = kt + NBUF * K::KBLK;           // [NBUF][BK][VP]
     const int b = bh / p.H, h = bh - b * p.H;
-    const int N = p.N, R = PM == 4 ? 2 : p.R;
+    const int N = p.N, M = p.M, R = PM == 4 ? 2 : p.R;   // N queries, M keys
     const bool phi_f32 = PM == 3 || PM == 4;
     const bool ITEMS = PM == 3 || PM == 4;     // key-side factors handled as (key, rank) items
     const float slope = PM == 4 ? p.slopes[h] : 0.f;
@@ -111,19 +111,19 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     const int qw0 = q0 + wave * (QB * 32);
 
     const size_t base = (size_t)bh * N * C;
+    const size_t kbase = (size_t)bh * M * C;
     const bf16_t* qg = (const bf16_t*)p.q + base;
-    const bf16_t* kg = (const bf16_t*)p.k + base;
-    const bf16_t* vg = (const bf16_t*)p.v + base;
+    const bf16_t* kg = (const bf16_t*)p.k + kbase;
+    const bf16_t* vg = (const bf16_t*)p.v + kbase;
     const size_t phi_esz = phi_f32 ? 4 : 2;
     const unsigned char* pqg = nullptr;
     const unsigned char* pkg = nullptr;
     if (RP > 0) {
-        const size_t pbase = ((size_t)b * p.phi_bstride + (size_t)h * N * R) * phi_esz;
-        pqg = (const unsigned char*)p.phi_q + pbase;
-        pkg = (const unsigned char*)p.phi_k + pbase;
+        pqg = (const unsigned char*)p.phi_q + ((size_t)b * p.phi_bstride + (size_t)h * N * R) * phi_esz;
+        pkg = (const unsigned char*)p.phi_k + ((size_t)b * p.phik_bstride + (size_t)h * M * R) * phi_esz;
     }
     const bf16_t* bg = nullptr;
-    if (DENSE) bg = (const bf16_t*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * N;
+    if (DENSE) bg = (const bf16_t*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * M;
 
     // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout).  Rows past N
     // read row N-1 (finite values) and are never stored.
@@ -159,14 +159,14 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             for (int r = 0; r < 16; r++) oacc[qb][cb][r] = 0.f;
     }
 
-    const int kend = CAUSAL ? min(N, q0 + K::BQ) : N;
+    const int kend = CAUSAL ? min(M, q0 + K::BQ) : M;
     const int nT = (kend + BK - 1) / BK;
     // Causal tiles walk the keys from the diagonal back to key 0: with a recency bias such as
     // ALiBi the row maximum is then met in the first block and the accumulator is never
     // rescaled again (in ascending order it would be rescaled in nearly every block).
     auto blk_of = [&](int t) { return CAUSAL ? max(nT - 1 - t, 0) : t; };
 
-    // ---- block staging: global -> registers -> LDS.  Rows past N are clamped to row N-1; the
+    // ---- block staging: global -> registers -> LDS.  Rows past M are clamped to row M-1; the
     // keys they stand for are masked to -inf before the softmax, so their values never count.
     u32x4 kraw[K::KIT], vraw[K::KIT];
     u32x4 praw[K::PIT > 0 ? K::PIT : 1];
@@ -204,7 +204,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 
     auto load_block = [&](int t) {
         const int k0 = blk_of(t) * BK;
-        if (k0 + BK <= N) {   // whole block in range (wave-uniform): base + 32-bit offset
+        if (k0 + BK <= M) {   // whole block in range (wave-uniform): base + 32-bit offset
             const unsigned boff = (unsigned)k0 * (unsigned)(C * 2);
 #pragma unroll
             for (int it = 0; it < K::KIT; it++) {
@@ -219,7 +219,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 const int e = tid + it * kThreads;
                 if (K::KCH % kThreads == 0 || e < K::KCH) {
                     const int row = e / (C / 8), c8 = e % (C / 8);
-                    const int j = min(k0 + row, N - 1);
+                    const int j = min(k0 + row, M - 1);
                     kraw[it] = *(const u32x4*)(kg + (size_t)j * C + c8 * 8);
                     vraw[it] = *(const u32x4*)(vg + (size_t)j * C + c8 * 8);
                 }
@@ -228,7 +228,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         if (PM == 3) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
-                if (fitem_ok[it]) fraw[it] = pkf[(size_t)min(k0 + fitem_row[it], N - 1) * R + fitem_r[it]];
+                if (fitem_ok[it]) fraw[it] = pkf[(size_t)min(k0 + fitem_row[it], M - 1) * R + fitem_r[it]];
         } else if (PM == 4) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
@@ -241,7 +241,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 const int e = ((tid + 64 * t) & (kThreads - 1)) + it * kThreads;
                 if (K::PCH % kThreads == 0 || e < K::PCH) {
                     const int row = e / (RP / 8), c8 = e % (RP / 8);
-                    const int j = min(k0 + row, N - 1);
+                    const int j = min(k0 + row, M - 1);
                     const unsigned char* src = pkg + (size_t)j * R * phi_esz;
                     if (PM == 1) {
                         praw[it] = (c8 * 8 < R) ? *(const u32x4*)(src + c8 * 16) : u32x4{0u, 0u, 0u, 0u};
@@ -291,7 +291,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     constexpr int BP = BK + 4;                       // bias tile row pitch (elements): 72 bytes
     bf16_t* const bt = vt + NBUF * K::VBLK + wave * (QB * 32 * BP);
     u32x4 braw[DENSE ? QB : 1][2];
-    const bool bias_fast = DENSE && ((N & 7) == 0);
+    const bool bias_fast = DENSE && ((M & 7) == 0);
     auto load_bias = [&](int t) {
         if (!DENSE) return;
         const int k0 = blk_of(t) * BK;
@@ -304,14 +304,14 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 const int qi = qw0 + qb * 32 + row;
                 const int j = k0 + 8 * c;
                 u32x4 a = u32x4{0u, 0u, 0u, 0u};
-                if (qi < N && j < N && !(CAUSAL && j > qi)) {
-                    const bf16_t* src = bg + (size_t)qi * N + j;
+                if (qi < N && j < M && !(CAUSAL && j > qi)) {
+                    const bf16_t* src = bg + (size_t)qi * M + j;
                     if (bias_fast) {
                         a = *(const u32x4*)src;
                     } else {
                         bf16x8 tmp;
 #pragma unroll
-                        for (int x = 0; x < 8; x++) tmp[x] = (j + x < N) ? src[x] : (bf16_t)0.f;
+                        for (int x = 0; x < 8; x++) tmp[x] = (j + x < M) ? src[x] : (bf16_t)0.f;
                         a = as_uint4(tmp);
                     }
                 }
@@ -433,7 +433,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int key = kb0 + 8 * (r / 4) + 4 * hf + (r % 4);
-                    if (key >= N || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
+                    if (key >= M || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
                 }
             }
             float mx = half_max(max16(s[qb])) * kLog2e;
@@ -487,7 +487,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     };
 
     // leading blocks that need no mask for any row of this wave, then the rest
-    int t_plain = N / BK;
+    int t_plain = M / BK;
     if (CAUSAL) t_plain = min(t_plain, (qw0 + 1) / BK);
     t_plain = min(t_plain, nT);
     if (CAUSAL) {   // reverse order: the masked blocks (diagonal, sequence end) come first

@@ -12,9 +12,9 @@ int fb_launch_fwd_f32(const FwdParams& p, int C, bool dense, hipStream_t stream)
 int fb_launch_fwd_bf16(const FwdParams& p, int C, int rp, bool dense, int qb, hipStream_t stream);
 // ALiBi factors generated in the kernel from p.slopes (p.phi_q / p.phi_k unused); qb = 1 or 2.
 int fb_launch_fwd_bf16_alibi(const FwdParams& p, int C, int qb, hipStream_t stream);
-// p.workspace points at fb_bwd_workspace_bytes(B*H*N, C, R) bytes of device scratch.
+// p.workspace points at fb_bwd_workspace_bytes(B*H*N, B*H*M, C, R) bytes of device scratch.
 int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream);
-size_t fb_bwd_workspace_bytes(long long rows, int C, int R);
+size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R);
 
 // Extra dynamic LDS bytes added to forward launches (experiments on occupancy; normally 0).
 size_t fb_debug_lds_pad();

@@ -15,10 +15,12 @@ struct FwdParams {
     const void* bias;     // [Bb,H,N,N] or null (dense-bias mode)
     void* out;            // [B,H,N,C]
     float* lse;           // [B,H,N]
-    int B, H, N, R;
+    int B, H, N, R;       // N = number of queries
+    int M;                // number of keys (= N except for cross-attention, four-wave bf16 kernel only)
     int causal;
     int phi_f32;          // factors stored as float (else bf16)
-    long long phi_bstride;   // elements between batch items of phi (0 when shared over batch)
+    long long phi_bstride;   // elements between batch items of phi_q (0 when shared over batch)
+    long long phik_bstride;  // ... of phi_k
     long long bias_bstride;  // elements between batch items of bias (0 when shared)
     float scale;
     int n_qtiles;         // query tiles per (b,h)
@@ -33,10 +35,12 @@ struct BwdParams {
     const void* out; const float* lse; const void* dout;
     void* dq; void* dk; void* dv; void* dphi_q; void* dphi_k;
     void* workspace;      // device scratch: (lse2, D) rows and the concatenated operand rows
-    int B, H, N, R;
+    int B, H, N, R;       // N = number of queries
+    int M;                // number of keys (= N except for cross-attention)
     int causal;
     int phi_f32;
-    long long phi_bstride;
+    long long phi_bstride;   // elements between batch items of phi_q (0 when shared over batch)
+    long long phik_bstride;  // ... of phi_k
     float scale;
     int n_tiles;          // tiles per (b,h) along the kernel's outer dimension
     int total_tiles;
