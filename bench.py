@@ -185,6 +185,20 @@ def main() -> int:
             "pct_of_hbm_peak": round(100 * w.pairs * 2 / (dense_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 2),
             "speedup_lowrank_vs_dense": round(dense_ms / kern_ms, 3),
         }
+        dense_bwd_ms = None
+        if w.N % 8 == 0 and "dout" in d:
+            # training-side baseline: dense-bias backward, which has to write the N x N bias gradient
+            wsd = torch.empty(max(16, api.fb_dense_bias_attn_bwd_workspace_bytes(w.B, w.H, w.N, w.C)),
+                              dtype=torch.uint8, device="cuda")
+            gd = (torch.empty_like(d["q"]), torch.empty_like(d["q"]), torch.empty_like(d["q"]),
+                  torch.empty((w.B, w.H, w.N, w.N), dtype=d["q"].dtype, device="cuda"))
+            dense()
+
+            def dense_bwd():
+                api.fb_dense_bias_attn_bwd(d["q"], d["k"], d["v"], d["bias"], d["out"], d["lse"], d["dout"],
+                                           causal=w.causal, workspace=wsd, grads=gd, stream=stream)
+            _, dense_bwd_ms = time_calls(dense_bwd, max(5, n // 2), 2)
+            del gd, wsd
         d.pop("bias", None)
         torch.cuda.empty_cache()
 
@@ -216,6 +230,10 @@ def main() -> int:
         _, bwd_ms = time_calls(bwd, n, 3)
         result["backward"] = {"ms": round(bwd_ms, 5),
                               "TFLOPs": round(w.bwd_flops() / (bwd_ms * 1e-3) / 1e12, 2)}
+        if dense_bwd_ms is not None:
+            result["backward"]["dense_bias_ms"] = round(dense_bwd_ms, 5)
+            result["backward"]["speedup_lowrank_vs_dense"] = round(dense_bwd_ms / bwd_ms, 3)
+            result["backward"]["dense_dbias_bytes"] = int(w.B * w.H * w.N * w.N * 2)
         del grads, ws
 
         others = {}
@@ -245,6 +263,20 @@ def main() -> int:
                    "dense_bias_GBps": round(wo.pairs * 2 / (ms_de * 1e-3) / 1e9, 1),
                    "speedup_lowrank_vs_dense": round(ms_de / ms_lr, 3)}
             if name == "long_train":
+                f_ms_db = None
+                if wo.N % 8 == 0:
+                    wsd = torch.empty(api.fb_dense_bias_attn_bwd_workspace_bytes(wo.B, wo.H, wo.N, wo.C),
+                                      dtype=torch.uint8, device="cuda")
+                    gd = (torch.empty_like(d["q"]), torch.empty_like(d["q"]), torch.empty_like(d["q"]),
+                          torch.empty((wo.B, wo.H, wo.N, wo.N), dtype=d["q"].dtype, device="cuda"))
+                    d2()
+
+                    def db2():
+                        api.fb_dense_bias_attn_bwd(d["q"], d["k"], d["v"], d["bias"], d["out"], d["lse"],
+                                                   d["dout"], causal=w_.causal, workspace=wsd, grads=gd,
+                                                   stream=stream)
+                    _, f_ms_db = time_calls(db2, 3, 1)
+                    del gd, wsd
                 d.pop("bias", None)
                 torch.cuda.empty_cache()
                 ws = torch.empty(api.fb_lowrank_attn_bwd_workspace_bytes(wo.B, wo.H, wo.N, wo.C, wo.R),
@@ -258,6 +290,10 @@ def main() -> int:
                 _, ms_b = time_calls(b2, 5, 1)
                 row["bwd_ms"] = round(ms_b, 4)
                 row["bwd_TFLOPs"] = round(wo.bwd_flops() / (ms_b * 1e-3) / 1e12, 2)
+                if f_ms_db is not None:
+                    row["dense_bwd_ms"] = round(f_ms_db, 4)
+                    row["bwd_speedup_lowrank_vs_dense"] = round(f_ms_db / ms_b, 3)
+                    row["dense_dbias_bytes"] = int(wo.B * wo.H * wo.N * wo.N * 2)
             others[name] = row
         result["other_workloads"] = others
 

@@ -150,6 +150,22 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
                         float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Backward of fb_dense_bias_attn_fwd, the training-side baseline: besides dq, dk, dv it has
+ * to write the dense gradient dbias [B,H,N,N] (= dL/dS, storage type `dtype`, always per batch
+ * element), the N x N object that the factorised form never materialises (Sec. 4.3, "record
+ * the gradient of the bias matrix").  Entries above the diagonal are zero when causal.
+ * Needs dtype = FB_BF16 and N % 8 == 0.  Workspace as for fb_lowrank_attn_bwd.
+ */
+size_t fb_dense_bias_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype);
+
+int fb_dense_bias_attn_bwd(const void* q, const void* k, const void* v, const void* bias,
+                           const void* out, const float* lse, const void* dout,
+                           void* dq, void* dk, void* dv, void* dbias,
+                           int B, int H, int N, int C, int causal,
+                           fb_dtype dtype, int bias_batch_broadcast, float scale,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Cross-attention form of fb_lowrank_attn_bwd: q, out, dout, dq [B,H,N,C]; k, v, dk, dv
  * [B,H,M,C]; phi_q, dphi_q [.,H,N,R]; phi_k, dphi_k [.,H,M,R]; lse [B,H,N].  No causal mask.
  * Workspace as for fb_lowrank_attn_bwd, sized by the query below.

@@ -23,6 +23,7 @@ EXPORTS = (
     "fb_version", "fb_status_string", "fb_tune_set", "fb_lowrank_attn_fwd", "fb_lowrank_xattn_fwd",
     "fb_alibi_attn_fwd", "fb_dense_bias_attn_fwd", "fb_lowrank_attn_bwd_workspace_bytes",
     "fb_lowrank_attn_bwd", "fb_lowrank_xattn_bwd_workspace_bytes", "fb_lowrank_xattn_bwd",
+    "fb_dense_bias_attn_bwd_workspace_bytes", "fb_dense_bias_attn_bwd",
 )
 
 
@@ -60,6 +61,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_lowrank_attn_bwd_workspace_bytes.argtypes = [ci] * 5 + [ci]
     lib.fb_lowrank_attn_bwd.restype = ci
     lib.fb_lowrank_attn_bwd.argtypes = [vp] * 13 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
+    lib.fb_dense_bias_attn_bwd_workspace_bytes.restype = sz
+    lib.fb_dense_bias_attn_bwd_workspace_bytes.argtypes = [ci] * 4 + [ci]
+    lib.fb_dense_bias_attn_bwd.restype = ci
+    lib.fb_dense_bias_attn_bwd.argtypes = [vp] * 11 + [ci] * 5 + [ci, ci, cf, vp, sz, vp]
     lib.fb_lowrank_xattn_bwd_workspace_bytes.restype = sz
     lib.fb_lowrank_xattn_bwd_workspace_bytes.argtypes = [ci] * 6 + [ci]
     lib.fb_lowrank_xattn_bwd.restype = ci
@@ -251,3 +256,36 @@ def fb_lowrank_xattn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, scale: float = 0
                                   workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "fb_lowrank_xattn_bwd")
     return dq, dk, dv, dpq, dpk
+
+
+def fb_dense_bias_attn_bwd_workspace_bytes(B, H, N, C, dtype_code=FB_BF16) -> int:
+    return int(load_library().fb_dense_bias_attn_bwd_workspace_bytes(B, H, N, C, dtype_code))
+
+
+def fb_lowrank_xattn_bwd_workspace_bytes(B, H, N, M, C, R, dtype_code=FB_BF16) -> int:
+    return int(load_library().fb_lowrank_xattn_bwd_workspace_bytes(B, H, N, M, C, R, dtype_code))
+
+
+def fb_dense_bias_attn_bwd(q, k, v, bias, out, lse, dout, causal=False, scale: float = 0.0,
+                           bias_batch_broadcast: Optional[bool] = None, workspace=None, grads=None,
+                           stream=None):
+    """dq, dk, dv, dbias ([B,H,N,N], q's dtype) for the dense-bias attention."""
+    lib = load_library()
+    B, H, N, C = q.shape
+    if bias_batch_broadcast is None:
+        bias_batch_broadcast = bias.shape[0] == 1 and B > 1
+    need = int(lib.fb_dense_bias_attn_bwd_workspace_bytes(B, H, N, C, _dtype_code(q)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    if grads is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        dbias = torch.empty((B, H, N, N), dtype=q.dtype, device=q.device)
+    else:
+        dq, dk, dv, dbias = grads
+    st = lib.fb_dense_bias_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(bias), _ptr(out), _ptr(lse),
+                                    _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dbias),
+                                    B, H, N, C, int(bool(causal)), _dtype_code(q),
+                                    int(bool(bias_batch_broadcast)), float(scale), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "fb_dense_bias_attn_bwd")
+    return dq, dk, dv, dbias

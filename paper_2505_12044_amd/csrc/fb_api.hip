@@ -232,6 +232,43 @@ static int lowrank_bwd_impl(const void* q, const void* k, const void* v,
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
+size_t fb_dense_bias_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype) {
+    (void)dtype;
+    return bwd_ws_impl(B, H, N, N, C, 0);
+}
+
+int fb_dense_bias_attn_bwd(const void* q, const void* k, const void* v, const void* bias,
+                           const void* out, const float* lse, const void* dout,
+                           void* dq, void* dk, void* dv, void* dbias,
+                           int B, int H, int N, int C, int causal,
+                           fb_dtype dtype, int bias_batch_broadcast, float scale,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !bias || !out || !lse || !dout || !dq || !dk || !dv || !dbias) return FB_ERR_NULL;
+    if (int st = check_common(B, H, N, C, 0)) return st;
+    if ((long long)B * H * N * (long long)N >= (1LL << 40)) return FB_ERR_SHAPE;
+    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if ((N % 8) != 0) return FB_ERR_UNSUPPORTED;      // bias rows are copied in 16-byte pieces
+    const void* ptrs[] = {q, k, v, bias, out, lse, dout, dq, dk, dv, dbias};
+    for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
+    if (!workspace || workspace_bytes < bwd_ws_impl(B, H, N, N, C, 0)) return FB_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FB_ERR_ALIGN;
+
+    BwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.phi_q = nullptr; p.phi_k = nullptr;
+    p.out = out; p.lse = lse; p.dout = dout;
+    p.dq = dq; p.dk = dk; p.dv = dv; p.dphi_q = nullptr; p.dphi_k = nullptr;
+    p.bias = bias; p.dbias = dbias;
+    p.bias_bstride = bias_batch_broadcast ? 0 : (long long)H * N * N;
+    p.workspace = workspace;
+    p.B = B; p.H = H; p.N = N; p.M = N; p.R = 0; p.causal = causal != 0;
+    p.phi_f32 = 0;
+    p.phi_bstride = 0;
+    p.phik_bstride = 0;
+    p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    const int rc = fb_launch_bwd_dense_bf16(p, C, (hipStream_t)stream);
+    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
 size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype) {
     (void)dtype;
     return bwd_ws_impl(B, H, N, N, C, R);

@@ -53,7 +53,7 @@ template <int N>
 FB_DEV void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
-FB_DEV void wait_vmcnt_n(int n) {   // n is wave-uniform, 0..7
+FB_DEV void wait_vmcnt_n(int n) {   // n is wave-uniform; larger values wait for 12 (stricter, still correct)
     switch (n) {
         case 0: wait_vmcnt<0>(); break;
         case 1: wait_vmcnt<1>(); break;
@@ -62,7 +62,12 @@ FB_DEV void wait_vmcnt_n(int n) {   // n is wave-uniform, 0..7
         case 4: wait_vmcnt<4>(); break;
         case 5: wait_vmcnt<5>(); break;
         case 6: wait_vmcnt<6>(); break;
-        default: wait_vmcnt<7>(); break;
+        case 7: wait_vmcnt<7>(); break;
+        case 8: wait_vmcnt<8>(); break;
+        case 9: wait_vmcnt<9>(); break;
+        case 10: wait_vmcnt<10>(); break;
+        case 11: wait_vmcnt<11>(); break;
+        default: wait_vmcnt<12>(); break;
     }
 }
 
@@ -205,13 +210,20 @@ struct MainArgs {
     const float2* vec;    // [B*H*N]  (lse * log2 e, D)
 };
 
-template <int C, int RP, bool CAUSAL, bool DKV>
+// DENSE (RP = 0 only): the bias is a dense [N][M] matrix instead of factors.  Every wave also
+// copies the 32 x 32 bias tile of (its lane rows) x (the streamed block) into the slot, two
+// direct loads per block; the S chain starts from those values; the dq kernel writes
+// dS = dBias from its packed operand registers.
+template <int C, int RP, bool CAUSAL, bool DKV, bool DENSE>
 FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem, const int bh, const int tile) {
+    static_assert(!DENSE || RP == 0, "dense bias and factors are exclusive");
     using K = Cfg<C, RP>;
     using T1 = typename K::T1;
     using T2 = typename K::T2;
-    constexpr int kSlotBytes = T1::BYTES + T2::BYTES + (DKV ? K::kVecBytes : 0);
+    constexpr int kBiasTile = 32 * 32 * 2;     // one wave's tile: 32 rows of 64 bytes
     constexpr int kOffT2 = T1::BYTES, kOffVec = T1::BYTES + T2::BYTES;
+    constexpr int kOffBias = kOffVec + (DKV ? K::kVecBytes : 0);
+    constexpr int kSlotBytes = kOffBias + (DENSE ? kWaves * kBiasTile : 0);
     constexpr int ND = T1::NDMA + T2::NDMA + (DKV ? 1 : 0);       // direct loads per block
     constexpr int NDW = (ND + kWaves - 1) / kWaves;               // ... per wave, at most
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -314,9 +326,76 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             }
         }
     };
-    auto wait_prev_loads = [&]() __attribute__((always_inline)) {   // all but the newest block's loads
-        if (my_ndma == NDW) wait_vmcnt<NDW>();
-        else wait_vmcnt<NDW - 1>();
+    // ---- dense bias tile of this wave: rows = queries, columns = keys, 64-byte rows; lane l of
+    // load i covers tile row 16*i + l/4; chunk position l%4 holds 8-key chunk (l%4) ^ ((row>>2)&3)
+    const int b_ = bh / p.H, h_ = bh - b_ * p.H;
+    const unsigned char* bias_src = nullptr;   // wave-uniform base of this wave's tiles
+    size_t bias_bstep = 0;                     // bytes per streamed block
+    int bias_var[2], bias_pitch = 0, bias_lshift = 0;
+    unsigned bias_fix[2];
+    if (DENSE) {
+        const bf16_t* bg = (const bf16_t*)p.bias + (size_t)b_ * p.bias_bstride + (size_t)h_ * p.N * p.M;
+        const int Mk = p.M;
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+            const int trow = 16 * i + (lane >> 2);
+            const int c = (lane & 3) ^ ((trow >> 2) & 3);
+            if (!DKV) {
+                // lane side = queries: fixed row per lane; the key chunk is clamped at the sequence end
+                const int rbase = min(rw0, NL - 1);
+                bias_fix[i] = (unsigned)(min(rw0 + trow, NL - 1) - rbase) * (unsigned)(Mk * 2);
+                bias_var[i] = c;
+                bias_src = (const unsigned char*)(bg + (size_t)rbase * Mk);
+            } else {
+                // lane side = keys: fixed 8-key chunk per lane; the query row is clamped at the end
+                const int kb = min(rw0, Mk - 8);
+                bias_fix[i] = (unsigned)(min(rw0 + 8 * c, Mk - 8) - kb) * 2u;
+                bias_var[i] = trow;
+                bias_src = (const unsigned char*)(bg + kb);
+            }
+        }
+        bias_pitch = DKV ? Mk * 2 : 16;
+        bias_lshift = DKV ? 0 : 3;
+        bias_bstep = DKV ? (size_t)BT * Mk * 2 : (size_t)BT * 2;
+    }
+    auto issue_bias = [&](int i, int slot) __attribute__((always_inline)) {
+        if (!DENSE) return;
+        const int blk = blk_of(i);
+        const int left = NS - blk * BT - 1;
+        const unsigned dst = lds0 + slot * kSlotBytes + kOffBias + wave * kBiasTile;
+#pragma unroll
+        for (int x = 0; x < 2; x++) {
+            const unsigned voff = (unsigned)(min(bias_var[x], left >> bias_lshift) * bias_pitch) + bias_fix[x];
+            dma16(bias_src + (size_t)blk * bias_bstep, voff, dst + x * 1024);
+        }
+    };
+    // all but the newest block's loads (plus `stores` global stores issued since) may remain
+    auto wait_prev_loads = [&](int stores) __attribute__((always_inline)) {
+        wait_vmcnt_n(my_ndma + (DENSE ? 2 : 0) + stores);
+    };
+    // per-lane offsets of the bias values of this lane's accumulator registers inside a tile:
+    // group g <-> registers 4g..4g+3
+    int boff[4];
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+        if (!DKV) {
+            boff[g] = l32 * 64 + ((g ^ ((l32 >> 2) & 3)) << 4) + hf * 8;             // row = query l32, keys 8g+4hf..
+        } else {
+            const int trow = 8 * g + 4 * hf + ((lane & 15) >> 2);                       // transpose read
+            const int chunk = 2 * (l32 >> 4) + (((lane & 15) & 3) >> 1);
+            boff[g] = trow * 64 + ((chunk ^ ((trow >> 2) & 3)) << 4) + (lane & 1) * 8;
+        }
+    }
+    auto bias_init = [&](f32x16& s, int slot_off) __attribute__((always_inline)) {
+        const unsigned char* tp = smem + (slot_off + kOffBias + wave * kBiasTile);
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            bf16x4 bv;
+            if (!DKV) bv = __builtin_bit_cast(bf16x4, *(const u32x2*)(tp + boff[g]));
+            else bv = __builtin_bit_cast(bf16x4, lds_read_tr16((const bf16_t*)(tp + boff[g])));
+#pragma unroll
+            for (int x = 0; x < 4; x++) s[4 * g + x] = (float)bv[x];
+        }
     };
 
     // ---- per-lane LDS read offsets (bytes inside a panel) ----
@@ -421,10 +500,10 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         // Ring of five slots: blocks i (transpose reads), i+1 (row reads), i+2 (prefetch),
         // i+3 (landing), i+4 (being issued).
         static_assert(NSLOT_DKV == 5, "slot arithmetic below assumes five slots");
-        issue_block(0, 0);
-        issue_block(1, 1);
-        issue_block(2, 2);
-        issue_block(3, 3);
+        issue_block(0, 0); issue_bias(0, 0);
+        issue_block(1, 1); issue_bias(1, 1);
+        issue_block(2, 2); issue_bias(2, 2);
+        issue_block(3, 3); issue_bias(3, 3);
         wait_vmcnt<0>();
         __syncthreads();
         f32x16 sA, dA, sB, dB;
@@ -433,6 +512,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             const TrBase t0 = mk_tr(0);
 #pragma unroll
             for (int r = 0; r < 16; r++) { sA[r] = 0.f; dA[r] = 0.f; }
+            if (DENSE) bias_init(sA, 0);
 #pragma unroll
             for (int n = 0; n < NA; n++) {
                 const bf16x8 o = read_op(r0, t0, n);
@@ -469,11 +549,13 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             const int sb0 = blk_of(i) * BT;
             const bool need_mask = (sb0 + BT > NS) || (CAUSAL && sb0 < rw0 + 31);
             bf16x8 pb[2], dsb[2];
+            f32x16 sinit = zero;
+            if (DENSE) bias_init(sinit, sl1 * kSlotBytes);      // S of block i+1 starts from its bias tile
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int n = 0; n < NA; n++) {
                 opr[(n + LA) % (LA + 1)] = read_op(rb1, tb0, n + LA);   // past NA: output operands of block i
-                if (n < K::KS) sn = mfma32(opr[n % (LA + 1)], l1reg[n], n == 0 ? zero : sn);
+                if (n < K::KS) sn = mfma32(opr[n % (LA + 1)], l1reg[n], n == 0 ? sinit : sn);
                 else dn = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], n == K::KS ? zero : dn);
 #pragma unroll
                 for (int e = (n * 16) / NA; e < ((n + 1) * 16) / NA; e++)
@@ -495,9 +577,10 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
                 }
             }
             // block i+2 has landed; everyone has left block i-1
-            wait_prev_loads();
+            wait_prev_loads(0);
             __syncthreads();
             issue_block(i + 4, sl4);
+            issue_bias(i + 4, sl4);
             bf16x8 nxt[LA];
 #pragma unroll
             for (int n = NA; n < NOPS; n++) {
@@ -524,12 +607,14 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         // Two waves per SIMD: the other workgroup's wave fills the gaps.  Iteration i:
         //     S, dP chains of block i | P, dS | wait, barrier | issue block i+3 |
         //     output chains of block i, first operand reads of block i+1
-        issue_block(0, 0);
-        issue_block(1, 1);
-        issue_block(2, 2);
+        issue_block(0, 0); issue_bias(0, 0);
+        issue_block(1, 1); issue_bias(1, 1);
+        issue_block(2, 2); issue_bias(2, 2);
         wait_vmcnt<0>();
         __syncthreads();
         RowBase rb0 = mk_row(0);
+        bf16_t* dbg = nullptr;      // dBias rows of this (b, h)
+        if (DENSE) dbg = (bf16_t*)p.dbias + (size_t)bh * p.N * p.M;
 #pragma unroll
         for (int n = 0; n < LA; n++) opr[n] = read_op(rb0, TrBase{}, n);
 
@@ -543,6 +628,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             f32x16 s, dp;
 #pragma unroll
             for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+            if (DENSE) bias_init(s, slot * kSlotBytes);
 #pragma unroll
             for (int n = 0; n < NA; n++) {
                 opr[(n + LA) % (LA + 1)] = read_op(rb0, tb0, n + LA);   // n + LA < NOPS: the output operands follow
@@ -562,10 +648,28 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
                     if (srow >= NS || (CAUSAL && srow > ri)) dsb[r / 8][r % 8] = (bf16_t)0.f;
                 }
             }
+            // ---------------- dBias = dS, straight from the packed operand registers ----------------
+            int nstores = 0;
+            if (DENSE) {
+                const int Mk = p.M;
+                if (ri < NL) {
+                    bf16_t* drow = dbg + (size_t)ri * Mk + sb0 + 4 * hf;
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        if (sb0 + 8 * g + 4 * hf < Mk) {
+                            const u32x4 w = as_uint4(dsb[g >> 1]);
+                            *(u32x2*)(drow + 8 * g) = (g & 1) ? u32x2{w.z, w.w} : u32x2{w.x, w.y};
+                        }
+                    }
+                }
+                // the wait below may count the stores only when every one of them is certain to issue
+                if (rw0 + 31 < NL && sb0 + BT <= Mk) nstores = 4;
+            }
             // ---------------- block i+1 has landed; everyone has left block i-1 ----------------
-            wait_prev_loads();
+            wait_prev_loads(nstores);
             __syncthreads();
             issue_block(i + 3, (i + 3) & (NSLOT - 1));
+            issue_bias(i + 3, (i + 3) & (NSLOT - 1));
 
             // ---------------- second half: output chains ----------------
             bf16x8 nxt[LA];      // first operands of block i+1 (the window restarts at 0 with every block)
@@ -579,6 +683,15 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
             for (int n = 0; n < LA; n++) opr[n] = nxt[n];
             rb0 = rbn;
+        }
+        if (DENSE && CAUSAL && ri < NL) {
+            // key blocks above the diagonal are never visited: their dBias is zero
+            for (int blk = b_end; blk < nblk_all; blk++) {
+                bf16_t* drow = dbg + (size_t)ri * p.M + blk * BT + 4 * hf;
+#pragma unroll
+                for (int g = 0; g < 4; g++)
+                    if (blk * BT + 8 * g + 4 * hf < p.M) *(u32x2*)(drow + 8 * g) = u32x2{0u, 0u};
+            }
         }
     }
     wait_vmcnt<0>();     // no direct load may outlive this tile's use of the ring
@@ -630,8 +743,8 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 
 // Work units: one 128-row tile per workgroup, or when causal the tile pair (n-1-u, u), whose
 // streamed ranges add up to the same length for every u (no tail of heavy tiles).
-template <int C, int RP, bool CAUSAL, bool DKV>
-__global__ __launch_bounds__(kThreads, (DKV || (C == 128 && RP > 32)) ? 1 : 2) void bwd_main_kernel(BwdParams p, MainArgs a) {
+template <int C, int RP, bool CAUSAL, bool DKV, bool DENSE = false>
+__global__ __launch_bounds__(kThreads, (DKV || DENSE || (C == 128 && RP > 32)) ? 1 : 2) void bwd_main_kernel(BwdParams p, MainArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
     if (L >= p.total_tiles) return;
@@ -641,13 +754,13 @@ __global__ __launch_bounds__(kThreads, (DKV || (C == 128 && RP > 32)) ? 1 : 2) v
     if (CAUSAL) {
         const int other = p.n_tiles - 1 - u;
         // heavier tile first: high query tiles for dq, low key tiles for dkv
-        bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, DKV ? u : other);
+        bwd_tile<C, RP, CAUSAL, DKV, DENSE>(p, a, smem, bh, DKV ? u : other);
         if (u != other) {
             __syncthreads();   // the epilogue's LDS scratch is reused as ring memory
-            bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, DKV ? other : u);
+            bwd_tile<C, RP, CAUSAL, DKV, DENSE>(p, a, smem, bh, DKV ? other : u);
         }
     } else {
-        bwd_tile<C, RP, CAUSAL, DKV>(p, a, smem, bh, u);
+        bwd_tile<C, RP, CAUSAL, DKV, DENSE>(p, a, smem, bh, u);
     }
 }
 
@@ -710,6 +823,51 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
+// Dense-bias backward: same pre-pass and kernels with RP = 0 and the bias tiles streamed.
+template <int C, bool CAUSAL>
+int launch_dense(const BwdParams& pin, hipStream_t stream) {
+    using K = Cfg<C, 0>;
+    constexpr size_t slot = K::T1::BYTES + K::T2::BYTES + (size_t)kWaves * 32 * 32 * 2;
+    constexpr size_t lds_dq = (size_t)NSLOT * slot;
+    constexpr size_t lds_dkv = (size_t)NSLOT_DKV * (slot + K::kVecBytes);
+    auto kdq = bwd_main_kernel<C, 0, CAUSAL, false, true>;
+    auto kdkv = bwd_main_kernel<C, 0, CAUSAL, true, true>;
+    static bool done_dq = false, done_dkv = false;
+    if (!set_lds(kdq, lds_dq, &done_dq) || !set_lds(kdkv, lds_dkv, &done_dkv)) return 1;
+
+    const long long rows = (long long)pin.B * pin.H * pin.N;
+    const long long rowsk = (long long)pin.B * pin.H * pin.M;
+    unsigned char* ws = (unsigned char*)pin.workspace;
+    MainArgs a;
+    a.vec = (const float2*)ws;
+    bf16_t* aq = (bf16_t*)(ws + (((size_t)rows * 8 + 15) & ~(size_t)15));
+    bf16_t* ak = aq + (size_t)rows * K::W;
+    a.aq = aq;
+    a.ak = ak;
+    hipLaunchKernelGGL((bwd_vec_kernel<C>), dim3((unsigned)((rows * (C / 8) + 255) / 256)), dim3(256), 0, stream,
+                       (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
+    if (hipGetLastError() != hipSuccess) return 1;
+    hipLaunchKernelGGL((bwd_prep_kernel<C, 0, true>), dim3((unsigned)((rows * (K::W / 8) + 255) / 256)),
+                       dim3(256), 0, stream, pin, aq);
+    if (hipGetLastError() != hipSuccess) return 1;
+    hipLaunchKernelGGL((bwd_prep_kernel<C, 0, false>), dim3((unsigned)((rowsk * (K::W / 8) + 255) / 256)),
+                       dim3(256), 0, stream, pin, ak);
+    if (hipGetLastError() != hipSuccess) return 1;
+    auto set_tiles = [](BwdParams& p, int lane_rows) {
+        p.n_tiles = (lane_rows + 127) / 128;
+        const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
+        p.total_tiles = p.B * p.H * n_units;
+        p.tiles_per_xcd = (p.total_tiles + 7) / 8;
+    };
+    BwdParams p = pin;
+    set_tiles(p, p.M);
+    hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p, a);
+    if (hipGetLastError() != hipSuccess) return 1;
+    set_tiles(p, p.N);
+    hipLaunchKernelGGL(kdq, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dq, stream, p, a);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
 template <int C, int RP>
 int dispatch_causal(const BwdParams& p, hipStream_t stream) {
     return p.causal ? launch<C, RP, true>(p, stream) : launch<C, RP, false>(p, stream);
@@ -733,6 +891,15 @@ size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R) 
     // R alone does not say whether the factors are fp32 (6 R columns): size for the widest rows
     const int w = C + (R > 0 ? 64 : 0);
     return (((size_t)rows_q * 8 + 15) & ~(size_t)15) + (size_t)(rows_q + rows_k) * w * 2;
+}
+
+int fb_launch_bwd_dense_bf16(const BwdParams& p, int C, hipStream_t stream) {
+    switch (C) {
+        case 32: return p.causal ? launch_dense<32, true>(p, stream) : launch_dense<32, false>(p, stream);
+        case 64: return p.causal ? launch_dense<64, true>(p, stream) : launch_dense<64, false>(p, stream);
+        case 128: return p.causal ? launch_dense<128, true>(p, stream) : launch_dense<128, false>(p, stream);
+        default: return -1;
+    }
 }
 
 int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream) {

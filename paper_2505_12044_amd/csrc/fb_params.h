@@ -34,6 +34,9 @@ struct BwdParams {
     const void* phi_q; const void* phi_k;
     const void* out; const float* lse; const void* dout;
     void* dq; void* dk; void* dv; void* dphi_q; void* dphi_k;
+    const void* bias;     // [Bb,H,N,M] dense-bias backward only
+    void* dbias;          // [B,H,N,M]
+    long long bias_bstride;  // elements between batch items of bias (0 when shared)
     void* workspace;      // device scratch: (lse2, D) rows and the concatenated operand rows
     int B, H, N, R;       // N = number of queries
     int M;                // number of keys (= N except for cross-attention)

@@ -1,0 +1,48 @@
+"""GPU parity of fb_dense_bias_attn_bwd (the training-side baseline that has to write the dense
+N x N bias gradient) against the float64 oracle's chain rule.  Tolerance as for the factorised
+backward: 5e-2 on every gradient, scaled by max|ref| / 2.5 where the reference exceeds 2.5."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fb_oracle as O
+from paper_2505_12044_amd import api, workloads as W
+from tests._gpu_util import GRAD_TOL, dev, host, max_abs
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    (1, 2, 256, 128, False, False),
+    (2, 2, 520, 64, True, False),      # 520 = 16 * 32 + 8: ragged last key block
+    (1, 2, 384, 32, True, False),
+    (1, 1, 8, 64, False, False),
+    (2, 2, 512, 128, True, True),      # bias shared over the batch
+    (2, 1, 200, 64, False, True),
+]
+
+
+@pytest.mark.parametrize("B,H,N,C,causal,shared", CASES)
+def test_dense_backward(B, H, N, C, causal, shared):
+    rng = np.random.default_rng(7000 + N + C)
+    rd = lambda shape: W.round_bf16(rng.standard_normal(shape).astype(np.float32))
+    q, k, v, dout = rd((B, H, N, C)), rd((B, H, N, C)), rd((B, H, N, C)), rd((B, H, N, C))
+    bias = rd((1 if shared else B, H, N, N))
+    d = [dev(x, "bf16") for x in (q, k, v)]
+    db = dev(bias, "bf16")
+    out, lse = api.fb_dense_bias_attn_fwd(*d, db, causal=causal)
+    dq, dk, dv, dbias = api.fb_dense_bias_attn_bwd(*d, db, out, lse, dev(dout, "bf16"), causal=causal)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for b in range(B):
+        for h in range(H):
+            ref = O.attention_with_bias_grads(q[b, h], k[b, h], v[b, h], bias[0 if shared else b, h], dout[b, h],
+                                              causal=causal)
+            for name, g, r in zip(("dq", "dk", "dv", "dbias"), (dq, dk, dv, dbias), ref):
+                gh = host(g[b, h])
+                assert np.isfinite(gh).all(), name
+                e = max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5)
+                worst = max(worst, e)
+            if causal:
+                assert float(np.abs(np.triu(host(dbias[b, h]), 1)).max()) == 0.0
+    print(f"dense bwd B{B} H{H} N{N} C{C} causal={causal} shared={shared}: worst scaled err {worst:.3e}", flush=True)
+    assert worst <= GRAD_TOL

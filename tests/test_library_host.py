@@ -70,6 +70,12 @@ def test_dense_and_backward_argument_errors(lib):
     assert f(64, 64, 64, None, 64, 64, 1, 1, 16, 64, 0, api.FB_BF16, 0, 0.0, None) == 1
     assert f(64, 64, 64, 64, 64, 64, 1, 1, 16, 96, 0, api.FB_BF16, 0, 0.0, None) == 3
     assert f(64, 64, 64, 68, 64, 64, 1, 1, 16, 64, 0, api.FB_BF16, 0, 0.0, None) == 4
+    db = lib.fb_dense_bias_attn_bwd
+    wsd = lib.fb_dense_bias_attn_bwd_workspace_bytes(1, 1, 64, 64, api.FB_BF16)
+    assert wsd == 64 * 8 + 2 * 64 * 64 * 2
+    assert db(*([64] * 10), None, 1, 1, 64, 64, 0, api.FB_BF16, 0, 0.0, 64, wsd, None) == 1         # dbias NULL
+    assert db(*([64] * 11), 1, 1, 60, 64, 0, api.FB_BF16, 0, 0.0, 64, wsd, None) == 3               # N % 8 != 0
+    assert db(*([64] * 11), 1, 1, 64, 64, 0, api.FB_BF16, 0, 0.0, 64, wsd - 1, None) == 5
     a = lib.fb_alibi_attn_fwd
     assert a(64, 64, 64, None, 64, 64, 1, 1, 16, 64, 1, api.FB_BF16, 0.0, None) == 1      # slopes NULL
     assert a(64, 64, 64, 64, 64, 64, 1, 1, 16, 64, 1, api.FB_F32, 0.0, None) == 3         # bf16 only
