@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __re
         const int i = (int)(row - bh * len);
         const int bb = (int)(bh / p.H), h = (int)(bh - (long long)bb * p.H);
         const size_t off = ((size_t)bb * (QSIDE ? p.phi_bstride : p.phik_bstride) + ((size_t)h * len + i) * p.R) * esz;
-        a = phi_chunk_gather<QSIDE>((const unsigned char*)(QSIDE ? p.phi_q : p.phi_k) + off, c - C / 8, p.R, f32);
+        a = phi_chunk_switch<QSIDE>((const unsigned char*)(QSIDE ? p.phi_q : p.phi_k) + off, c - C / 8, p.R, f32);
     }
     *(u32x4*)(dst + row * K::W + c * 8) = as_uint4(a);
 }

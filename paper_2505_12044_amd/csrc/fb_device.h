@@ -188,4 +188,50 @@ FB_DEV bf16x8 phi_chunk_from_pair(int c8, float x0, float x1) {
     return out;
 }
 
+// phi_chunk_gather with the chunk index known at compile time: the rank and limb slot of each
+// of the eight columns are constants, so an fp32 chunk costs at most three loads and three
+// limb splits instead of eight of each.
+template <bool QSIDE, int C8>
+FB_DEV bf16x8 phi_chunk_static(const void* row, int R, bool f32) {
+    bf16x8 out;
+    if (!f32) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) out[e] = (C8 * 8 + e < R) ? ((const bf16_t*)row)[C8 * 8 + e] : (bf16_t)0.f;
+        return out;
+    }
+    constexpr int r0 = (C8 * 8) / 6;
+    bf16_t limb[3][3];
+#pragma unroll
+    for (int d = 0; d < 3; d++) {
+        const float x = (r0 + d < R && r0 + d <= (C8 * 8 + 7) / 6) ? ((const float*)row)[r0 + d] : 0.f;
+        const bf16_t l1 = (bf16_t)x;
+        const float e1 = x - (float)l1;
+        const bf16_t l2 = (bf16_t)e1;
+        limb[d][0] = l1;
+        limb[d][1] = l2;
+        limb[d][2] = (bf16_t)(e1 - (float)l2);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        constexpr int dummy = 0; (void)dummy;
+        const int j = C8 * 8 + e;
+        const int r = j / 6, slot = j - 6 * r;
+        out[e] = limb[r - r0][QSIDE ? q_limb_of_slot(slot) : k_limb_of_slot(slot)];
+    }
+    return out;
+}
+template <bool QSIDE>
+FB_DEV bf16x8 phi_chunk_switch(const void* row, int c8, int R, bool f32) {
+    switch (c8) {
+        case 0: return phi_chunk_static<QSIDE, 0>(row, R, f32);
+        case 1: return phi_chunk_static<QSIDE, 1>(row, R, f32);
+        case 2: return phi_chunk_static<QSIDE, 2>(row, R, f32);
+        case 3: return phi_chunk_static<QSIDE, 3>(row, R, f32);
+        case 4: return phi_chunk_static<QSIDE, 4>(row, R, f32);
+        case 5: return phi_chunk_static<QSIDE, 5>(row, R, f32);
+        case 6: return phi_chunk_static<QSIDE, 6>(row, R, f32);
+        default: return phi_chunk_static<QSIDE, 7>(row, R, f32);
+    }
+}
+
 #endif
