@@ -74,6 +74,14 @@ FB_DEV bf16x8 join_tr(s16x4 lo, s16x4 hi) {
 
 FB_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// acc + a.x + a.y for a packed bf16 pair (v_dot2c_f32_bf16 against {1, 1}): the softmax row sum
+// taken over the bf16-rounded probabilities, i.e. over exactly the values the second MFMA
+// multiplies with V, at one instruction per two elements.
+FB_DEV float pair_sum(bf16x2 a, float acc) {
+    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(a, ones, acc, false);
+}
+
 // Maximum of the 16 accumulator registers as a shallow tree (three-input maxima, depth 3)
 // rather than a 15-deep dependent chain.
 FB_DEV float max3f(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }

@@ -451,10 +451,12 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             const float nm = mref[qb] == -INFINITY ? 0.f : -mref[qb];
             float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const float pr = fast_exp2(fmaf(s[qb][r], kLog2e, nm));
-                ps[r & 3] += pr;
-                pb[qb][r / 8][r % 8] = (bf16_t)pr;
+            for (int r = 0; r < 16; r += 2) {
+                const bf16x2 pr2 = {(bf16_t)fast_exp2(fmaf(s[qb][r], kLog2e, nm)),
+                                    (bf16_t)fast_exp2(fmaf(s[qb][r + 1], kLog2e, nm))};
+                ps[(r >> 1) & 3] = pair_sum(pr2, ps[(r >> 1) & 3]);
+                pb[qb][r / 8][r % 8] = pr2[0];
+                pb[qb][r / 8][r % 8 + 1] = pr2[1];
             }
             lsum[qb] += (ps[0] + ps[1]) + (ps[2] + ps[3]);
         }

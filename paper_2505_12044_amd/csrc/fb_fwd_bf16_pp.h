@@ -312,10 +312,12 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
             const float nm = -mref;
             float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const float pr = fast_exp2(fmaf(s[r], kLog2e, nm));
-                ps[r & 3] += pr;
-                pb[r / 8][r % 8] = (bf16_t)pr;
+            for (int r = 0; r < 16; r += 2) {
+                const bf16x2 pr2 = {(bf16_t)fast_exp2(fmaf(s[r], kLog2e, nm)),
+                                    (bf16_t)fast_exp2(fmaf(s[r + 1], kLog2e, nm))};
+                ps[(r >> 1) & 3] = pair_sum(pr2, ps[(r >> 1) & 3]);
+                pb[r / 8][r % 8] = pr2[0];
+                pb[r / 8][r % 8 + 1] = pr2[1];
             }
             lsum += (ps[0] + ps[1]) + (ps[2] + ps[3]);
         }
