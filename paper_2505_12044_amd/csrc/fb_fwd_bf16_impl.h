@@ -58,10 +58,11 @@ constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int BK = 32;       // keys per block
 constexpr int NBUF = 3;      // LDS ring depth
-// The running reference maximum of a row is only raised when the true maximum exceeds it by
-// more than this (log2 units); until then probabilities are at most 2^tau, which fp32 sums
-// and bf16 P (same exponent range) hold without loss.  The final o = O / l is unaffected.
-constexpr float kRescaleTau = 8.0f;
+// The running reference maximum of a row is only raised when a lane's partial sum of the
+// block's probabilities reaches 2^tau; until then every probability is below 2^tau, which
+// fp32 sums and bf16 P (same exponent range) hold without loss.  The final o = O / l is
+// unaffected by the choice of reference.
+constexpr float kSumLimit = 256.0f;   // 2^tau, tau = 8
 
 template <int C, int RP, int QB>
 struct Cfg {
@@ -149,10 +150,12 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 
     f32x16 oacc[QB][C / 32];
     float mref[QB], lsum[QB];
+    bool ref_ok[QB];      // wave-uniform: every row of the wave has a finite reference maximum
 #pragma unroll
     for (int qb = 0; qb < QB; qb++) {
         mref[qb] = -INFINITY;
         lsum[qb] = 0.f;
+        ref_ok[qb] = false;
 #pragma unroll
         for (int cb = 0; cb < C / 32; cb++)
 #pragma unroll
@@ -436,29 +439,49 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                     if (key >= M || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
                 }
             }
-            float mx = half_max(max16(s[qb])) * kLog2e;
-            if (__any(mx > mref[qb] + kRescaleTau)) {
-                const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
-                const float alpha = fast_exp2(mref[qb] - mnew);
-                mref[qb] = mnew;
-                lsum[qb] *= alpha;
+            // P = exp2(S log2e - mref), packed to bf16, and this lane's partial row sum
+            auto exps = [&](float nm) __attribute__((always_inline)) {
+                float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
-                for (int cb = 0; cb < C / 32; cb++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) oacc[qb][cb][r] *= alpha;
+                for (int r = 0; r < 16; r += 2) {
+                    const bf16x2 pr2 = {(bf16_t)fast_exp2(fmaf(s[qb][r], kLog2e, nm)),
+                                        (bf16_t)fast_exp2(fmaf(s[qb][r + 1], kLog2e, nm))};
+                    ps[(r >> 1) & 3] = pair_sum(pr2, ps[(r >> 1) & 3]);
+                    pb[qb][r / 8][r % 8] = pr2[0];
+                    pb[qb][r / 8][r % 8 + 1] = pr2[1];
+                }
+                return (ps[0] + ps[1]) + (ps[2] + ps[3]);
+            };
+            // Fast path: once every row of the wave has a finite reference maximum, the block's row
+            // maximum is not computed at all.  Any reference is exact as long as nothing overflows,
+            // and the partial row sum (needed anyway) bounds every probability from above: if it
+            // stays below 2^tau in every lane, so did each of them.  inf and NaN fail the test too.
+            float psum = 0.f;
+            bool done = false;
+            if (ref_ok[qb]) {
+                psum = exps(-mref[qb]);
+                done = !__any(!(psum < kSumLimit));
             }
-            // a row that has not met a visible key yet (causal, reverse order) keeps p = 0
-            const float nm = mref[qb] == -INFINITY ? 0.f : -mref[qb];
-            float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
+            if (!done) {
+                // first visible blocks of a tile, or the scores outgrew the reference: take the true
+                // row maximum, rescale what has been accumulated, and redo the exponentials
+                asm volatile("" ::: "memory");   // keep this a real (rarely taken) branch
+                const float mx = half_max(max16(s[qb])) * kLog2e;
+                if (__any(mx > mref[qb])) {
+                    const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
+                    const float alpha = fast_exp2(mref[qb] - mnew);
+                    mref[qb] = mnew;
+                    lsum[qb] *= alpha;
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const bf16x2 pr2 = {(bf16_t)fast_exp2(fmaf(s[qb][r], kLog2e, nm)),
-                                    (bf16_t)fast_exp2(fmaf(s[qb][r + 1], kLog2e, nm))};
-                ps[(r >> 1) & 3] = pair_sum(pr2, ps[(r >> 1) & 3]);
-                pb[qb][r / 8][r % 8] = pr2[0];
-                pb[qb][r / 8][r % 8 + 1] = pr2[1];
+                    for (int cb = 0; cb < C / 32; cb++)
+#pragma unroll
+                        for (int r = 0; r < 16; r++) oacc[qb][cb][r] *= alpha;
+                }
+                // a row that has not met a visible key yet (causal, reverse order) keeps p = 0
+                psum = exps(mref[qb] == -INFINITY ? 0.f : -mref[qb]);
+                if (!ref_ok[qb]) ref_ok[qb] = !__any(mref[qb] == -INFINITY);
             }
-            lsum[qb] += (ps[0] + ps[1]) + (ps[2] + ps[3]);
+            lsum[qb] += psum;
         }
         __builtin_amdgcn_sched_barrier(0);
         FB_T4(3)

@@ -43,7 +43,7 @@ constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int BK = 32;
 constexpr int NBUF = 4;
-constexpr float kRescaleTau = 8.0f;
+constexpr float kSumLimit = 256.0f;   // 2^tau: bound on a lane's partial probability sum per block
 
 template <int C, int RP>
 struct Cfg {
@@ -126,6 +126,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
 #pragma unroll
         for (int r = 0; r < 16; r++) oacc[cb][r] = 0.f;
     float mref = -INFINITY, lsum = 0.f;
+    bool ref_ok = false;   // wave-uniform: every row of the wave has a finite reference maximum
 
     const int kend = CAUSAL ? min(N, q0 + K::BQ) : N;
     const int nT = (kend + BK - 1) / BK;
@@ -296,20 +297,9 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
                 if (key >= N || (CAUSAL && key > qi)) s[r] = -INFINITY;
             }
         }
-        float mx = half_max(max16(s)) * kLog2e;
-        if (__any(mx > mref + kRescaleTau)) {
-            const float mnew = fmaxf(fmaxf(mref, mx), -1e30f);
-            const float alpha = fast_exp2(mref - mnew);
-            mref = mnew;
-            lsum *= alpha;
-#pragma unroll
-            for (int cb = 0; cb < C / 32; cb++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) oacc[cb][r] *= alpha;
-        }
         bf16x8 pb[2];
-        {
-            const float nm = -mref;
+        // P = exp2(S log2e - mref), packed to bf16, and this lane's partial row sum
+        auto exps = [&](float nm) __attribute__((always_inline)) {
             float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
@@ -319,8 +309,33 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
                 pb[r / 8][r % 8] = pr2[0];
                 pb[r / 8][r % 8 + 1] = pr2[1];
             }
-            lsum += (ps[0] + ps[1]) + (ps[2] + ps[3]);
+            return (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        };
+        // Fast path without the row maximum (see fb_fwd_bf16_impl.h): the partial row sum bounds
+        // every probability; inf and NaN fail the test as well.
+        float psum = 0.f;
+        bool done = false;
+        if (ref_ok) {
+            psum = exps(-mref);
+            done = !__any(!(psum < kSumLimit));
         }
+        if (!done) {
+            asm volatile("" ::: "memory");   // keep this a real (rarely taken) branch
+            const float mx = half_max(max16(s)) * kLog2e;
+            if (__any(mx > mref)) {
+                const float mnew = fmaxf(fmaxf(mref, mx), -1e30f);
+                const float alpha = fast_exp2(mref - mnew);
+                mref = mnew;
+                lsum *= alpha;
+#pragma unroll
+                for (int cb = 0; cb < C / 32; cb++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) oacc[cb][r] *= alpha;
+            }
+            psum = exps(mref == -INFINITY ? 0.f : -mref);
+            if (!ref_ok) ref_ok = !__any(mref == -INFINITY);
+        }
+        lsum += psum;
         __builtin_amdgcn_sched_barrier(0);
         FB_T(2)
         __syncthreads();
