@@ -295,6 +295,29 @@ def main() -> int:
                     row["bwd_speedup_lowrank_vs_dense"] = round(f_ms_db / ms_b, 3)
                     row["dense_dbias_bytes"] = int(wo.B * wo.H * wo.N * wo.N * 2)
             others[name] = row
+        # the PDE-solver shape (Sec. 4.3): ragged N, head dimension 16, rank-9 fp32 distance factors
+        del d
+        torch.cuda.empty_cache()
+        wp = W.make_pde_workload()
+        d = to_device(wp)
+        ws = torch.empty(api.fb_lowrank_attn_bwd_workspace_bytes(wp.B, wp.H, wp.N, wp.C, wp.R),
+                         dtype=torch.uint8, device="cuda")
+
+        def f3():
+            api.fb_lowrank_attn_fwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out=d["out"],
+                                    lse=d["lse"], stream=stream)
+
+        def b3():
+            api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], d["out"], d["lse"],
+                                    d["dout"], workspace=ws, stream=stream)
+        _, ms_f = time_calls(f3, 10, 2)
+        _, ms_b = time_calls(b3, 5, 1)
+        others["pde_distance"] = {
+            "B": wp.B, "H": wp.H, "N": wp.N, "C": wp.C, "R": wp.R, "phi_dtype": "f32",
+            "fwd_ms": round(ms_f, 4), "fwd_TFLOPs": round(wp.fwd_flops() / (ms_f * 1e-3) / 1e12, 2),
+            "bwd_ms": round(ms_b, 4), "bwd_TFLOPs": round(wp.bwd_flops() / (ms_b * 1e-3) / 1e12, 2),
+            "dense_bias_bytes_avoided": int(wp.H * wp.N * wp.N * 2)}
+        del ws
         result["other_workloads"] = others
 
     # ------------------------------------------------------------------ CPU oracle

@@ -27,9 +27,11 @@
  *     into three bf16 limbs inside the kernel (six product columns per rank), which keeps
  *     ~24 bits of each factor (needed e.g. for ALiBi positions up to N).  With
  *     dtype = FB_F32 everything is fp32 FMA and phi_dtype must be FB_F32.
- *   - Supported: C in {32, 64, 128}; 0 <= R, with the padded factor width (R for bf16
- *     factors, 6R for fp32 factors in a bf16 run, rounded up to 16) at most 64 (forward) or
- *     32 (backward); fp32 forward: R <= 64.  R = 0 (phi pointers may be NULL) is plain attention.
+ *   - Supported: C in {16, 32, 64, 128} (fb_dense_bias_attn_bwd: not 16); 0 <= R, with the
+ *     padded factor width (R for bf16 factors, 6R for fp32 factors in a bf16 run, rounded up
+ *     to 16) at most 64; fp32 forward: R <= 64.  R = 0 (phi pointers may be NULL) is plain
+ *     attention.  C = 16 (the PDE-solver head dimension of Sec. 4.3) runs on the 32-channel
+ *     bf16 tiles with the missing channels zero-filled inside the kernels.
  *   - scale <= 0 selects 1/sqrt(C).
  *   - stream is a hipStream_t passed as void*; NULL is the default stream.  Calls only
  *     enqueue work: they never synchronise and never block on the device.
@@ -136,7 +138,8 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
  * reused as soon as the call's work on `stream` has finished.  It receives, per (b, h, i):
  * (lse * log2 e, D_i = sum_c dout * out) and the concatenated bf16 operand rows
  * [q*scale | phi_q | 0] and [k | phi_k | 0] that the two main kernels stream
- * (8 + 4 * (C + 64) bytes per row when R > 0, 8 + 4 * C otherwise).
+ * (8 + 4 * (C + 64) bytes per row when R > 0, 8 + 4 * C otherwise; C = 16 counts as 32 and
+ * adds 32-channel copies of v and dout, 128 more bytes per row).
  * Results are deterministic (no floating-point atomics).
  */
 size_t fb_lowrank_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype);
@@ -154,7 +157,7 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
  * to write the dense gradient dbias [B,H,N,N] (= dL/dS, storage type `dtype`, always per batch
  * element), the N x N object that the factorised form never materialises (Sec. 4.3, "record
  * the gradient of the bias matrix").  Entries above the diagonal are zero when causal.
- * Needs dtype = FB_BF16 and N % 8 == 0.  Workspace as for fb_lowrank_attn_bwd.
+ * Needs dtype = FB_BF16, N % 8 == 0 and C >= 32.  Workspace as for fb_lowrank_attn_bwd.
  */
 size_t fb_dense_bias_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype);
 

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflashbias.so")
 
-SOURCES = ["fb_api.hip", "fb_fwd_f32.hip", "fb_fwd_bf16.hip", "fb_fwd_bf16_c32.hip",
+SOURCES = ["fb_api.hip", "fb_fwd_f32.hip", "fb_fwd_bf16.hip", "fb_fwd_bf16_c16.hip", "fb_fwd_bf16_c32.hip",
            "fb_fwd_bf16_c64.hip", "fb_fwd_bf16_c128.hip", "fb_fwd_bf16_alibi.hip", "fb_bwd_bf16.hip"]
 
 FLAGS = [

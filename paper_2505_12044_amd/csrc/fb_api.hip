@@ -26,7 +26,7 @@ int padded_rank(int R, fb_dtype dtype, fb_dtype phi_dtype) {
 int check_common(int B, int H, int N, int C, int R) {
     if (B <= 0 || H <= 0 || N <= 0 || R < 0) return FB_ERR_SHAPE;
     if ((long long)B * H * N * (long long)(C > R ? C : R) >= (1LL << 31)) return FB_ERR_SHAPE;
-    if (C != 32 && C != 64 && C != 128) return FB_ERR_UNSUPPORTED;
+    if (C != 16 && C != 32 && C != 64 && C != 128) return FB_ERR_UNSUPPORTED;
     return FB_OK;
 }
 
@@ -223,7 +223,7 @@ static int lowrank_bwd_impl(const void* q, const void* k, const void* v,
     p.out = out; p.lse = lse; p.dout = dout;
     p.dq = dq; p.dk = dk; p.dv = dv; p.dphi_q = dphi_q; p.dphi_k = dphi_k;
     p.workspace = workspace;
-    p.B = B; p.H = H; p.N = N; p.M = M; p.R = R; p.causal = causal != 0;
+    p.B = B; p.H = H; p.N = N; p.M = M; p.R = R; p.Cg = C; p.causal = causal != 0;
     p.phi_f32 = phi_dtype == FB_F32;
     p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
     p.phik_bstride = phi_batch_broadcast ? 0 : (long long)H * M * R;
@@ -260,7 +260,7 @@ int fb_dense_bias_attn_bwd(const void* q, const void* k, const void* v, const vo
     p.bias = bias; p.dbias = dbias;
     p.bias_bstride = bias_batch_broadcast ? 0 : (long long)H * N * N;
     p.workspace = workspace;
-    p.B = B; p.H = H; p.N = N; p.M = N; p.R = 0; p.causal = causal != 0;
+    p.B = B; p.H = H; p.N = N; p.M = N; p.R = 0; p.Cg = C; p.causal = causal != 0;
     p.phi_f32 = 0;
     p.phi_bstride = 0;
     p.phik_bstride = 0;

@@ -130,7 +130,13 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __re
     if (row >= rows) return;
     bf16x8 a;
     if (c < C / 8) {
-        const bf16x8 x = as_bf16x8(*(const u32x4*)((const bf16_t*)(QSIDE ? p.q : p.k) + row * C + c * 8));
+        bf16x8 x;
+        if (c * 8 < p.Cg) {
+            x = as_bf16x8(*(const u32x4*)((const bf16_t*)(QSIDE ? p.q : p.k) + row * p.Cg + c * 8));
+        } else {      // channels the caller's rows do not have
+#pragma unroll
+            for (int e = 0; e < 8; e++) x[e] = (bf16_t)0.f;
+        }
         if (QSIDE) {
 #pragma unroll
             for (int e = 0; e < 8; e++) a[e] = (bf16_t)((float)x[e] * p.scale);
@@ -168,6 +174,19 @@ __global__ __launch_bounds__(256) void bwd_vec_kernel(const bf16_t* __restrict__
 #pragma unroll
     for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
     if (c8 == 0 && row < rows) vec[row] = make_float2(lse[row] * kLog2e, acc);
+}
+
+// Head dimension 16: rows of 16 channels widened to 32 with zeros (the main kernels stream
+// v and dO tiles of 32 channels).  One thread per 16-byte piece of the destination.
+__global__ __launch_bounds__(256) void bwd_pad16_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                                        long long rows) {
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long row = gid >> 2;
+    const int c = (int)(gid & 3);
+    if (row >= rows) return;
+    u32x4 x = u32x4{0u, 0u, 0u, 0u};
+    if (c < 2) x = *(const u32x4*)(src + row * 16 + c * 8);
+    *(u32x4*)(dst + row * 32 + c * 8) = x;
 }
 
 // Write one wave's factor-gradient columns to LDS scratch and reduce limb columns.
@@ -699,15 +718,17 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 
     // ---- epilogue ----
     const bool rok = ri < NL;
-    const size_t base = (size_t)bh * NL * C;
+    const int Cg = p.Cg;      // channels of the caller's gradient rows (< C: the rest is not stored)
+    const size_t base = (size_t)bh * NL * Cg;
     if (rok) {
         if (DKV) {
-            bf16_t* dvg = (bf16_t*)p.dv + base + (size_t)ri * C;
-            bf16_t* dkg = (bf16_t*)p.dk + base + (size_t)ri * C;
+            bf16_t* dvg = (bf16_t*)p.dv + base + (size_t)ri * Cg;
+            bf16_t* dkg = (bf16_t*)p.dk + base + (size_t)ri * Cg;
 #pragma unroll
             for (int mb = 0; mb < K::MBC; mb++)
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
+                    if (mb * 32 + 8 * g >= Cg) continue;
                     bf16x4 a4, b4;
 #pragma unroll
                     for (int x = 0; x < 4; x++) {
@@ -718,11 +739,12 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
                     *(u32x2*)(dkg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, b4);
                 }
         } else {
-            bf16_t* dqg = (bf16_t*)p.dq + base + (size_t)ri * C;
+            bf16_t* dqg = (bf16_t*)p.dq + base + (size_t)ri * Cg;
 #pragma unroll
             for (int mb = 0; mb < K::MBC; mb++)
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
+                    if (mb * 32 + 8 * g >= Cg) continue;
                     bf16x4 o4;
 #pragma unroll
                     for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(acc1[mb][4 * g + x] * p.scale);
@@ -797,10 +819,33 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     a.aq = aq;
     a.ak = ak;
 
-    const long long vthreads = rows * (C / 8);
-    hipLaunchKernelGGL((bwd_vec_kernel<C>), dim3((unsigned)((vthreads + 255) / 256)), dim3(256), 0, stream,
-                       (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
-    if (hipGetLastError() != hipSuccess) return 1;
+    BwdParams p = pin;
+    bool narrow = false;
+    if constexpr (C == 32) {
+        if (pin.Cg == 16) {
+            // widened copies of v and dO behind the operand rows; out and dO keep their 16-channel rows
+            // for the row sums
+            narrow = true;
+            bf16_t* vpad = ak + (size_t)rowsk * K::W;
+            bf16_t* dpad = vpad + (size_t)rowsk * 32;
+            hipLaunchKernelGGL(bwd_pad16_kernel, dim3((unsigned)((rowsk * 4 + 255) / 256)), dim3(256), 0, stream,
+                               (const bf16_t*)pin.v, vpad, rowsk);
+            hipLaunchKernelGGL(bwd_pad16_kernel, dim3((unsigned)((rows * 4 + 255) / 256)), dim3(256), 0, stream,
+                               (const bf16_t*)pin.dout, dpad, rows);
+            hipLaunchKernelGGL((bwd_vec_kernel<16>), dim3((unsigned)((rows * 2 + 255) / 256)), dim3(256), 0, stream,
+                               (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
+            if (hipGetLastError() != hipSuccess) return 1;
+            p.v = vpad;
+            p.dout = dpad;
+        }
+    }
+    if (!narrow) {
+        if (pin.Cg != C) return -1;
+        const long long vthreads = rows * (C / 8);
+        hipLaunchKernelGGL((bwd_vec_kernel<C>), dim3((unsigned)((vthreads + 255) / 256)), dim3(256), 0, stream,
+                           (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
+        if (hipGetLastError() != hipSuccess) return 1;
+    }
     hipLaunchKernelGGL((bwd_prep_kernel<C, RP, true>), dim3((unsigned)((rows * (K::W / 8) + 255) / 256)),
                        dim3(256), 0, stream, pin, aq);
     if (hipGetLastError() != hipSuccess) return 1;
@@ -814,7 +859,6 @@ int launch(const BwdParams& pin, hipStream_t stream) {
         p.total_tiles = p.B * p.H * n_units;
         p.tiles_per_xcd = (p.total_tiles + 7) / 8;
     };
-    BwdParams p = pin;
     set_tiles(p, p.M);
     hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p, a);
     if (hipGetLastError() != hipSuccess) return 1;
@@ -888,8 +932,9 @@ int dispatch_rp(const BwdParams& p, int rp, hipStream_t stream) {
 }  // namespace
 
 size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R) {
-    // R alone does not say whether the factors are fp32 (6 R columns): size for the widest rows
-    const int w = C + (R > 0 ? 64 : 0);
+    // R alone does not say whether the factors are fp32 (6 R columns): size for the widest rows.
+    // Head dimension 16 runs on 32-channel operand rows and adds widened copies of v and dO.
+    const int w = (C == 16 ? 32 : C) + (R > 0 ? 64 : 0) + (C == 16 ? 32 : 0);
     return (((size_t)rows_q * 8 + 15) & ~(size_t)15) + (size_t)(rows_q + rows_k) * w * 2;
 }
 
@@ -904,6 +949,7 @@ int fb_launch_bwd_dense_bf16(const BwdParams& p, int C, hipStream_t stream) {
 
 int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream) {
     switch (C) {
+        case 16: return dispatch_rp<32>(p, rp, stream);      // p.Cg = 16
         case 32: return dispatch_rp<32>(p, rp, stream);
         case 64: return dispatch_rp<64>(p, rp, stream);
         case 128: return dispatch_rp<128>(p, rp, stream);

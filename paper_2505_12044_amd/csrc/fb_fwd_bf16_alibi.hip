@@ -4,6 +4,7 @@
 
 int fb_launch_fwd_bf16_alibi(const FwdParams& p, int C, int qb, hipStream_t stream) {
     switch (C) {
+        case 16: return dispatch_qb<32, 16, 4, false, 16>(p, qb, stream);
         case 32: return dispatch_qb<32, 16, 4, false>(p, qb, stream);
         case 64: return dispatch_qb<64, 16, 4, false>(p, qb, stream);
         case 128: return dispatch_qb<128, 16, 4, false>(p, qb, stream);

@@ -94,7 +94,9 @@ struct Cfg {
 // positions from q0 keeps the operands small near the diagonal, where the bias matters, so
 // the result does not degrade with N.  No factor memory is read.
 // One tile: the 128 * QB query rows [qt * BQ, (qt + 1) * BQ) of head bh against all keys they see.
-template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE>
+// CG: channels per head in global memory.  CG < C (head dimension 16 run on the C = 32 tiles)
+// zero-fills channels CG..C-1 of q, k and v on the way in and never stores them.
+template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE, int CG = C>
 FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, const int qt) {
     using K = Cfg<C, RP, QB>;
     bf16_t* const kt = (bf16_t*)smem;                 // [NBUF][BK][KP]
@@ -111,8 +113,8 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     const int q0 = qt * K::BQ;
     const int qw0 = q0 + wave * (QB * 32);
 
-    const size_t base = (size_t)bh * N * C;
-    const size_t kbase = (size_t)bh * M * C;
+    const size_t base = (size_t)bh * N * CG;
+    const size_t kbase = (size_t)bh * M * CG;
     const bf16_t* qg = (const bf16_t*)p.q + base;
     const bf16_t* kg = (const bf16_t*)p.k + kbase;
     const bf16_t* vg = (const bf16_t*)p.v + kbase;
@@ -136,9 +138,14 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         for (int ks = 0; ks < K::KS; ks++) {
             bf16x8 val;
             if (ks < C / 16) {
-                const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qi * C + ks * 16 + 8 * hf));
+                if (ks * 16 < CG) {
+                    const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qi * CG + ks * 16 + 8 * hf));
 #pragma unroll
-                for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
+                    for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
+                }
             } else {
                 const int c8 = (ks - C / 16) * 2 + hf;
                 if (PM == 4) val = phi_chunk_from_pair(c8, -slope * (float)(qi - q0), slope);
@@ -195,12 +202,17 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         __syncthreads();   // before any thread writes item columns into the same rows
     }
 
-    // byte offsets of this thread's chunks inside a block (row-major rows of C elements)
+    // byte offsets of this thread's chunks inside a block (row-major rows of CG elements);
+    // chunks of the channels past CG are never loaded and stay zero
     unsigned goff[K::KIT];
+    bool gok[K::KIT];
 #pragma unroll
     for (int it = 0; it < K::KIT; it++) {
         const int e = tid + it * kThreads;
-        goff[it] = (unsigned)(((e / (C / 8)) * C + (e % (C / 8)) * 8) * 2);
+        goff[it] = (unsigned)(((e / (C / 8)) * CG + (e % (C / 8)) * 8) * 2);
+        gok[it] = (K::KCH % kThreads == 0 || e < K::KCH) && (CG == C || (e % (C / 8)) * 8 < CG);
+        kraw[it] = u32x4{0u, 0u, 0u, 0u};
+        vraw[it] = u32x4{0u, 0u, 0u, 0u};
     }
     const unsigned char* kgb = (const unsigned char*)kg;
     const unsigned char* vgb = (const unsigned char*)vg;
@@ -208,10 +220,10 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     auto load_block = [&](int t) {
         const int k0 = blk_of(t) * BK;
         if (k0 + BK <= M) {   // whole block in range (wave-uniform): base + 32-bit offset
-            const unsigned boff = (unsigned)k0 * (unsigned)(C * 2);
+            const unsigned boff = (unsigned)k0 * (unsigned)(CG * 2);
 #pragma unroll
             for (int it = 0; it < K::KIT; it++) {
-                if (K::KCH % kThreads == 0 || tid + it * kThreads < K::KCH) {
+                if ((CG == C && K::KCH % kThreads == 0) || gok[it]) {
                     kraw[it] = *(const u32x4*)(kgb + (boff + goff[it]));
                     vraw[it] = *(const u32x4*)(vgb + (boff + goff[it]));
                 }
@@ -220,11 +232,11 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 #pragma unroll
             for (int it = 0; it < K::KIT; it++) {
                 const int e = tid + it * kThreads;
-                if (K::KCH % kThreads == 0 || e < K::KCH) {
+                if ((CG == C && K::KCH % kThreads == 0) || gok[it]) {
                     const int row = e / (C / 8), c8 = e % (C / 8);
                     const int j = min(k0 + row, M - 1);
-                    kraw[it] = *(const u32x4*)(kg + (size_t)j * C + c8 * 8);
-                    vraw[it] = *(const u32x4*)(vg + (size_t)j * C + c8 * 8);
+                    kraw[it] = *(const u32x4*)(kg + (size_t)j * CG + c8 * 8);
+                    vraw[it] = *(const u32x4*)(vg + (size_t)j * CG + c8 * 8);
                 }
             }
         }
@@ -532,11 +544,12 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         const float ltot = half_sum(lsum[qb]);
         const float inv = 1.f / ltot;
         if (qi < N) {
-            bf16_t* og = (bf16_t*)p.out + base + (size_t)qi * C;
+            bf16_t* og = (bf16_t*)p.out + base + (size_t)qi * CG;
 #pragma unroll
             for (int cb = 0; cb < C / 32; cb++) {
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
+                    if (cb * 32 + 8 * g >= CG) continue;
                     bf16x4 o4;
 #pragma unroll
                     for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(oacc[qb][cb][4 * g + x] * inv);
@@ -554,7 +567,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 // tiles per workgroup the heaviest tile alone lasts almost half of the whole launch at
 // N = 4096).  Units are numbered so that each XCD gets a contiguous run (workgroup w lands
 // on XCD w % 8): the workgroups sharing one head's K/V also share one L2.
-template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE>
+template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE, int CG = C>
 __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
@@ -574,20 +587,20 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     }
     if (CAUSAL) {
         const int heavy = p.n_qtiles - 1 - u;
-        fwd_tile<C, RP, QB, PM, CAUSAL, DENSE>(p, smem, bh, heavy);
+        fwd_tile<C, RP, QB, PM, CAUSAL, DENSE, CG>(p, smem, bh, heavy);
         if (u != heavy) {
             __syncthreads();   // the LDS ring is reused: every wave must have left the first tile
-            fwd_tile<C, RP, QB, PM, CAUSAL, DENSE>(p, smem, bh, u);
+            fwd_tile<C, RP, QB, PM, CAUSAL, DENSE, CG>(p, smem, bh, u);
         }
     } else {
-        fwd_tile<C, RP, QB, PM, CAUSAL, DENSE>(p, smem, bh, u);
+        fwd_tile<C, RP, QB, PM, CAUSAL, DENSE, CG>(p, smem, bh, u);
     }
 }
 
-template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE>
+template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE, int CG = C>
 int launch(const FwdParams& pin, hipStream_t stream) {
     using K = Cfg<C, RP, QB>;
-    auto kern = fwd_bf16_kernel<C, RP, QB, PM, CAUSAL, DENSE>;
+    auto kern = fwd_bf16_kernel<C, RP, QB, PM, CAUSAL, DENSE, CG>;
     static bool attr_done = false;   // benign race: the call is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -604,25 +617,39 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
-template <int C, int RP, int QB, int PM, bool DENSE>
+template <int C, int RP, int QB, int PM, bool DENSE, int CG = C>
 int dispatch_causal(const FwdParams& p, hipStream_t stream) {
-    if (p.causal) return launch<C, RP, QB, PM, true, DENSE>(p, stream);
-    return launch<C, RP, QB, PM, false, DENSE>(p, stream);
+    if (p.causal) return launch<C, RP, QB, PM, true, DENSE, CG>(p, stream);
+    return launch<C, RP, QB, PM, false, DENSE, CG>(p, stream);
 }
 
-template <int C, int RP, int PM, bool DENSE>
+template <int C, int RP, int PM, bool DENSE, int CG = C>
 int dispatch_qb(const FwdParams& p, int qb, hipStream_t stream) {
     if constexpr (C <= 64) {
-        if (qb == 2) return dispatch_causal<C, RP, 2, PM, DENSE>(p, stream);
+        if (qb == 2) return dispatch_causal<C, RP, 2, PM, DENSE, CG>(p, stream);
     }
-    return dispatch_causal<C, RP, 1, PM, DENSE>(p, stream);
+    return dispatch_causal<C, RP, 1, PM, DENSE, CG>(p, stream);
 }
 
-template <int C, int RP>
+template <int C, int RP, int CG = C>
 int dispatch_pm(const FwdParams& p, int qb, hipStream_t stream) {
-    if (p.phi_f32) return dispatch_qb<C, RP, 3, false>(p, qb, stream);
-    if ((p.R % 8) == 0) return dispatch_qb<C, RP, 1, false>(p, qb, stream);
-    return dispatch_qb<C, RP, 2, false>(p, qb, stream);
+    if (p.phi_f32) return dispatch_qb<C, RP, 3, false, CG>(p, qb, stream);
+    if ((p.R % 8) == 0) return dispatch_qb<C, RP, 1, false, CG>(p, qb, stream);
+    return dispatch_qb<C, RP, 2, false, CG>(p, qb, stream);
+}
+
+// Head dimension 16 on the C = 32 tiles of the four-wave kernel (qb = 1 or 2).
+inline int fwd_bf16_dispatch_c16(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream) {
+    if (qb != 2) qb = 1;
+    if (dense) return dispatch_qb<32, 0, 0, true, 16>(p, qb, stream);
+    switch (rp) {
+        case 0: return dispatch_qb<32, 0, 0, false, 16>(p, qb, stream);
+        case 16: return dispatch_pm<32, 16, 16>(p, qb, stream);
+        case 32: return dispatch_pm<32, 32, 16>(p, qb, stream);
+        case 48: return dispatch_pm<32, 48, 16>(p, qb, stream);
+        case 64: return dispatch_pm<32, 64, 16>(p, qb, stream);
+        default: return -1;
+    }
 }
 
 // rp: padded factor width (multiple of 16, <= 64); qb: 32-row query blocks per wave of the

@@ -139,6 +139,7 @@ int dispatch_c(const FwdParams& p, bool dense, hipStream_t stream) {
 int fb_launch_fwd_f32(const FwdParams& p, int C, bool dense, hipStream_t stream) {
     if (p.R > 64) return -1;
     switch (C) {
+        case 16: return dispatch_c<16>(p, dense, stream);
         case 32: return dispatch_c<32>(p, dense, stream);
         case 64: return dispatch_c<64>(p, dense, stream);
         case 128: return dispatch_c<128>(p, dense, stream);

@@ -40,6 +40,7 @@ struct BwdParams {
     void* workspace;      // device scratch: (lse2, D) rows and the concatenated operand rows
     int B, H, N, R;       // N = number of queries
     int M;                // number of keys (= N except for cross-attention)
+    int Cg;               // channels per head in caller memory (16 runs on the C = 32 kernels), else C
     int causal;
     int phi_f32;
     long long phi_bstride;   // elements between batch items of phi_q (0 when shared over batch)

@@ -25,7 +25,8 @@ from typing import Optional
 import numpy as np
 
 __all__ = ["Workload", "make_workload", "CONFIG_NAMES", "round_bf16", "f32_to_bf16_bits",
-           "bf16_bits_to_f32", "alibi_factors", "swin_table_bias", "pair_bias"]
+           "bf16_bits_to_f32", "alibi_factors", "swin_table_bias", "pair_bias", "distance_factors",
+           "make_pde_workload"]
 
 CONFIG_NAMES = ("tiny_fp32", "alibi_causal", "vision_relpos", "pairformer", "long_train")
 
@@ -78,6 +79,24 @@ def alibi_factors(num_heads: int, n: int):
     phi_k[0, :, :, 0] = 1.0
     phi_k[0, :, :, 1] = pos[None, :]
     return phi_q.astype(np.float32), phi_k.astype(np.float32)
+
+
+def distance_factors(x: np.ndarray, alpha: np.ndarray, strength: float):
+    """Exact rank-9 factors of the weighted squared-distance bias
+    b_ij = -strength * alpha_i * ||x_i - x_j||^2 for 3-D positions x [n,3] (Example 3.5 with
+    the token-wise weight of the PDE-solver experiment, Sec. 4.3): per axis a the three
+    columns [x_a^2, 1, -2 x_a] on the query side against [1, y_a^2, y_a] on the key side; the
+    weight multiplies the query side.  alpha: [H, n].  Returns float32 [1,H,n,9] each."""
+    x = np.asarray(x, dtype=np.float64)
+    n = x.shape[0]
+    uq = np.empty((n, 9)); uk = np.empty((n, 9))
+    for a in range(3):
+        uq[:, 3 * a] = x[:, a] ** 2; uq[:, 3 * a + 1] = 1.0; uq[:, 3 * a + 2] = -2.0 * x[:, a]
+        uk[:, 3 * a] = 1.0; uk[:, 3 * a + 1] = x[:, a] ** 2; uk[:, 3 * a + 2] = x[:, a]
+    w = -float(strength) * np.asarray(alpha, dtype=np.float64)          # [H, n]
+    phi_q = (w[:, :, None] * uq[None]).astype(np.float32)[None]
+    phi_k = np.broadcast_to(uk.astype(np.float32), (1, w.shape[0], n, 9)).copy()
+    return phi_q, phi_k
 
 
 def swin_table_bias(rng, num_heads: int, grid: int, sigma: float = 4.0) -> np.ndarray:
@@ -251,3 +270,21 @@ def make_workload(name: str, dense: bool = False, with_dout: Optional[bool] = No
     return Workload(name=name, B=B, H=H, N=N, C=C, R=R, causal=p["causal"], dtype=dtype,
                     phi_dtype=phi_dtype, q=q, k=k, v=v, phi_q=phi_q, phi_k=phi_k, dout=dout,
                     bias=bias, bias_exact=bias_exact, notes=notes)
+
+
+def make_pde_workload(B: int = 1, H: int = 8, N: int = 32186, C: int = 16, strength: float = 4.0,
+                      seed: int = 1006) -> Workload:
+    """The shape of the paper's PDE-solver attention (Sec. 4.3): N = 32186 mesh points, 8 heads
+    of 16 channels, bias -s alpha_i ||x_i - x_j||^2 as rank-9 fp32 factors shared over the
+    batch.  Points are uniform in the unit cube, alpha ~ U(0.5, 1.5) per head and point;
+    q, k, v, dout ~ N(0,1) rounded to bf16.  A stand-in for the mesh of the paper's dataset,
+    which is not reproduced."""
+    rng = np.random.default_rng(seed)
+    q, k, v = (_store(rng.standard_normal((B, H, N, C)), "bf16") for _ in range(3))
+    x = rng.random((N, 3))
+    alpha = 0.5 + rng.random((H, N))
+    phi_q, phi_k = distance_factors(x, alpha, strength)
+    dout = _store(rng.standard_normal((B, H, N, C)), "bf16")
+    return Workload(name="pde_distance", B=B, H=H, N=N, C=C, R=9, causal=False, dtype="bf16",
+                    phi_dtype="f32", q=q, k=k, v=v, phi_q=phi_q, phi_k=phi_k, dout=dout,
+                    notes={"x": x, "alpha": alpha, "strength": strength})

@@ -27,7 +27,7 @@ def _run(q, k, v, slopes, causal):
     return out, lse
 
 
-@pytest.mark.parametrize("C", [32, 64, 128])
+@pytest.mark.parametrize("C", [16, 32, 64, 128])
 @pytest.mark.parametrize("N,causal", [(1, True), (100, True), (333, True), (512, True), (333, False), (512, False)])
 def test_alibi_small(N, C, causal):
     B, H = 2, 3

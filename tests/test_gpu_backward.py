@@ -66,6 +66,10 @@ CASES = [
     ("long_train", dict(B=1, H=1, N=260, R=64)),                  # widest bf16 factors, C = 128
     ("long_train", dict(B=1, H=2, N=200, C=32, R=40, causal=True)),
     ("long_train", dict(B=1, H=2, N=256, C=64, R=48)),
+    ("long_train", dict(B=2, H=2, N=300, C=16, R=8)),             # head dimension 16 (32-byte rows)
+    ("long_train", dict(B=1, H=2, N=333, C=16, R=9, phi_dtype="f32", causal=True)),
+    ("long_train", dict(B=1, H=3, N=129, C=16, R=0)),
+    ("long_train", dict(B=1, H=2, N=256, C=16, R=64)),
 ]
 
 

@@ -34,7 +34,7 @@ def _problem(N, C, H, seed):
     return q, k, v, dout, phi_q, phi_k, uq, dist2, bias
 
 
-@pytest.mark.parametrize("N,C", [(1500, 32), (777, 64), (520, 128)])
+@pytest.mark.parametrize("N,C", [(1500, 32), (777, 64), (520, 128), (2100, 16)])
 def test_distance_bias_forward_and_alpha_gradient(N, C):
     H = 2
     q, k, v, dout, phi_q, phi_k, uq, dist2, bias = _problem(N, C, H, seed=5000 + N)

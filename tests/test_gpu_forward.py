@@ -48,7 +48,7 @@ def test_config1_tiny_fp32_full():
     _check_dense(w)
 
 
-@pytest.mark.parametrize("N,C,R,causal", [(200, 32, 3, True), (77, 128, 9, False), (129, 64, 0, True)])
+@pytest.mark.parametrize("N,C,R,causal", [(200, 32, 3, True), (77, 128, 9, False), (129, 64, 0, True), (150, 16, 4, False)])
 def test_fp32_ragged(N, C, R, causal):
     w = W.make_workload("tiny_fp32", dense=True, B=2, H=2, N=N, C=C, R=R, causal=causal)
     _check_lowrank(w)
@@ -77,6 +77,18 @@ def test_bf16_dense_small(name, ov, qb):
     _check_dense(W.make_workload(name, dense=True, **ov), qb=qb)
 
 
+@pytest.mark.parametrize("N", [1, 100, 256, 700])
+@pytest.mark.parametrize("causal", [False, True])
+def test_bf16_head_dim_16(N, causal):
+    """C = 16 (the PDE-solver head dimension): 32-byte rows in memory, run on the 32-channel tiles."""
+    w = W.make_workload("long_train", dense=True, B=2, H=2, N=N, C=16, R=8, causal=causal)
+    for qb in (1, 2):
+        _check_lowrank(w, qb=qb)
+        _check_dense(w, qb=qb)
+    _check_lowrank(W.make_workload("long_train", B=1, H=2, N=N, C=16, R=0, causal=causal))
+    _check_lowrank(W.make_workload("long_train", B=1, H=2, N=N, C=16, R=5, causal=causal))
+
+
 @pytest.mark.parametrize("N", [1, 31, 64, 65])
 @pytest.mark.parametrize("causal", [False, True])
 def test_bf16_edge_lengths(N, causal):
@@ -87,7 +99,8 @@ def test_bf16_edge_lengths(N, causal):
 
 
 @pytest.mark.parametrize("C,R,phi_dtype", [(32, 64, "bf16"), (64, 0, "bf16"), (128, 48, "bf16"),
-                                           (64, 10, "f32"), (128, 1, "f32")])
+                                           (64, 10, "f32"), (128, 1, "f32"), (16, 64, "bf16"),
+                                           (16, 9, "f32")])
 def test_bf16_rank_range(C, R, phi_dtype):
     w = W.make_workload("long_train", B=1, H=2, N=320, C=C, R=R, phi_dtype=phi_dtype)
     _check_lowrank(w, qb=1)

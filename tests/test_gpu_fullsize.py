@@ -100,3 +100,40 @@ def test_long_train_full_forward_and_gradients():
             msg.append(f"{name} {err:.3e} (max|ref| {np.abs(r[lo:hi]).max():.3f})")
             assert err <= GRAD_TOL, (name, err)
         print(f"long_train gradients, slice [{lo},{hi}) of (b,h)=({b},{h}): " + ", ".join(msg), flush=True)
+
+
+def test_pde_distance_full_forward_and_gradients():
+    """The PDE-solver shape (Sec. 4.3): N = 32186 (no multiple of any tile), C = 16, rank-9 fp32
+    distance factors.  Forward rows against the oracle on bias rows materialised from the
+    definition -s alpha_i ||x_i - x_j||^2; gradients of one head on an unaligned token slice
+    against the oracle's chain rule (bound scaled with the data as for the small cases)."""
+    w = W.make_pde_workload()
+    x, alpha, s = w.notes["x"], w.notes["alpha"], w.notes["strength"]
+    d = workload_to_device(w)
+    out, lse = api.fb_lowrank_attn_fwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"])
+    grads = api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out, lse, d["dout"])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    eo = el = 0.0
+    for h in (0, 5, 7):
+        rows = _sample_rows(w.N, rng)
+        go, gl = host(out[0, h, rows]), host(lse[0, h, rows])
+        assert np.isfinite(go).all() and np.isfinite(gl).all()
+        for n, r in enumerate(rows):
+            brow = -s * alpha[h, r] * O.squared_distance_bias(x[r:r + 1], x)
+            o1, l1 = O.attention_with_bias(w.q[0, h, r:r + 1], w.k[0, h], w.v[0, h], brow, row_offset=r)
+            eo = max(eo, max_abs(go[n], o1[0]))
+            el = max(el, max_abs(gl[n], l1[0]))
+    print(f"full-size pde_distance: out err {eo:.3e}, lse err {el:.3e}", flush=True)
+    assert eo <= TOL["bf16"] and el <= TOL["bf16"]
+    h, lo, hi = 3, 15001, 16025
+    ref = O.attention_lowrank_grads(w.q[0, h], w.k[0, h], w.v[0, h], w.phi_q[0, h], w.phi_k[0, h],
+                                    w.dout[0, h], row_block=512)
+    msg = []
+    for name, g, r in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), grads, ref):
+        gh = host(g[0, h, lo:hi])
+        assert np.isfinite(gh).all(), name
+        err = max_abs(gh, r[lo:hi]) / max(1.0, float(np.abs(r[lo:hi]).max()) / 2.5)
+        msg.append(f"{name} {err:.3e} (max|ref| {np.abs(r[lo:hi]).max():.3f})")
+        assert err <= GRAD_TOL, (name, err)
+    print(f"pde_distance gradients, slice [{lo},{hi}) of head {h}: " + ", ".join(msg), flush=True)

@@ -28,7 +28,8 @@ def _problem(B, H, N, M, C, R, phi_dtype, seed):
 
 
 CASES = [(2, 2, 300, 1000, 128, 8, "bf16"), (1, 3, 1000, 300, 64, 16, "bf16"), (2, 2, 129, 33, 32, 3, "f32"),
-         (1, 2, 64, 4096, 128, 0, "bf16"), (1, 1, 1, 77, 64, 5, "bf16"), (1, 2, 500, 1, 128, 8, "bf16")]
+         (1, 2, 64, 4096, 128, 0, "bf16"), (1, 1, 1, 77, 64, 5, "bf16"), (1, 2, 500, 1, 128, 8, "bf16"),
+         (2, 2, 300, 1001, 16, 8, "bf16"), (1, 2, 131, 333, 16, 9, "f32")]
 
 
 @pytest.mark.parametrize("B,H,N,M,C,R,phi_dtype", CASES)

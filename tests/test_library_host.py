@@ -85,6 +85,8 @@ def test_dense_and_backward_argument_errors(lib):
     # (lse, D) pairs plus the two concatenated operand copies of width up to C + 64
     assert ws == 2 * 3 * 100 * 8 + 2 * (2 * 3 * 100) * (64 + 64) * 2
     assert lib.fb_lowrank_attn_bwd_workspace_bytes(0, 3, 100, 64, 8, api.FB_BF16) == 0
+    # head dimension 16: 32-channel operand rows plus widened copies of v and dO
+    assert lib.fb_lowrank_attn_bwd_workspace_bytes(1, 1, 10, 16, 9, api.FB_F32) == 10 * 8 + 2 * 10 * (32 + 64 + 32) * 2
     g = lib.fb_lowrank_attn_bwd
     ptrs = [64] * 13
 

@@ -348,6 +348,18 @@ def test_workload_recipes():
     np.testing.assert_array_equal(w1.q, w1b.q)
 
 
+def test_pde_workload_factors_equal_dense_definition():
+    """The generator's rank-9 factors against the oracle's dense definition of the weighted
+    squared-distance bias (Example 3.5 with the token-wise weight of Sec. 4.3)."""
+    w = W.make_pde_workload(N=300, H=2)
+    assert w.q.shape == (1, 2, 300, 16) and w.phi_q.shape == (1, 2, 300, 9) and w.phi_q.dtype == np.float32
+    x, alpha, s = w.notes["x"], w.notes["alpha"], w.notes["strength"]
+    for h in range(2):
+        ref = -s * alpha[h][:, None] * O.squared_distance_bias(x, x)
+        got = O.lowrank_bias(w.phi_q[0, h], w.phi_k[0, h])
+        assert np.max(np.abs(got - ref)) < 5e-6      # fp32 storage of factors of magnitude <= 12
+
+
 def test_bf16_rounding_helper():
     x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -9, -3.14159, 4095.0, 1e-30], dtype=np.float32)
     r = W.round_bf16(x)
