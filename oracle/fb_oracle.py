@@ -31,6 +31,11 @@ against torch's float64 scaled_dot_product_attention, Eckart-Young for truncated
 (Remark 3.8's "energy"), and central finite differences plus invariants for gradients.
 The paper prints no worked numeric example of attention outputs, so output values are
 pinned only through those identities, closed forms and the library cross-check.
+
+The multiplicative-bias extension (App. I) is covered by its definition
+o = softmax((q k^T / sqrt(C)) o b) v with b materialised, pinned by brute force on tiny
+inputs, by b = 1 reducing to plain attention, by the cos(i - j) rank-2 example and by the
+repeated-and-reweighted-channel identity of that appendix.
 """
 from __future__ import annotations
 
@@ -40,6 +45,9 @@ __all__ = [
     "lowrank_bias",
     "attention_with_bias",
     "attention_lowrank",
+    "attention_with_multiplicative_bias",
+    "multiplicative_concat",
+    "cosine_multiplicative_factors",
     "attention_with_bias_grads",
     "attention_lowrank_grads",
     "batched_attention_lowrank",
@@ -124,6 +132,40 @@ def attention_lowrank(q, k, v, phi_q, phi_k, causal=False, scale=None, row_offse
     """Same as attention_with_bias with b = phi_q phi_k^T materialised first (Eq. 2)."""
     b = lowrank_bias(phi_q, phi_k)
     return attention_with_bias(q, k, v, b, causal=causal, scale=scale, row_offset=row_offset)
+
+
+# ----------------------------------------------------------------------------------
+# Multiplicative bias (App. I)
+# ----------------------------------------------------------------------------------
+def attention_with_multiplicative_bias(q, k, v, b, causal=False, scale=None, row_offset=0):
+    """o = softmax((scale q k^T) o b [+ causal mask]) v for one head, o = Hadamard product
+    (App. I, the definition the extension starts from).  b: N x M dense.  scale defaults to
+    1/sqrt(C) with C the channel count of q itself.  Returns (o, lse)."""
+    q, k, v, b = _f64(q), _f64(k), _f64(v), _f64(b)
+    if scale is None:
+        scale = 1.0 / np.sqrt(q.shape[1])
+    s = (scale * (q @ k.T)) * b
+    if causal:
+        i = np.arange(q.shape[0])[:, None] + row_offset
+        j = np.arange(k.shape[0])[None, :]
+        s = np.where(j > i, -np.inf, s)
+    p, lse = _softmax_rows(s)
+    return p @ v, lse
+
+
+def multiplicative_concat(x, phi):
+    """App. I's reweighted repeat: [x o phi_1, ..., x o phi_R] along the channel axis, each
+    factor column broadcast over the C channels of x.  x: N x C, phi: N x R -> N x (C R)."""
+    x, phi = _f64(x), _f64(phi)
+    return np.concatenate([x * phi[:, r:r + 1] for r in range(phi.shape[1])], axis=1)
+
+
+def cosine_multiplicative_factors(n, m=None):
+    """App. I's example: b_ij = cos(i - j) = cos i cos j + sin i sin j, rank 2 (0-based positions)."""
+    m = n if m is None else m
+    i = np.arange(n, dtype=np.float64)
+    j = np.arange(m, dtype=np.float64)
+    return np.stack([np.cos(i), np.sin(i)], axis=1), np.stack([np.cos(j), np.sin(j)], axis=1)
 
 
 # ----------------------------------------------------------------------------------

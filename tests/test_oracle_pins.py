@@ -348,6 +348,38 @@ def test_workload_recipes():
     np.testing.assert_array_equal(w1.q, w1b.q)
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_multiplicative_bias_brute_force_and_identities(causal):
+    """App. I: definition by explicit loops, the cos(i - j) rank-2 example, the reweighted-repeat
+    identity softmax(q' k'^T / sqrt(C)) v with the ORIGINAL C in the scale, and b = 1."""
+    rng = np.random.default_rng(77)
+    n, m, c = 7, 7, 4
+    q, k, v = _rand(rng, n, c), _rand(rng, m, c), _rand(rng, m, c)
+    pq, pk = O.cosine_multiplicative_factors(n, m)
+    b = np.array([[math.cos(i - j) for j in range(m)] for i in range(n)])
+    np.testing.assert_allclose(O.lowrank_bias(pq, pk), b, atol=1e-13)
+    o, lse = O.attention_with_multiplicative_bias(q, k, v, b, causal=causal)
+    for i in range(n):
+        js = [j for j in range(m) if not (causal and j > i)]
+        sc = [sum(q[i, x] * k[j, x] for x in range(c)) / math.sqrt(c) * b[i, j] for j in js]
+        z = sum(math.exp(t) for t in sc)
+        assert abs(lse[i] - math.log(z)) < 1e-12
+        for x in range(c):
+            assert abs(o[i, x] - sum(math.exp(t) / z * v[j, x] for t, j in zip(sc, js))) < 1e-12
+    # reweighted repeat of q and k: plain attention on C R channels with scale 1/sqrt(C)
+    q2, k2 = O.multiplicative_concat(q, pq), O.multiplicative_concat(k, pk)
+    assert q2.shape == (n, 2 * c)
+    np.testing.assert_allclose(q2[:, c:], q * pq[:, 1:2], atol=0)
+    o2, lse2 = O.attention_with_bias(q2, k2, v, None, causal=causal, scale=1.0 / math.sqrt(c))
+    np.testing.assert_allclose(o2, o, atol=1e-12)
+    np.testing.assert_allclose(lse2, lse, atol=1e-12)
+    # b = 1 is plain attention; a multiplicative bias is not an additive one
+    o1, l1 = O.attention_with_multiplicative_bias(q, k, v, np.ones((n, m)), causal=causal)
+    o0, l0 = O.attention_with_bias(q, k, v, None, causal=causal)
+    np.testing.assert_allclose(o1, o0, atol=1e-13)
+    assert np.max(np.abs(o - O.attention_with_bias(q, k, v, b, causal=causal)[0])) > 1e-3
+
+
 def test_pde_workload_factors_equal_dense_definition():
     """The generator's rank-9 factors against the oracle's dense definition of the weighted
     squared-distance bias (Example 3.5 with the token-wise weight of Sec. 4.3)."""
