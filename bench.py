@@ -317,7 +317,35 @@ def main() -> int:
             "fwd_ms": round(ms_f, 4), "fwd_TFLOPs": round(wp.fwd_flops() / (ms_f * 1e-3) / 1e12, 2),
             "bwd_ms": round(ms_b, 4), "bwd_TFLOPs": round(wp.bwd_flops() / (ms_b * 1e-3) / 1e12, 2),
             "dense_bias_bytes_avoided": int(wp.H * wp.N * wp.N * 2)}
-        del ws
+        del ws, d
+        torch.cuda.empty_cache()
+
+        # multiplicative bias cos(i - j) as rank-2 factors (App. I): pre-pass + forward on 2C channels
+        Bm, Hm, Nm, Cm = 4, 16, 4096, 64
+        g = torch.Generator(device="cuda").manual_seed(1007)
+        qm, km, vm = (torch.randn((Bm, Hm, Nm, Cm), device="cuda", generator=g).to(torch.bfloat16) for _ in range(3))
+        pos = torch.arange(Nm, device="cuda", dtype=torch.float64)
+        fm = torch.stack([torch.cos(pos), torch.sin(pos)], dim=1).to(torch.float32)
+        fm = fm.expand(1, Hm, Nm, 2).contiguous()
+        om = torch.empty_like(qm)
+        lm = torch.empty((Bm, Hm, Nm), dtype=torch.float32, device="cuda")
+        wsm = torch.empty(api.fb_lowrank_mulbias_attn_fwd_workspace_bytes(Bm, Hm, Nm, Cm, 2), dtype=torch.uint8,
+                          device="cuda")
+
+        def fm_():
+            api.fb_lowrank_mulbias_attn_fwd(qm, km, vm, fm, fm, out=om, lse=lm, workspace=wsm, stream=stream)
+
+        def plain():
+            api.fb_lowrank_attn_fwd(qm, km, vm, None, None, out=om, lse=lm, stream=stream)
+        _, ms_m = time_calls(fm_, 10, 2)
+        _, ms_p = time_calls(plain, 10, 2)
+        pairs_m = Bm * Hm * Nm * Nm
+        others["multiplicative_cos"] = {
+            "B": Bm, "H": Hm, "N": Nm, "C": Cm, "R": 2, "fwd_ms_incl_prepass": round(ms_m, 4),
+            "fwd_TFLOPs": round(2.0 * (Cm * 2 + Cm) * pairs_m / (ms_m * 1e-3) / 1e12, 2),
+            "plain_attention_ms": round(ms_p, 4), "cost_vs_plain": round(ms_m / ms_p, 3),
+            "dense_bias_bytes_avoided": int(Hm * Nm * Nm * 2)}
+        del qm, km, vm, om, lm, wsm
         result["other_workloads"] = others
 
     # ------------------------------------------------------------------ CPU oracle

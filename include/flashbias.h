@@ -127,6 +127,29 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
                            float scale, void* stream);
 
 /*
+ * Forward with a MULTIPLICATIVE low-rank bias (App. I):
+ *   out = softmax((q k^T * scale) o (phi_q phi_k^T)) v,   o = element-wise product,
+ * evaluated as plain attention over the reweighted repeats q' = [q o phi_q,1 | ... | q o phi_q,R],
+ * k' = [k o phi_k,1 | ... | k o phi_k,R] (C R channels, scale of the original C), so the N x N
+ * bias is never formed.  A pre-pass writes q' * scale and k' (bf16) into the workspace; the
+ * additive-bias forward kernels then run with the first C channels as q / k and the other
+ * C (R - 1) as extra columns of the same contraction.
+ *   phi_q, phi_k [Bp,H,N,R], R >= 1, 4-byte aligned; needs dtype = FB_BF16 and C (R - 1) <= 64
+ *   (C = 64: R <= 2; C = 32: R <= 3; C = 16: R <= 5; C = 128: R = 1).
+ *   workspace: device scratch of at least fb_lowrank_mulbias_attn_fwd_workspace_bytes(...)
+ *   = 4 B H N C R bytes, 16-byte aligned, owned by the caller, contents ignored on entry,
+ *   reusable once the call's work on `stream` has finished.
+ * lse is the log-sum-exp of the scaled, bias-multiplied, masked score row.
+ */
+size_t fb_lowrank_mulbias_attn_fwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype);
+
+int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
+                                const void* phi_q, const void* phi_k, void* out, float* lse,
+                                int B, int H, int N, int C, int R, int causal,
+                                fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                                float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Backward of fb_lowrank_attn_fwd for an upstream gradient dout (loss L = sum(dout * out)):
  * dq, dk, dv [B,H,N,C] dtype; dphi_q, dphi_k [B,H,N,R] phi_dtype, always per batch element
  * (a caller whose factors are shared over the batch sums them over B).  The factor

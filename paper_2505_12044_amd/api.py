@@ -24,6 +24,7 @@ EXPORTS = (
     "fb_alibi_attn_fwd", "fb_dense_bias_attn_fwd", "fb_lowrank_attn_bwd_workspace_bytes",
     "fb_lowrank_attn_bwd", "fb_lowrank_xattn_bwd_workspace_bytes", "fb_lowrank_xattn_bwd",
     "fb_dense_bias_attn_bwd_workspace_bytes", "fb_dense_bias_attn_bwd",
+    "fb_lowrank_mulbias_attn_fwd_workspace_bytes", "fb_lowrank_mulbias_attn_fwd",
 )
 
 
@@ -69,6 +70,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_lowrank_xattn_bwd_workspace_bytes.argtypes = [ci] * 6 + [ci]
     lib.fb_lowrank_xattn_bwd.restype = ci
     lib.fb_lowrank_xattn_bwd.argtypes = [vp] * 13 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
+    lib.fb_lowrank_mulbias_attn_fwd_workspace_bytes.restype = sz
+    lib.fb_lowrank_mulbias_attn_fwd_workspace_bytes.argtypes = [ci] * 5 + [ci]
+    lib.fb_lowrank_mulbias_attn_fwd.restype = ci
+    lib.fb_lowrank_mulbias_attn_fwd.argtypes = [vp] * 7 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
     if path is None:
         _lib_handle = lib
     return lib
@@ -152,6 +157,35 @@ def fb_lowrank_xattn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, scale: float
                                   _ptr(lse), B, H, N, M, C, R, _dtype_code(q), phi_code,
                                   int(bool(phi_batch_broadcast)), float(scale), _stream(stream))
     _check(st, "fb_lowrank_xattn_fwd")
+    return out, lse
+
+
+def fb_lowrank_mulbias_attn_fwd_workspace_bytes(B, H, N, C, R, dtype_code=FB_BF16) -> int:
+    return int(load_library().fb_lowrank_mulbias_attn_fwd_workspace_bytes(B, H, N, C, R, dtype_code))
+
+
+def fb_lowrank_mulbias_attn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, causal=False,
+                                scale: float = 0.0, phi_batch_broadcast: Optional[bool] = None,
+                                workspace=None, stream=None):
+    """out, lse = softmax((q k^T scale) * (phi_q phi_k^T)) v, the multiplicative-bias form.
+    q, k, v: [B,H,N,C] bf16; phi_q, phi_k: [B or 1,H,N,R], R >= 1, C (R - 1) <= 64."""
+    lib = load_library()
+    B, H, N, C = q.shape
+    R = phi_q.shape[-1]
+    if phi_batch_broadcast is None:
+        phi_batch_broadcast = phi_q.shape[0] == 1 and B > 1
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    need = fb_lowrank_mulbias_attn_fwd_workspace_bytes(B, H, N, C, R)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    st = lib.fb_lowrank_mulbias_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(phi_q), _ptr(phi_k), _ptr(out),
+                                         _ptr(lse), B, H, N, C, R, int(bool(causal)), _dtype_code(q),
+                                         _dtype_code(phi_q), int(bool(phi_batch_broadcast)), float(scale),
+                                         _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "fb_lowrank_mulbias_attn_fwd")
     return out, lse
 
 

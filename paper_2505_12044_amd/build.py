@@ -12,7 +12,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflashbias.so")
 
 SOURCES = ["fb_api.hip", "fb_fwd_f32.hip", "fb_fwd_bf16.hip", "fb_fwd_bf16_c16.hip", "fb_fwd_bf16_c32.hip",
-           "fb_fwd_bf16_c64.hip", "fb_fwd_bf16_c128.hip", "fb_fwd_bf16_alibi.hip", "fb_bwd_bf16.hip"]
+           "fb_fwd_bf16_c64.hip", "fb_fwd_bf16_c128.hip", "fb_fwd_bf16_alibi.hip", "fb_bwd_bf16.hip",
+           "fb_mulbias.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffast-math", "-fno-finite-math-only",

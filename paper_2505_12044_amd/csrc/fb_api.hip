@@ -189,6 +189,60 @@ int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* 
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
+size_t fb_lowrank_mulbias_attn_fwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype) {
+    (void)dtype;
+    if (B <= 0 || H <= 0 || N <= 0 || C <= 0 || R <= 0) return 0;
+    return (size_t)2 * B * H * N * C * R * 2;     // q' and k' rows of C R bf16 channels
+}
+
+int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
+                                const void* phi_q, const void* phi_k, void* out, float* lse,
+                                int B, int H, int N, int C, int R, int causal,
+                                fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                                float scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !phi_q || !phi_k || !out || !lse) return FB_ERR_NULL;
+    if (R <= 0) return FB_ERR_SHAPE;
+    if (int st = check_common(B, H, N, C, R)) return st;
+    if ((long long)B * H * N * (long long)C * R >= (1LL << 31)) return FB_ERR_SHAPE;
+    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    const int rest = C * (R - 1);                  // channels beyond the first repeat
+    if (rest > 64) return FB_ERR_UNSUPPORTED;
+    const void* ptrs[] = {q, k, v, out, lse};
+    for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(phi_q) & 3u) != 0 || (reinterpret_cast<uintptr_t>(phi_k) & 3u) != 0)
+        return FB_ERR_ALIGN;
+    if (!workspace || workspace_bytes < fb_lowrank_mulbias_attn_fwd_workspace_bytes(B, H, N, C, R, dtype))
+        return FB_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FB_ERR_ALIGN;
+
+    const size_t rows = (size_t)B * H * N;
+    unsigned char* ws = (unsigned char*)workspace;
+    void* qh = ws;                                  // [rows][C]
+    void* kh = ws + rows * C * 2;                   // [rows][C]
+    void* qr = ws + rows * C * 4;                   // [rows][C (R-1)]
+    void* kr = ws + rows * C * 4 + rows * rest * 2;
+    const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    const long long pbs = phi_batch_broadcast ? 0 : (long long)H * N * R;
+    const int f32 = phi_dtype == FB_F32;
+    if (fb_launch_mulbias_prep(q, phi_q, qh, qr, B, (long long)H * N, C, R, f32, pbs, sc, (hipStream_t)stream) ||
+        fb_launch_mulbias_prep(k, phi_k, kh, kr, B, (long long)H * N, C, R, f32, pbs, 1.0f, (hipStream_t)stream))
+        return FB_ERR_LAUNCH;
+
+    FwdParams p{};
+    p.q = qh; p.k = kh; p.v = v; p.phi_q = rest ? qr : nullptr; p.phi_k = rest ? kr : nullptr; p.bias = nullptr;
+    p.out = out; p.lse = lse;
+    p.B = B; p.H = H; p.N = N; p.M = N; p.R = rest; p.causal = causal != 0;
+    p.phi_f32 = 0;
+    p.phi_bstride = (long long)H * N * rest;
+    p.phik_bstride = (long long)H * N * rest;
+    p.bias_bstride = 0;
+    p.scale = 1.0f;                                 // already folded into q'
+    const int rc = fb_launch_fwd_bf16(p, C, rest, false, pick_qb(B, H, N, C, rest, false, causal != 0),
+                                      (hipStream_t)stream);
+    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
 static size_t bwd_ws_impl(int B, int H, int N, int M, int C, int R) {
     if (B <= 0 || H <= 0 || N <= 0 || M <= 0) return 0;
     // (lse * log2 e, D) per query row and the concatenated operand rows [q*scale | phi_q], [k | phi_k]

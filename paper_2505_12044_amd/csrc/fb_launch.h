@@ -18,6 +18,12 @@ size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R);
 // Dense-bias backward (p.bias, p.dbias, p.bias_bstride set; p.R = 0; workspace as above with R = 0).
 int fb_launch_bwd_dense_bf16(const BwdParams& p, int C, hipStream_t stream);
 
+// Multiplicative bias pre-pass: head[row][C] = x * phi[:, 0] * mul, rest[row][C (R-1)] = the other
+// repeats, bf16, for the B * rows_per_batch rows of x (rows_per_batch = H * sequence length);
+// phi is [Bp, rows_per_batch, R] with phi_bstride elements between batch items (0 when shared).
+int fb_launch_mulbias_prep(const void* x, const void* phi, void* head, void* rest, int B, long long rows_per_batch,
+                           int C, int R, int phi_f32, long long phi_bstride, float mul, hipStream_t stream);
+
 // Extra dynamic LDS bytes added to forward launches (experiments on occupancy; normally 0).
 size_t fb_debug_lds_pad();
 

@@ -1,0 +1,47 @@
+// Multiplicative low-rank bias (FlashBias App. I): softmax((q k^T / sqrt(C)) o (phi_q phi_k^T)) v
+// equals plain attention on the reweighted repeats
+//   q' = [q o phi_q,1 | ... | q o phi_q,R],  k' = [k o phi_k,1 | ... | k o phi_k,R]   (C R channels)
+// with the scale of the ORIGINAL C.  This file holds the pre-pass that writes q' (with the
+// scale folded in) and k' as bf16 rows, split into the first C channels and the remaining
+// C (R - 1): the forward kernels then take the first part as their q / k operand and the rest
+// as "factor" columns of the same contraction, so no kernel of its own is needed.
+#include <hip/hip_runtime.h>
+
+#include "fb_device.h"
+#include "fb_launch.h"
+
+namespace {
+
+// One thread per 16-byte piece (8 channels) of one repeat r of one row.
+__global__ __launch_bounds__(256) void mulbias_prep_kernel(const bf16_t* __restrict__ x, const void* __restrict__ phi,
+                                                           bf16_t* __restrict__ head, bf16_t* __restrict__ rest,
+                                                           long long rows, long long rows_per_batch, int C, int R,
+                                                           int phi_f32, long long phi_bstride, float mul) {
+    const int cpr = C / 8;                                   // pieces per repeat
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long row = gid / (cpr * R);
+    if (row >= rows) return;
+    const int rem = (int)(gid - row * (cpr * R));
+    const int r = rem / cpr, c8 = rem - r * cpr;
+    const long long bb = row / rows_per_batch;
+    const long long poff = bb * phi_bstride + (row - bb * rows_per_batch) * R + r;
+    const float f = (phi_f32 ? ((const float*)phi)[poff] : (float)((const bf16_t*)phi)[poff]) * mul;
+    const bf16x8 a = as_bf16x8(*(const u32x4*)(x + row * C + c8 * 8));
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; e++) o[e] = (bf16_t)((float)a[e] * f);
+    bf16_t* dst = r == 0 ? head + row * C + c8 * 8 : rest + row * (long long)(C * (R - 1)) + (r - 1) * C + c8 * 8;
+    *(u32x4*)dst = as_uint4(o);
+}
+
+}  // namespace
+
+int fb_launch_mulbias_prep(const void* x, const void* phi, void* head, void* rest, int B, long long rows_per_batch,
+                           int C, int R, int phi_f32, long long phi_bstride, float mul, hipStream_t stream) {
+    const long long rows = (long long)B * rows_per_batch;
+    const long long threads = rows * (C / 8) * R;
+    hipLaunchKernelGGL(mulbias_prep_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+                       (const bf16_t*)x, phi, (bf16_t*)head, (bf16_t*)rest, rows, rows_per_batch, C, R, phi_f32,
+                       phi_bstride, mul);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}

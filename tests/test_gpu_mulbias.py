@@ -1,0 +1,99 @@
+"""GPU parity of fb_lowrank_mulbias_attn_fwd (multiplicative low-rank bias, App. I) against the
+float64 oracle's definition softmax((q k^T / sqrt(C)) o b) v with b = phi_q phi_k^T
+materialised.  Tolerance 2e-2 on out and lse as for every bf16 forward.  The GPU rounds the
+reweighted repeats q o phi_r to bf16 once (one more 2^-9 relative rounding than the additive
+path), so the factors are kept O(1) as in the appendix's cos(i - j) example."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fb_oracle as O
+from paper_2505_12044_amd import api, workloads as W
+from tests._gpu_util import TOL, dev, host, max_abs
+
+pytestmark = pytest.mark.gpu
+
+
+def _qkv(B, H, N, C, seed):
+    rng = np.random.default_rng(seed)
+    return tuple(W.round_bf16(rng.standard_normal((B, H, N, C)).astype(np.float32)) for _ in range(3)) + (rng,)
+
+
+def _check(q, k, v, pq, pk, phi_dtype, causal, tag):
+    B, H, N, C = q.shape
+    out, lse = api.fb_lowrank_mulbias_attn_fwd(dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"),
+                                               dev(pq, phi_dtype), dev(pk, phi_dtype), causal=causal)
+    torch.cuda.synchronize()
+    go, gl = host(out), host(lse)
+    assert np.isfinite(go).all() and np.isfinite(gl).all()
+    eo = el = 0.0
+    for b in range(B):
+        for h in range(H):
+            bp = 0 if pq.shape[0] == 1 else b
+            bias = O.lowrank_bias(pq[bp, h], pk[bp, h])
+            ro, rl = O.attention_with_multiplicative_bias(q[b, h], k[b, h], v[b, h], bias, causal=causal)
+            eo = max(eo, max_abs(go[b, h], ro))
+            el = max(el, max_abs(gl[b, h], rl))
+    print(f"mulbias {tag} B{B} H{H} N{N} C{C} R{pq.shape[-1]} {phi_dtype} causal={causal}: "
+          f"out err {eo:.3e}, lse err {el:.3e}", flush=True)
+    assert eo <= TOL["bf16"] and el <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,C", [(1, 64), (200, 64), (777, 64), (333, 32), (515, 16)])
+def test_cosine_bias(N, C, causal):
+    """b_ij = cos(i - j), the appendix's rank-2 example, as fp32 factors shared over batch and heads."""
+    B, H = 2, 2
+    q, k, v, _ = _qkv(B, H, N, C, seed=8000 + N + C)
+    fq, fk = O.cosine_multiplicative_factors(N)
+    pq = np.broadcast_to(fq.astype(np.float32), (1, H, N, 2)).copy()
+    pk = np.broadcast_to(fk.astype(np.float32), (1, H, N, 2)).copy()
+    _check(q, k, v, pq, pk, "f32", causal, "cos(i-j)")
+
+
+@pytest.mark.parametrize("C,R,phi_dtype", [(128, 1, "bf16"), (64, 1, "f32"), (32, 3, "bf16"), (16, 5, "f32"),
+                                           (16, 2, "bf16"), (32, 2, "f32")])
+def test_random_factors_rank_range(C, R, phi_dtype):
+    B, H, N = 2, 3, 300
+    q, k, v, rng = _qkv(B, H, N, C, seed=8100 + C + R)
+    # bounded factors, |b_ij| <= 1 as for the cosine example: the scores then stay in the range of the
+    # additive-bias tests, where the 2e-2 bound is meaningful for bf16 operands (a score of
+    # magnitude s carries an absolute error of about s * 2^-8 from the operand rounding alone)
+    sc = R ** -0.5
+    pq = (sc * rng.uniform(-1.0, 1.0, (B, H, N, R))).astype(np.float32)
+    pk = (sc * rng.uniform(-1.0, 1.0, (B, H, N, R))).astype(np.float32)
+    if phi_dtype == "bf16":
+        pq, pk = W.round_bf16(pq), W.round_bf16(pk)
+    _check(q, k, v, pq, pk, phi_dtype, False, "random")
+
+
+def test_unit_bias_is_plain_attention():
+    """phi_q = phi_k = 1 (R = 1): identical numbers to the additive path with R = 0."""
+    B, H, N, C = 1, 2, 384, 64
+    q, k, v, _ = _qkv(B, H, N, C, seed=8200)
+    ones = np.ones((B, H, N, 1), dtype=np.float32)
+    dq_, dk_, dv_ = dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16")
+    o1, l1 = api.fb_lowrank_mulbias_attn_fwd(dq_, dk_, dv_, dev(ones, "f32"), dev(ones, "f32"))
+    o0, l0 = api.fb_lowrank_attn_fwd(dq_, dk_, dv_, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o0) and torch.equal(l1, l0)
+
+
+def test_workspace_reuse_and_argument_errors():
+    B, H, N, C, R = 1, 2, 256, 64, 2
+    q, k, v, rng = _qkv(B, H, N, C, seed=8300)
+    pq = rng.standard_normal((B, H, N, R)).astype(np.float32)
+    pk = rng.standard_normal((B, H, N, R)).astype(np.float32)
+    need = api.fb_lowrank_mulbias_attn_fwd_workspace_bytes(B, H, N, C, R)
+    assert need == 4 * B * H * N * C * R
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    args = [dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), dev(pq, "f32"), dev(pk, "f32")]
+    o1, l1 = api.fb_lowrank_mulbias_attn_fwd(*args, workspace=ws)
+    o2, l2 = api.fb_lowrank_mulbias_attn_fwd(*args, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+    with pytest.raises(api.FlashBiasError):
+        api.fb_lowrank_mulbias_attn_fwd(*args, workspace=ws[:need - 16])
+    pq3 = dev(rng.standard_normal((B, H, N, 3)).astype(np.float32), "f32")
+    with pytest.raises(api.FlashBiasError):      # C (R - 1) = 128 > 64
+        api.fb_lowrank_mulbias_attn_fwd(args[0], args[1], args[2], pq3, pq3)

@@ -101,6 +101,27 @@ def test_dense_and_backward_argument_errors(lib):
     assert bwd(w=72) == 4
 
 
+def test_mulbias_argument_errors(lib):
+    f = lib.fb_lowrank_mulbias_attn_fwd
+    need = lib.fb_lowrank_mulbias_attn_fwd_workspace_bytes(1, 2, 100, 64, 2, api.FB_BF16)
+    assert need == 4 * 1 * 2 * 100 * 64 * 2
+    assert lib.fb_lowrank_mulbias_attn_fwd_workspace_bytes(1, 2, 100, 64, 0, api.FB_BF16) == 0
+
+    def call(ptrs=None, C=64, R=2, dtype=api.FB_BF16, w=64, wb=need):
+        ptrs = ptrs or [64] * 7
+        return f(*ptrs, 1, 2, 100, C, R, 0, dtype, api.FB_F32, 0, 0.0, w, wb, None)
+
+    assert call(ptrs=[64, 64, 64, None, 64, 64, 64]) == 1      # factors are required
+    assert call(R=0) == 2
+    assert call(R=3) == 3                                      # C (R - 1) = 128 > 64
+    assert call(C=128, R=2) == 3
+    assert call(dtype=api.FB_F32) == 3
+    assert call(ptrs=[64, 64, 64, 66, 64, 64, 64]) == 4        # factors not 4-byte aligned
+    assert call(w=None) == 5
+    assert call(wb=need - 1) == 5
+    assert call(w=72) == 4
+
+
 def test_tune_knob(lib):
     assert lib.fb_tune_set(b"fwd_qb", 2) == 0
     assert lib.fb_tune_set(b"fwd_qb", 0) == 0
