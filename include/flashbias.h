@@ -75,6 +75,10 @@ const char* fb_status_string(int status);
  *                 4    = in-wave interleaved kernel (falls back to 1 for padded rank > 32)
  *                 8    = eight-wave ping-pong kernel
  *                 16   = direct-to-LDS kernel (falls back to 1 for shapes it does not take)
+ *   "fwd_causal_up" 1 (default): of the two query tiles a workgroup of the causal four-wave
+ *                 kernel takes, the first walks its off-diagonal key blocks upwards from key 0
+ *                 and the second downwards, so the workgroups of a head read the same block at
+ *                 the same time (fewer L2 misses); 0: both walk downwards from the diagonal.
  *   "fwd_lds_pad" extra dynamic LDS bytes per workgroup of the four-wave kernel
  *                 (0 .. 102400), to study occupancy; 0 by default.
  */

@@ -14,6 +14,7 @@ namespace {
 
 std::atomic<int> g_fwd_qb{0};   // 0 = choose automatically
 std::atomic<int> g_lds_pad{0};
+std::atomic<int> g_causal_up{1};
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -73,6 +74,11 @@ int fb_tune_set(const char* name, int value) {
         g_fwd_qb.store(value, std::memory_order_relaxed);
         return FB_OK;
     }
+    if (std::strcmp(name, "fwd_causal_up") == 0) {
+        if (value != 0 && value != 1) return FB_ERR_SHAPE;
+        g_causal_up.store(value, std::memory_order_relaxed);
+        return FB_OK;
+    }
     if (std::strcmp(name, "fwd_lds_pad") == 0) {
         if (value < 0 || value > 100 * 1024) return FB_ERR_SHAPE;
         g_lds_pad.store(value, std::memory_order_relaxed);
@@ -109,6 +115,7 @@ static int lowrank_fwd_impl(const void* q, const void* k, const void* v,
     p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
     p.phik_bstride = phi_batch_broadcast ? 0 : (long long)H * M * R;
     p.bias_bstride = 0;
+    p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int rc;
     if (dtype == FB_F32) {
@@ -157,6 +164,7 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
     p.phi_bstride = 0;
     p.phik_bstride = 0;
     p.bias_bstride = bias_batch_broadcast ? 0 : (long long)H * N * N;
+    p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int rc;
     if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, true, (hipStream_t)stream);
@@ -182,6 +190,7 @@ int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* 
     p.phi_bstride = 0;
     p.phik_bstride = 0;
     p.bias_bstride = 0;
+    p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     int qb = pick_qb(B, H, N, C, 16, false, causal != 0);
     if (qb != 2) qb = 1;     // only the four-wave kernel generates factors
@@ -237,6 +246,7 @@ int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
     p.phi_bstride = (long long)H * N * rest;
     p.phik_bstride = (long long)H * N * rest;
     p.bias_bstride = 0;
+    p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = 1.0f;                                 // already folded into q'
     const int rc = fb_launch_fwd_bf16(p, C, rest, false, pick_qb(B, H, N, C, rest, false, causal != 0),
                                       (hipStream_t)stream);

@@ -97,7 +97,7 @@ struct Cfg {
 // CG: channels per head in global memory.  CG < C (head dimension 16 run on the C = 32 tiles)
 // zero-fills channels CG..C-1 of q, k and v on the way in and never stores them.
 template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE, int CG = C>
-FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, const int qt) {
+FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, const int qt, const bool asc = false) {
     using K = Cfg<C, RP, QB>;
     bf16_t* const kt = (bf16_t*)smem;                 // [NBUF][BK][KP]
     bf16_t* const vt = kt + NBUF * K::KBLK;           // [NBUF][BK][VP]
@@ -171,10 +171,21 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 
     const int kend = CAUSAL ? min(M, q0 + K::BQ) : M;
     const int nT = (kend + BK - 1) / BK;
-    // Causal tiles walk the keys from the diagonal back to key 0: with a recency bias such as
-    // ALiBi the row maximum is then met in the first block and the accumulator is never
-    // rescaled again (in ascending order it would be rescaled in nearly every block).
-    auto blk_of = [&](int t) { return CAUSAL ? max(nT - 1 - t, 0) : t; };
+    // Causal tiles start at their diagonal blocks: with a recency bias such as ALiBi the row
+    // maximum is then met at once and the accumulator is never rescaled again (walking up to
+    // the diagonal it would be rescaled in nearly every block).  The other blocks follow either
+    // downwards to key 0 or (asc) upwards from key 0.  The first tile of a workgroup's pair
+    // goes up and the second down: the workgroups of one head, launched together, then read
+    // the same key block at the same time in both phases (the tile n-1-u reaches block t after
+    // 4 QB + t steps whatever u is, and every second tile reaches block 0 after the same total
+    // number of steps), so a K/V block is fetched into the XCD's L2 once instead of once per
+    // straggling workgroup.
+    const int nd = CAUSAL ? nT - q0 / BK : 0;      // blocks on the tile's diagonal (taken first, downwards)
+    auto blk_of = [&](int t) {
+        if (!CAUSAL) return t;
+        if (asc && t >= nd) return min(t - nd, nT - 1);
+        return max(nT - 1 - t, 0);
+    };
 
     // ---- block staging: global -> registers -> LDS.  Rows past M are clamped to row M-1; the
     // keys they stand for are masked to -inf before the softmax, so their values never count.
@@ -587,7 +598,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_kernel(FwdParams p) {
     }
     if (CAUSAL) {
         const int heavy = p.n_qtiles - 1 - u;
-        fwd_tile<C, RP, QB, PM, CAUSAL, DENSE, CG>(p, smem, bh, heavy);
+        fwd_tile<C, RP, QB, PM, CAUSAL, DENSE, CG>(p, smem, bh, heavy, p.causal_up != 0);
         if (u != heavy) {
             __syncthreads();   // the LDS ring is reused: every wave must have left the first tile
             fwd_tile<C, RP, QB, PM, CAUSAL, DENSE, CG>(p, smem, bh, u);

@@ -89,6 +89,21 @@ def test_bf16_head_dim_16(N, causal):
     _check_lowrank(W.make_workload("long_train", B=1, H=2, N=N, C=16, R=5, causal=causal))
 
 
+@pytest.mark.parametrize("up", [0, 1])
+@pytest.mark.parametrize("N", [100, 640, 1000])
+def test_causal_walk_orders(N, up):
+    """Both key-block orders of the causal tile pairs give the oracle's result (any order is exact
+    for an online softmax; the two differ only in rounding)."""
+    w = W.make_workload("alibi_causal", dense=True, B=1, H=3, N=N)
+    api.fb_tune_set("fwd_causal_up", up)
+    try:
+        for qb in (1, 2):
+            _check_lowrank(w, qb=qb)
+        _check_dense(w, qb=1)
+    finally:
+        api.fb_tune_set("fwd_causal_up", 1)
+
+
 @pytest.mark.parametrize("N", [1, 31, 64, 65])
 @pytest.mark.parametrize("causal", [False, True])
 def test_bf16_edge_lengths(N, causal):

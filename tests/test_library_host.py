@@ -128,6 +128,9 @@ def test_tune_knob(lib):
     assert lib.fb_tune_set(b"fwd_qb", 3) == 2
     assert lib.fb_tune_set(b"fwd_qb", 8) == 0
     assert lib.fb_tune_set(b"fwd_qb", 0) == 0
+    assert lib.fb_tune_set(b"fwd_causal_up", 0) == 0
+    assert lib.fb_tune_set(b"fwd_causal_up", 2) == 2
+    assert lib.fb_tune_set(b"fwd_causal_up", 1) == 0
     assert lib.fb_tune_set(b"nope", 1) == 3
     assert lib.fb_tune_set(None, 1) == 1
 
