@@ -649,20 +649,6 @@ int dispatch_pm(const FwdParams& p, int qb, hipStream_t stream) {
     return dispatch_qb<C, RP, 2, false, CG>(p, qb, stream);
 }
 
-// Head dimension 16 on the C = 32 tiles of the four-wave kernel (qb = 1 or 2).
-inline int fwd_bf16_dispatch_c16(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream) {
-    if (qb != 2) qb = 1;
-    if (dense) return dispatch_qb<32, 0, 0, true, 16>(p, qb, stream);
-    switch (rp) {
-        case 0: return dispatch_qb<32, 0, 0, false, 16>(p, qb, stream);
-        case 16: return dispatch_pm<32, 16, 16>(p, qb, stream);
-        case 32: return dispatch_pm<32, 32, 16>(p, qb, stream);
-        case 48: return dispatch_pm<32, 48, 16>(p, qb, stream);
-        case 64: return dispatch_pm<32, 64, 16>(p, qb, stream);
-        default: return -1;
-    }
-}
-
 // rp: padded factor width (multiple of 16, <= 64); qb: 32-row query blocks per wave of the
 // four-wave kernel (1 or 2; 2 exists for C <= 64 only and falls back to 1 otherwise), or 8 for
 // the eight-wave ping-pong kernel.
