@@ -40,20 +40,9 @@
 #include "fb_launch.h"
 #include "fb_params.h"
 
-#ifndef FB_PRIO_MFMA
-#define FB_PRIO_MFMA 2
-#endif
-
-#ifdef FB_TRACE4
-__device__ long long fb_trace4_buf[4 * 64 * 8];
-#define FB_T4(slot)                                                                         \
-    if (blockIdx.x == FB_TRACE4 && lane == 0 && t < 64) fb_trace4_buf[(wave * 64 + t) * 8 + (slot)] = clock64();
-#else
-#define FB_T4(slot)
-#endif
-
 namespace {
 
+constexpr int kPrioMfma = 2;   // wave priority while an MFMA chain is being issued
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int BK = 32;       // keys per block
@@ -393,7 +382,6 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     // MFMA chains of a block no row of this wave can see; interior blocks carry none of that.
     auto body = [&](int t, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        FB_T4(0)
         const int kb0 = blk_of(t) * BK;
         const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;       // (t+1) % NBUF
         const int buf2 = buf1 == NBUF - 1 ? 0 : buf1 + 1;     // (t+2) % NBUF
@@ -423,7 +411,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         {
             const bf16_t* vbase = vt + buf * K::VBLK + vlane_off;
             constexpr int NV = (C / 32) * 2;
-            __builtin_amdgcn_s_setprio(FB_PRIO_MFMA);
+            __builtin_amdgcn_s_setprio(kPrioMfma);
 #pragma unroll
             for (int ks = 0; ks < K::KS; ks++) {
                 if (!skip) {
@@ -441,14 +429,12 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             __builtin_amdgcn_s_setprio(0);
         }
 
-        FB_T4(1)
         // ---- staging: block t+2 registers -> LDS, block t+3 global -> registers ----
         store_block(buf2, t + 2);
         load_block(t + 3);
         stage_bias();                   // block t+1 (loaded one iteration ago) -> wave-private LDS
         load_bias(t + 2);
         __builtin_amdgcn_sched_barrier(0);
-        FB_T4(2)
 
         // ---- online softmax: a row lives in this lane and the one 32 away ----
         bf16x8 pb[QB][2];
@@ -507,13 +493,12 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             lsum[qb] += psum;
         }
         __builtin_amdgcn_sched_barrier(0);
-        FB_T4(3)
 
         // ---- O^T += V^T . P^T, each MFMA followed by a K operand read of the next block ----
         {
             const bf16_t* krow = kt + buf1 * K::KBLK + krow_off;
             constexpr int NM = (C / 32) * 2;
-            __builtin_amdgcn_s_setprio(FB_PRIO_MFMA);
+            __builtin_amdgcn_s_setprio(kPrioMfma);
 #pragma unroll
             for (int i = 0; i < NM; i++) {
                 if (!skip) {
@@ -528,9 +513,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             }
             __builtin_amdgcn_s_setprio(0);
         }
-        FB_T4(4)
         __syncthreads();
-        FB_T4(5)
         buf = buf1;
     };
 

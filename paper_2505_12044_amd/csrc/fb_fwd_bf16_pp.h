@@ -29,13 +29,6 @@
 #include "fb_launch.h"
 #include "fb_params.h"
 
-#ifdef FB_TRACE
-__device__ long long fb_trace_buf[8 * 64 * 8];
-#define FB_T(slot)                                                                          \
-    if (blockIdx.x == FB_TRACE && lane == 0 && t < 64) fb_trace_buf[(wave * 64 + t) * 8 + (slot)] = clock64();
-#else
-#define FB_T(slot)
-#endif
 
 namespace fbpp {
 
@@ -283,12 +276,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
         const int buf3 = (buf + 3) & (NBUF - 1);
 
         // ================= VALU phase =================
-        FB_T(0)
         store_block(buf3);              // block t+3 (loaded two iterations ago)
         rotate_regs();
         load_block(t + 5);
         __builtin_amdgcn_sched_barrier(0);
-        FB_T(1)
 
         if (MASKED) {
 #pragma unroll
@@ -337,9 +328,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
         }
         lsum += psum;
         __builtin_amdgcn_sched_barrier(0);
-        FB_T(2)
         __syncthreads();
-        FB_T(3)
 
         // ================= MFMA phase =================
         // a block no row of this wave can see contributes P = 0: its chains are skipped
@@ -384,9 +373,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
         }
         __builtin_amdgcn_s_setprio(0);
         __builtin_amdgcn_sched_barrier(0);
-        FB_T(4)
         __syncthreads();
-        FB_T(5)
         buf = buf1;
     };
 
