@@ -202,48 +202,53 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         __syncthreads();   // before any thread writes item columns into the same rows
     }
 
-    // byte offsets of this thread's chunks inside a block (row-major rows of CG elements);
-    // chunks of the channels past CG are never loaded and stay zero
-    unsigned goff[K::KIT];
+    // This thread's chunks of a block: byte offset of the chunk's row inside the block and of the
+    // chunk inside the row (rows of CG elements); chunks of the channels past CG are never
+    // loaded and stay zero.  All offsets inside one head fit 32 bits (the entry points reject
+    // larger problems).  A row past M is clamped to row M-1 by a minimum on the byte offset,
+    // so one code path serves whole and partial blocks without a multiply.
+    unsigned grow[K::KIT], gcol[K::KIT];
     bool gok[K::KIT];
 #pragma unroll
     for (int it = 0; it < K::KIT; it++) {
         const int e = tid + it * kThreads;
-        goff[it] = (unsigned)(((e / (C / 8)) * CG + (e % (C / 8)) * 8) * 2);
+        grow[it] = (unsigned)((e / (C / 8)) * CG * 2);
+        gcol[it] = (unsigned)((e % (C / 8)) * 16);
         gok[it] = (K::KCH % kThreads == 0 || e < K::KCH) && (CG == C || (e % (C / 8)) * 8 < CG);
         kraw[it] = u32x4{0u, 0u, 0u, 0u};
         vraw[it] = u32x4{0u, 0u, 0u, 0u};
     }
     const unsigned char* kgb = (const unsigned char*)kg;
     const unsigned char* vgb = (const unsigned char*)vg;
+    const unsigned kv_last = (unsigned)(M - 1) * (unsigned)(CG * 2);       // byte offset of the last row
+    const unsigned phi_rb = (unsigned)R * (unsigned)phi_esz;                // bytes per factor row
+    const unsigned phi_last = (unsigned)(M - 1) * phi_rb;
+    unsigned fitem_off[K::FIT], fitem_col[K::FIT];
+    if (PM == 3) {
+#pragma unroll
+        for (int it = 0; it < K::FIT; it++) {
+            fitem_off[it] = (unsigned)fitem_row[it] * phi_rb;
+            fitem_col[it] = (unsigned)fitem_r[it] * 4u;
+        }
+    }
 
     auto load_block = [&](int t) {
         const int k0 = blk_of(t) * BK;
-        if (k0 + BK <= M) {   // whole block in range (wave-uniform): base + 32-bit offset
-            const unsigned boff = (unsigned)k0 * (unsigned)(CG * 2);
+        const unsigned boff = (unsigned)k0 * (unsigned)(CG * 2);
 #pragma unroll
-            for (int it = 0; it < K::KIT; it++) {
-                if ((CG == C && K::KCH % kThreads == 0) || gok[it]) {
-                    kraw[it] = *(const u32x4*)(kgb + (boff + goff[it]));
-                    vraw[it] = *(const u32x4*)(vgb + (boff + goff[it]));
-                }
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < K::KIT; it++) {
-                const int e = tid + it * kThreads;
-                if ((CG == C && K::KCH % kThreads == 0) || gok[it]) {
-                    const int row = e / (C / 8), c8 = e % (C / 8);
-                    const int j = min(k0 + row, M - 1);
-                    kraw[it] = *(const u32x4*)(kg + (size_t)j * CG + c8 * 8);
-                    vraw[it] = *(const u32x4*)(vg + (size_t)j * CG + c8 * 8);
-                }
+        for (int it = 0; it < K::KIT; it++) {
+            if ((CG == C && K::KCH % kThreads == 0) || gok[it]) {
+                const unsigned off = min(boff + grow[it], kv_last) + gcol[it];
+                kraw[it] = *(const u32x4*)(kgb + off);
+                vraw[it] = *(const u32x4*)(vgb + off);
             }
         }
+        const unsigned pboff = (unsigned)k0 * phi_rb;
         if (PM == 3) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
-                if (fitem_ok[it]) fraw[it] = pkf[(size_t)min(k0 + fitem_row[it], M - 1) * R + fitem_r[it]];
+                if (fitem_ok[it])
+                    fraw[it] = *(const float*)(pkg + (min(pboff + fitem_off[it], phi_last) + fitem_col[it]));
         } else if (PM == 4) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
@@ -251,13 +256,12 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
-                // rotate the factor chunks over the waves from block to block so the
-                // conversion work of the general mode is shared
-                const int e = ((tid + 64 * t) & (kThreads - 1)) + it * kThreads;
+                // general mode: rotate the factor chunks over the waves from block to block so
+                // the conversion work is shared (whole-chunk copies need no conversion)
+                const int e = ((tid + (PM == 2 ? 64 * t : 0)) & (kThreads - 1)) + it * kThreads;
                 if (K::PCH % kThreads == 0 || e < K::PCH) {
                     const int row = e / (RP / 8), c8 = e % (RP / 8);
-                    const int j = min(k0 + row, M - 1);
-                    const unsigned char* src = pkg + (size_t)j * R * phi_esz;
+                    const unsigned char* src = pkg + min(pboff + __umul24((unsigned)row, phi_rb), phi_last);
                     if (PM == 1) {
                         praw[it] = (c8 * 8 < R) ? *(const u32x4*)(src + c8 * 16) : u32x4{0u, 0u, 0u, 0u};
                     } else {
@@ -288,7 +292,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
-                const int e = ((tid + 64 * t) & (kThreads - 1)) + it * kThreads;
+                const int e = ((tid + (PM == 2 ? 64 * t : 0)) & (kThreads - 1)) + it * kThreads;
                 if (K::PCH % kThreads == 0 || e < K::PCH) {
                     const int row = e / (RP / 8), c8 = e % (RP / 8);
                     const u32x4 v = PM == 1 ? praw[it] : as_uint4(phi_chunk_finish<false>(praw[it], c8, phi_f32));
