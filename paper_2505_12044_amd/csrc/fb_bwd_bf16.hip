@@ -302,8 +302,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     // ---- this wave's share of a block's direct loads: load d = wave + 4*j, j < my_ndma ----
     // wave-uniform per load: source array, bytes per block and per row, LDS offset inside a slot;
     // per lane: source row (a chunk index for the vec rows) and byte offset inside the row
-    int dma_row[NDW];
-    unsigned dma_col[NDW];
+    unsigned dma_rowoff[NDW], dma_col[NDW];
     const unsigned char* dma_src[NDW];
     int dma_bstride[NDW], dma_pitch[NDW], dma_lshift[NDW], dma_dst[NDW];
 #pragma unroll
@@ -330,7 +329,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             dma_col[j] = 0u;
             dma_dst[j] = kOffVec;
         }
-        dma_row[j] = row;
+        dma_rowoff[j] = (unsigned)(row * dma_pitch[j]);
     }
     const int my_ndma = (ND - wave + kWaves - 1) / kWaves;     // wave-uniform: NDW or NDW - 1
     auto issue_block = [&](int i, int slot) __attribute__((always_inline)) {
@@ -340,7 +339,8 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
         for (int j = 0; j < NDW; j++) {
             if (j < my_ndma) {
-                const unsigned voff = (unsigned)(min(dma_row[j], left >> dma_lshift[j]) * dma_pitch[j]) + dma_col[j];
+                // rows past the end repeat the last valid row: a minimum on the byte offset (scalar operand)
+                const unsigned voff = min(dma_rowoff[j], (unsigned)((left >> dma_lshift[j]) * dma_pitch[j])) + dma_col[j];
                 dma16(dma_src[j] + (size_t)blk * dma_bstride[j], voff, sbase + dma_dst[j]);
             }
         }

@@ -133,8 +133,9 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
     if (PM != 0) {
         const int pe = K::PDIV ? tid / K::PSUB : tid;
         p_active = K::PDIV ? (tid % K::PSUB) == 0 : tid < K::PCH;
-        prow = pe / (RP / 8);
-        pc8 = pe % (RP / 8);
+        constexpr int kChunksPerRow = RP > 0 ? RP / 8 : 1;
+        prow = pe / kChunksPerRow;
+        pc8 = pe % kChunksPerRow;
     }
     // two blocks are kept in flight in registers (global latency exceeds one iteration):
     // (kraw, vraw, praw) is the older one, (kraw2, vraw2, praw2) the newer
@@ -146,17 +147,24 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
         praw = praw2;
     };
 
+    // 32-bit byte offsets inside the head (the entry points reject larger problems); rows past
+    // N are clamped to row N-1 by a minimum on the offset
+    const unsigned char* kgb = (const unsigned char*)kg;
+    const unsigned char* vgb = (const unsigned char*)vg;
+    const unsigned grow_off = (unsigned)krow * (unsigned)(C * 2), gcol_off = (unsigned)kc8 * 16u;
+    const unsigned kv_last = (unsigned)(N - 1) * (unsigned)(C * 2);
+    const unsigned phi_rb = (unsigned)R * (unsigned)phi_esz;
+    const unsigned prow_off = (unsigned)prow * phi_rb, phi_last = (unsigned)(N - 1) * phi_rb;
     auto load_block = [&](int t) {
         const int k0 = t * BK;
         if (k_active) {
-            const int j = min(k0 + krow, N - 1);
-            kraw2 = *(const u32x4*)(kg + (size_t)j * C + kc8 * 8);
-            vraw2 = *(const u32x4*)(vg + (size_t)j * C + kc8 * 8);
+            const unsigned off = min((unsigned)k0 * (unsigned)(C * 2) + grow_off, kv_last) + gcol_off;
+            kraw2 = *(const u32x4*)(kgb + off);
+            vraw2 = *(const u32x4*)(vgb + off);
         }
         if (PM != 0) {
             if (p_active) {
-                const int j = min(k0 + prow, N - 1);
-                const unsigned char* src = pkg + (size_t)j * R * phi_esz;
+                const unsigned char* src = pkg + min((unsigned)k0 * phi_rb + prow_off, phi_last);
                 if (PM == 1) {
                     praw2 = (pc8 * 8 < R) ? *(const u32x4*)(src + pc8 * 16) : u32x4{0u, 0u, 0u, 0u};
                 } else {
