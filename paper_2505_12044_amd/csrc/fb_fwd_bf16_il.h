@@ -76,7 +76,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_il_kernel(FwdParams p) {
     const bool phi_f32 = PM == 2 && p.phi_f32 != 0;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it scalar
     const int l32 = lane & 31, hf = lane >> 5;
     const int q0 = qt * K::BQ;
     const int qw0 = q0 + wave * (QB * 32);

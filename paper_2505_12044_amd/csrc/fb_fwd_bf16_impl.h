@@ -97,7 +97,8 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     const float slope = PM == 4 ? p.slopes[h] : 0.f;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it scalar
     const int l32 = lane & 31, hf = lane >> 5;
     const int q0 = qt * K::BQ;
     const int qw0 = q0 + wave * (QB * 32);

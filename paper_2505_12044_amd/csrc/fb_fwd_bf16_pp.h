@@ -72,7 +72,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
     const bool phi_f32 = PM == 2 && p.phi_f32 != 0;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it scalar
     const int grp = wave >> 2;                        // waves w and w+4 share a SIMD
     const int l32 = lane & 31, hf = lane >> 5;
     const int q0 = qt * K::BQ;
