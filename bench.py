@@ -50,8 +50,9 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="headline kernel only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--probe", action="store_true",
-                    help="counter-collection mode: 3 launches each of the low-rank and dense "
-                         "forward plus one 1 GiB device copy (calibration), no timing output")
+                    help="counter-collection mode: 3 launches each of the low-rank forward, the dense "
+                         "forward and the low-rank backward plus one 1 GiB device copy (calibration), "
+                         "no timing output")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, "
@@ -130,6 +131,13 @@ def main() -> int:
         for _ in range(3):
             api.fb_dense_bias_attn_fwd(d["q"], d["k"], d["v"], d["bias"], out=d["out"], lse=d["lse"],
                                        causal=w.causal, stream=stream)
+        if "dout" in d:
+            wsb = torch.empty(max(16, api.fb_lowrank_attn_bwd_workspace_bytes(w.B, w.H, w.N, w.C, w.R)),
+                              dtype=torch.uint8, device="cuda")
+            fwd()
+            for _ in range(3):
+                api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], d["out"], d["lse"],
+                                        d["dout"], causal=w.causal, workspace=wsb, stream=stream)
         dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"probe": w.name, "copy_bytes_read": src.numel() * 4,
