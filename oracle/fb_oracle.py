@@ -46,6 +46,7 @@ __all__ = [
     "attention_with_bias",
     "attention_lowrank",
     "attention_with_multiplicative_bias",
+    "attention_multiplicative_lowrank_grads",
     "multiplicative_concat",
     "cosine_multiplicative_factors",
     "attention_with_bias_grads",
@@ -226,6 +227,32 @@ def attention_lowrank_grads(q, k, v, phi_q, phi_k, dout, causal=False, scale=Non
             dphi_q[r0:r1] = ds @ phi_k
             dphi_k += ds.T @ phi_q[r0:r1]
     return dq, dk, dv, dphi_q, dphi_k
+
+
+def attention_multiplicative_lowrank_grads(q, k, v, phi_q, phi_k, dout, causal=False, scale=None):
+    """(dq, dk, dv, dphi_q, dphi_k) for one head of the multiplicative form (App. I),
+    s = (scale q k^T) o b with b = phi_q phi_k^T, L = sum(dO * O).  Chain rule on the definition
+    (the appendix gives no backward): with a = scale q k^T and ds from the softmax Jacobian,
+    da = ds o b, db = ds o a, dq = scale da k, dk = scale da^T q, dphi_q = db phi_k,
+    dphi_k = db^T phi_q, dv = p^T dO."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    phi_q, phi_k = _f64(phi_q), _f64(phi_k)
+    if scale is None:
+        scale = 1.0 / np.sqrt(q.shape[1])
+    b = phi_q @ phi_k.T
+    a = scale * (q @ k.T)
+    s = a * b
+    if causal:
+        i = np.arange(q.shape[0])[:, None]
+        j = np.arange(k.shape[0])[None, :]
+        s = np.where(j > i, -np.inf, s)
+    p, _ = _softmax_rows(s)
+    dv = p.T @ dout
+    dp = dout @ v.T
+    ds = p * (dp - np.sum(p * dp, axis=1, keepdims=True))
+    da = ds * b
+    db = ds * a
+    return scale * (da @ k), scale * (da.T @ q), dv, db @ phi_k, db.T @ phi_q
 
 
 # ----------------------------------------------------------------------------------

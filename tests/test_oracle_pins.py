@@ -380,6 +380,43 @@ def test_multiplicative_bias_brute_force_and_identities(causal):
     assert np.max(np.abs(o - O.attention_with_bias(q, k, v, b, causal=causal)[0])) > 1e-3
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_multiplicative_gradients_finite_differences(causal):
+    """Chain-rule gradients of the multiplicative form against central differences of the
+    forward definition, every input element."""
+    rng = np.random.default_rng(21)
+    n, c, r = 8, 5, 2
+    arrs = [_rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, c), _rand(rng, n, r), _rand(rng, n, r)]
+    dout = _rand(rng, n, c)
+
+    def loss():
+        o, _ = O.attention_with_multiplicative_bias(arrs[0], arrs[1], arrs[2], O.lowrank_bias(arrs[3], arrs[4]),
+                                                    causal=causal)
+        return float(np.sum(o * dout))
+
+    grads = O.attention_multiplicative_lowrank_grads(*arrs, dout, causal=causal)
+    eps = 1e-6
+    for a, g in zip(arrs, grads):
+        num = np.zeros_like(a)
+        it = np.nditer(a, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = a[idx]
+            a[idx] = old + eps
+            lp = loss()
+            a[idx] = old - eps
+            lm = loss()
+            a[idx] = old
+            num[idx] = (lp - lm) / (2 * eps)
+        np.testing.assert_allclose(g, num, rtol=1e-6, atol=1e-8)
+    # b = 1 (phi = 1, R = 1): dq, dk, dv equal those of plain attention
+    ones = np.ones((n, 1))
+    g1 = O.attention_multiplicative_lowrank_grads(arrs[0], arrs[1], arrs[2], ones, ones, dout, causal=causal)
+    g0 = O.attention_with_bias_grads(arrs[0], arrs[1], arrs[2], None, dout, causal=causal)
+    for x, y in zip(g1[:3], g0[:3]):
+        np.testing.assert_allclose(x, y, atol=1e-13)
+
+
 def test_pde_workload_factors_equal_dense_definition():
     """The generator's rank-9 factors against the oracle's dense definition of the weighted
     squared-distance bias (Example 3.5 with the token-wise weight of Sec. 4.3)."""
