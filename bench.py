@@ -347,11 +347,21 @@ def main() -> int:
             api.fb_lowrank_attn_fwd(qm, km, vm, None, None, out=om, lse=lm, stream=stream)
         _, ms_m = time_calls(fm_, 10, 2)
         _, ms_p = time_calls(plain, 10, 2)
+        dom = torch.randn((Bm, Hm, Nm, Cm), device="cuda", generator=g).to(torch.bfloat16)
+        wsb = torch.empty(api.fb_lowrank_mulbias_attn_bwd_workspace_bytes(Bm, Hm, Nm, Cm, 2), dtype=torch.uint8,
+                          device="cuda")
+        fm_()
+
+        def bm_():
+            api.fb_lowrank_mulbias_attn_bwd(qm, km, vm, fm, fm, om, lm, dom, workspace=wsb, stream=stream)
+        _, ms_mb = time_calls(bm_, 5, 1)
+        del wsb, dom
         pairs_m = Bm * Hm * Nm * Nm
         others["multiplicative_cos"] = {
             "B": Bm, "H": Hm, "N": Nm, "C": Cm, "R": 2, "fwd_ms_incl_prepass": round(ms_m, 4),
             "fwd_TFLOPs": round(2.0 * (Cm * 2 + Cm) * pairs_m / (ms_m * 1e-3) / 1e12, 2),
             "plain_attention_ms": round(ms_p, 4), "cost_vs_plain": round(ms_m / ms_p, 3),
+            "bwd_ms_incl_prepass_and_fold": round(ms_mb, 4),
             "dense_bias_bytes_avoided": int(Hm * Nm * Nm * 2)}
         del qm, km, vm, om, lm, wsm
         result["other_workloads"] = others

@@ -154,6 +154,26 @@ int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
                                 float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Backward of fb_lowrank_mulbias_attn_fwd (chain rule on App. I's reformulation; the appendix
+ * itself stops at the forward): dq, dk, dv [B,H,N,C] dtype and dphi_q, dphi_k [B,H,N,R]
+ * phi_dtype, always per batch element.  The pre-pass of the forward is repeated, the
+ * additive-bias backward kernels give the gradients of the reweighted repeats q', k', and a
+ * fold kernel applies dq = scale sum_r phi_q,r dq'_r, dphi_q,r = scale sum_c q_c dq'_r,c (and
+ * the same without the scale on the key side).  Same limits as the forward.
+ *   workspace: fb_lowrank_mulbias_attn_bwd_workspace_bytes(...) bytes (the repeats, their
+ *   gradients and the additive backward's scratch), 16-byte aligned, caller-owned.
+ */
+size_t fb_lowrank_mulbias_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype);
+
+int fb_lowrank_mulbias_attn_bwd(const void* q, const void* k, const void* v,
+                                const void* phi_q, const void* phi_k,
+                                const void* out, const float* lse, const void* dout,
+                                void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                                int B, int H, int N, int C, int R, int causal,
+                                fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                                float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Backward of fb_lowrank_attn_fwd for an upstream gradient dout (loss L = sum(dout * out)):
  * dq, dk, dv [B,H,N,C] dtype; dphi_q, dphi_k [B,H,N,R] phi_dtype, always per batch element
  * (a caller whose factors are shared over the batch sums them over B).  The factor

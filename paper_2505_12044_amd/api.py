@@ -25,6 +25,7 @@ EXPORTS = (
     "fb_lowrank_attn_bwd", "fb_lowrank_xattn_bwd_workspace_bytes", "fb_lowrank_xattn_bwd",
     "fb_dense_bias_attn_bwd_workspace_bytes", "fb_dense_bias_attn_bwd",
     "fb_lowrank_mulbias_attn_fwd_workspace_bytes", "fb_lowrank_mulbias_attn_fwd",
+    "fb_lowrank_mulbias_attn_bwd_workspace_bytes", "fb_lowrank_mulbias_attn_bwd",
 )
 
 
@@ -74,6 +75,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_lowrank_mulbias_attn_fwd_workspace_bytes.argtypes = [ci] * 5 + [ci]
     lib.fb_lowrank_mulbias_attn_fwd.restype = ci
     lib.fb_lowrank_mulbias_attn_fwd.argtypes = [vp] * 7 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
+    lib.fb_lowrank_mulbias_attn_bwd_workspace_bytes.restype = sz
+    lib.fb_lowrank_mulbias_attn_bwd_workspace_bytes.argtypes = [ci] * 5 + [ci]
+    lib.fb_lowrank_mulbias_attn_bwd.restype = ci
+    lib.fb_lowrank_mulbias_attn_bwd.argtypes = [vp] * 13 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
     if path is None:
         _lib_handle = lib
     return lib
@@ -187,6 +192,34 @@ def fb_lowrank_mulbias_attn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, causa
                                          _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "fb_lowrank_mulbias_attn_fwd")
     return out, lse
+
+
+def fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R, dtype_code=FB_BF16) -> int:
+    return int(load_library().fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R, dtype_code))
+
+
+def fb_lowrank_mulbias_attn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, causal=False, scale: float = 0.0,
+                                phi_batch_broadcast: Optional[bool] = None, workspace=None, stream=None):
+    """dq, dk, dv, dphi_q, dphi_k of the multiplicative-bias attention (dphi_*: [B,H,N,R] in the
+    factors' dtype, per batch element)."""
+    lib = load_library()
+    B, H, N, C = q.shape
+    R = phi_q.shape[-1]
+    if phi_batch_broadcast is None:
+        phi_batch_broadcast = phi_q.shape[0] == 1 and B > 1
+    need = fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    dpq = torch.empty((B, H, N, R), dtype=phi_q.dtype, device=q.device)
+    dpk = torch.empty((B, H, N, R), dtype=phi_k.dtype, device=q.device)
+    st = lib.fb_lowrank_mulbias_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(phi_q), _ptr(phi_k), _ptr(out), _ptr(lse),
+                                         _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dpq), _ptr(dpk),
+                                         B, H, N, C, R, int(bool(causal)), _dtype_code(q), _dtype_code(phi_q),
+                                         int(bool(phi_batch_broadcast)), float(scale), _ptr(workspace),
+                                         workspace.numel(), _stream(stream))
+    _check(st, "fb_lowrank_mulbias_attn_bwd")
+    return dq, dk, dv, dpq, dpk
 
 
 def fb_alibi_attn_fwd(q, k, v, slopes, out=None, lse=None, causal=False, scale: float = 0.0,

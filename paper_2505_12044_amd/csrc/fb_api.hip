@@ -253,6 +253,73 @@ int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
+size_t fb_lowrank_mulbias_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype) {
+    (void)dtype;
+    if (B <= 0 || H <= 0 || N <= 0 || C <= 0 || R <= 0) return 0;
+    const long long rows = (long long)B * H * N;
+    // q', k' and their gradients (C R bf16 channels each) and the additive backward's own scratch
+    return (size_t)4 * rows * C * R * 2 + fb_bwd_workspace_bytes(rows, rows, C, C * (R - 1));
+}
+
+int fb_lowrank_mulbias_attn_bwd(const void* q, const void* k, const void* v,
+                                const void* phi_q, const void* phi_k,
+                                const void* out, const float* lse, const void* dout,
+                                void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                                int B, int H, int N, int C, int R, int causal,
+                                fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                                float scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !phi_q || !phi_k || !out || !lse || !dout || !dq || !dk || !dv || !dphi_q || !dphi_k)
+        return FB_ERR_NULL;
+    if (R <= 0) return FB_ERR_SHAPE;
+    if (int st = check_common(B, H, N, C, R)) return st;
+    if ((long long)B * H * N * (long long)C * R >= (1LL << 31)) return FB_ERR_SHAPE;
+    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    const int rest = C * (R - 1);
+    if (rest > 64) return FB_ERR_UNSUPPORTED;
+    const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
+    for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
+    const void* p4[] = {phi_q, phi_k, dphi_q, dphi_k};
+    for (const void* ptr : p4) if ((reinterpret_cast<uintptr_t>(ptr) & 3u) != 0) return FB_ERR_ALIGN;
+    if (!workspace || workspace_bytes < fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R, dtype))
+        return FB_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FB_ERR_ALIGN;
+
+    const size_t rows = (size_t)B * H * N;
+    const size_t head_b = rows * C * 2, rest_b = rows * (size_t)rest * 2;
+    unsigned char* ws = (unsigned char*)workspace;
+    void* qh = ws;                 void* kh = ws + head_b;
+    void* qr = ws + 2 * head_b;    void* kr = ws + 2 * head_b + rest_b;
+    unsigned char* g = ws + 2 * head_b + 2 * rest_b;       // gradients in the same order
+    void* dqh = g;                 void* dkh = g + head_b;
+    void* dqr = g + 2 * head_b;    void* dkr = g + 2 * head_b + rest_b;
+    void* inner = g + 2 * head_b + 2 * rest_b;
+    const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    const long long pbs = phi_batch_broadcast ? 0 : (long long)H * N * R;
+    const int f32 = phi_dtype == FB_F32;
+    hipStream_t st = (hipStream_t)stream;
+    if (fb_launch_mulbias_prep(q, phi_q, qh, qr, B, (long long)H * N, C, R, f32, pbs, sc, st) ||
+        fb_launch_mulbias_prep(k, phi_k, kh, kr, B, (long long)H * N, C, R, f32, pbs, 1.0f, st))
+        return FB_ERR_LAUNCH;
+
+    BwdParams p{};
+    p.q = qh; p.k = kh; p.v = v; p.phi_q = rest ? qr : nullptr; p.phi_k = rest ? kr : nullptr;
+    p.out = out; p.lse = lse; p.dout = dout;
+    p.dq = dqh; p.dk = dkh; p.dv = dv; p.dphi_q = rest ? dqr : nullptr; p.dphi_k = rest ? dkr : nullptr;
+    p.workspace = inner;
+    p.B = B; p.H = H; p.N = N; p.M = N; p.R = rest; p.Cg = C; p.causal = causal != 0;
+    p.phi_f32 = 0;
+    p.phi_bstride = (long long)H * N * rest;
+    p.phik_bstride = (long long)H * N * rest;
+    p.scale = 1.0f;                // folded into q'
+    const int rc = fb_launch_bwd_bf16(p, C, rest, st);
+    if (rc != 0) return rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH;
+    if (fb_launch_mulbias_fold(q, phi_q, dqh, dqr, dq, dphi_q, B, (long long)H * N, C, R, f32, pbs, sc, st) ||
+        fb_launch_mulbias_fold(k, phi_k, dkh, dkr, dk, dphi_k, B, (long long)H * N, C, R, f32, pbs, 1.0f, st))
+        return FB_ERR_LAUNCH;
+    return FB_OK;
+}
+
 static size_t bwd_ws_impl(int B, int H, int N, int M, int C, int R) {
     if (B <= 0 || H <= 0 || N <= 0 || M <= 0) return 0;
     // (lse * log2 e, D) per query row and the concatenated operand rows [q*scale | phi_q], [k | phi_k]

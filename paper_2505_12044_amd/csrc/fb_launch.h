@@ -24,6 +24,12 @@ int fb_launch_bwd_dense_bf16(const BwdParams& p, int C, hipStream_t stream);
 int fb_launch_mulbias_prep(const void* x, const void* phi, void* head, void* rest, int B, long long rows_per_batch,
                            int C, int R, int phi_f32, long long phi_bstride, float mul, hipStream_t stream);
 
+// Multiplicative bias backward fold: dx[row][C] = mul * sum_r phi_r g_r, dphi[row][R] = mul * sum_c x_c g_r,c
+// from g_head [rows][C], g_rest [rows][C (R-1)] (gradients of the reweighted repeats); dphi is per batch element.
+int fb_launch_mulbias_fold(const void* x, const void* phi, const void* g_head, const void* g_rest, void* dx,
+                           void* dphi, int B, long long rows_per_batch, int C, int R, int phi_f32,
+                           long long phi_bstride, float mul, hipStream_t stream);
+
 // Extra dynamic LDS bytes added to forward launches (experiments on occupancy; normally 0).
 size_t fb_debug_lds_pad();
 

@@ -9,7 +9,7 @@ import torch
 
 from oracle import fb_oracle as O
 from paper_2505_12044_amd import api, workloads as W
-from tests._gpu_util import TOL, dev, host, max_abs
+from tests._gpu_util import GRAD_TOL, TOL, dev, host, max_abs
 
 pytestmark = pytest.mark.gpu
 
@@ -97,3 +97,59 @@ def test_workspace_reuse_and_argument_errors():
     pq3 = dev(rng.standard_normal((B, H, N, 3)).astype(np.float32), "f32")
     with pytest.raises(api.FlashBiasError):      # C (R - 1) = 128 > 64
         api.fb_lowrank_mulbias_attn_fwd(args[0], args[1], args[2], pq3, pq3)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,C,R,phi_dtype,shared", [(300, 64, 2, "f32", True), (257, 32, 3, "bf16", False),
+                                                    (200, 16, 5, "f32", False), (384, 128, 1, "f32", False),
+                                                    (130, 16, 2, "bf16", True)])
+def test_backward(N, C, R, phi_dtype, shared, causal):
+    """dq, dk, dv, dphi_q, dphi_k against the oracle's chain rule on the definition; 5e-2, scaled
+    with the data where the reference exceeds 2.5 (as for the additive backward)."""
+    B, H = 2, 2
+    q, k, v, rng = _qkv(B, H, N, C, seed=8400 + N + C)
+    dout = W.round_bf16(rng.standard_normal((B, H, N, C)).astype(np.float32))
+    Bp = 1 if shared else B
+    if R == 2 and shared:
+        fq, fk = O.cosine_multiplicative_factors(N)
+        pq = np.broadcast_to(fq.astype(np.float32), (Bp, H, N, 2)).copy()
+        pk = np.broadcast_to(fk.astype(np.float32), (Bp, H, N, 2)).copy()
+    else:
+        sc = R ** -0.5
+        pq = (sc * rng.uniform(-1.0, 1.0, (Bp, H, N, R))).astype(np.float32)
+        pk = (sc * rng.uniform(-1.0, 1.0, (Bp, H, N, R))).astype(np.float32)
+    if phi_dtype == "bf16":
+        pq, pk = W.round_bf16(pq), W.round_bf16(pk)
+    d = [dev(x, "bf16") for x in (q, k, v)] + [dev(pq, phi_dtype), dev(pk, phi_dtype)]
+    out, lse = api.fb_lowrank_mulbias_attn_fwd(*d, causal=causal)
+    grads = api.fb_lowrank_mulbias_attn_bwd(*d, out, lse, dev(dout, "bf16"), causal=causal)
+    torch.cuda.synchronize()
+    worst = 0.0
+    msg = []
+    for b in range(B):
+        for h in range(H):
+            bp = 0 if shared else b
+            ref = O.attention_multiplicative_lowrank_grads(q[b, h], k[b, h], v[b, h], pq[bp, h], pk[bp, h],
+                                                           dout[b, h], causal=causal)
+            for name, g, r in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), grads, ref):
+                gh = host(g[b, h])
+                assert np.isfinite(gh).all(), name
+                err = max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5)
+                if err > worst:
+                    worst = err
+                    msg = [name, b, h, err, float(np.abs(r).max())]
+    print(f"mulbias bwd N{N} C{C} R{R} {phi_dtype} shared={shared} causal={causal}: worst {msg}", flush=True)
+    assert worst <= GRAD_TOL
+
+
+def test_backward_workspace_and_errors():
+    B, H, N, C, R = 1, 1, 64, 64, 2
+    need = api.fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R)
+    assert need == 8 * N * C * R + api.fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, C * (R - 1))
+    q, k, v, rng = _qkv(B, H, N, C, seed=8500)
+    f = dev(rng.uniform(-1, 1, (B, H, N, R)).astype(np.float32), "f32")
+    d = [dev(x, "bf16") for x in (q, k, v)] + [f, f]
+    out, lse = api.fb_lowrank_mulbias_attn_fwd(*d)
+    ws = torch.empty(need - 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(api.FlashBiasError):
+        api.fb_lowrank_mulbias_attn_bwd(*d, out, lse, d[0], workspace=ws)

@@ -122,6 +122,24 @@ def test_mulbias_argument_errors(lib):
     assert call(w=72) == 4
 
 
+def test_mulbias_backward_argument_errors(lib):
+    f = lib.fb_lowrank_mulbias_attn_bwd
+    need = lib.fb_lowrank_mulbias_attn_bwd_workspace_bytes(1, 2, 100, 32, 3, api.FB_BF16)
+    assert need == 4 * 200 * 32 * 3 * 2 + lib.fb_lowrank_attn_bwd_workspace_bytes(1, 2, 100, 32, 64, api.FB_BF16)
+
+    def call(ptrs=None, C=32, R=3, dtype=api.FB_BF16, w=64, wb=need):
+        ptrs = ptrs or [64] * 13
+        return f(*ptrs, 1, 2, 100, C, R, 0, dtype, api.FB_BF16, 0, 0.0, w, wb, None)
+
+    assert call(ptrs=[64] * 12 + [None]) == 1
+    assert call(R=0) == 2
+    assert call(R=4) == 3                      # C (R - 1) = 96 > 64
+    assert call(dtype=api.FB_F32) == 3
+    assert call(ptrs=[64] * 11 + [66, 64]) == 4
+    assert call(wb=need - 1) == 5
+    assert call(w=None) == 5
+
+
 def test_tune_knob(lib):
     assert lib.fb_tune_set(b"fwd_qb", 2) == 0
     assert lib.fb_tune_set(b"fwd_qb", 0) == 0
