@@ -299,50 +299,63 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     const int nIt = b_end - b_begin;
     auto blk_of = [&](int i) __attribute__((always_inline)) { return min(b_begin + i, nblk_all - 1); };
 
-    // ---- this wave's share of a block's direct loads: load d = wave + 4*j, j < my_ndma ----
-    // wave-uniform per load: source array, bytes per block and per row, LDS offset inside a slot;
-    // per lane: source row (a chunk index for the vec rows) and byte offset inside the row
-    unsigned dma_rowoff[NDW], dma_col[NDW];
-    const unsigned char* dma_src[NDW];
-    int dma_bstride[NDW], dma_pitch[NDW], dma_lshift[NDW], dma_dst[NDW];
+    // ---- this wave's share of a block's direct loads: load d = wave + 4*j, j < NDW ----
+    // Every wave issues NDW loads per block so that the vmcnt waits are compile-time constants and
+    // the issue code carries no per-load guards: where ND is not a multiple of four the surplus
+    // slots repeat load ND-1 (same source, same destination, same bytes as the wave that owns it).
+    // wave-uniform per load: running source pointer of the block being issued, bytes per block,
+    // LDS offset inside a slot, row-offset limit for the sequence's last (partial) block;
+    // per lane: byte offset of its source row (a chunk of two rows for the vec rows) and of its
+    // 16 bytes inside the row
+    unsigned dma_rowoff[NDW], dma_col[NDW], dma_taillim[NDW];
+    const unsigned char* dma_ptr[NDW];
+    int dma_bstride[NDW], dma_dst[NDW];
+    const int tail_left = NS - (nblk_all - 1) * BT - 1;      // last valid row of the sequence's last block
+    int dma_blk = blk_of(0);                                 // block the running pointers stand at
 #pragma unroll
     for (int j = 0; j < NDW; j++) {
-        const int d = wave + kWaves * j;
+        const int d = min(wave + kWaves * j, ND - 1);
+        const unsigned char* dma_src_j;
+        int dma_pitch_j, dma_lshift_j;
         int row = 0, chunk = 0, dst = 0;
         if (d < T1::NDMA) {
             T1::dma_map(d, lane, row, chunk, dst);
-            dma_src[j] = (const unsigned char*)t1g;
-            dma_bstride[j] = BT * K::W * 2; dma_pitch[j] = K::W * 2; dma_lshift[j] = 0;
+            dma_src_j = (const unsigned char*)t1g;
+            dma_bstride[j] = BT * K::W * 2; dma_pitch_j = K::W * 2; dma_lshift_j = 0;
             dma_col[j] = (unsigned)chunk * 16u;
             dma_dst[j] = dst;
         } else if (d < T1::NDMA + T2::NDMA) {
             T2::dma_map(d - T1::NDMA, lane, row, chunk, dst);
-            dma_src[j] = (const unsigned char*)t2g;
-            dma_bstride[j] = BT * C * 2; dma_pitch[j] = C * 2; dma_lshift[j] = 0;
+            dma_src_j = (const unsigned char*)t2g;
+            dma_bstride[j] = BT * C * 2; dma_pitch_j = C * 2; dma_lshift_j = 0;
             dma_col[j] = (unsigned)chunk * 16u;
             dma_dst[j] = kOffT2 + dst;
         } else {
             // vec: 32 rows x 8 bytes = 16 chunks of two rows; the other lanes repeat chunk 15
             row = min(lane, 15);
-            dma_src[j] = (const unsigned char*)vecg;
-            dma_bstride[j] = BT * 8; dma_pitch[j] = 16; dma_lshift[j] = 1;
+            dma_src_j = (const unsigned char*)vecg;
+            dma_bstride[j] = BT * 8; dma_pitch_j = 16; dma_lshift_j = 1;
             dma_col[j] = 0u;
             dma_dst[j] = kOffVec;
         }
-        dma_rowoff[j] = (unsigned)(row * dma_pitch[j]);
+        dma_dst[j] = __builtin_amdgcn_readfirstlane(dma_dst[j]);     // wave-uniform by construction: keep it scalar
+        dma_rowoff[j] = (unsigned)(row * dma_pitch_j);
+        dma_taillim[j] = (unsigned)__builtin_amdgcn_readfirstlane((tail_left >> dma_lshift_j) * dma_pitch_j);
+        dma_ptr[j] = dma_src_j + (size_t)dma_blk * dma_bstride[j];
     }
-    const int my_ndma = (ND - wave + kWaves - 1) / kWaves;     // wave-uniform: NDW or NDW - 1
+    // Blocks are issued in ascending order of i (the clamp in blk_of makes the index stall at the
+    // last block), so the source pointers advance by at most one block per call.
     auto issue_block = [&](int i, int slot) __attribute__((always_inline)) {
         const int blk = blk_of(i);
-        const int left = NS - blk * BT - 1;    // last valid row inside the block; rows past it repeat it
+        const bool adv = blk != dma_blk;       // wave-uniform; false once the index is clamped (and on the first call)
+        dma_blk = blk;
+        const bool tail = blk == nblk_all - 1; // rows past the sequence end repeat the last valid row
         const unsigned sbase = lds0 + slot * kSlotBytes;
 #pragma unroll
         for (int j = 0; j < NDW; j++) {
-            if (j < my_ndma) {
-                // rows past the end repeat the last valid row: a minimum on the byte offset (scalar operand)
-                const unsigned voff = min(dma_rowoff[j], (unsigned)((left >> dma_lshift[j]) * dma_pitch[j])) + dma_col[j];
-                dma16(dma_src[j] + (size_t)blk * dma_bstride[j], voff, sbase + dma_dst[j]);
-            }
+            dma_ptr[j] += adv ? dma_bstride[j] : 0;
+            const unsigned voff = min(dma_rowoff[j], tail ? dma_taillim[j] : ~0u) + dma_col[j];
+            dma16(dma_ptr[j], voff, sbase + dma_dst[j]);
         }
     };
     // ---- dense bias tile of this wave: rows = queries, columns = keys, 64-byte rows; lane l of
@@ -390,7 +403,9 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     };
     // all but the newest block's loads (plus `stores` global stores issued since) may remain
     auto wait_prev_loads = [&](int stores) __attribute__((always_inline)) {
-        wait_vmcnt_n(my_ndma + (DENSE ? 2 : 0) + stores);
+        constexpr int NLD = NDW + (DENSE ? 2 : 0);
+        if (stores == 0) wait_vmcnt<NLD>();
+        else wait_vmcnt_n(NLD + stores);
     };
     // per-lane offsets of the bias values of this lane's accumulator registers inside a tile:
     // group g <-> registers 4g..4g+3
