@@ -37,6 +37,9 @@ int pick_qb(int B, int H, int N, int C, int rp, bool dense, bool causal) {
     (void)rp;
     // Long non-causal C = 128 sequences: the eight-wave ping-pong kernel (256-row tiles).
     if (C == 128 && !dense && !causal && N >= 8192) return 8;
+    // Short sequences at C = 32 (a few key blocks per tile, the tile's set-up dominates): the
+    // direct-to-LDS kernel, whose prologue is cheaper; it falls back for shapes it does not take.
+    if (C == 32 && !causal && N <= 384) return 16;
     // Two query blocks per wave halve the LDS traffic per MFMA but double the accumulator
     // registers: they fit the 256-register budget (two waves per SIMD) only for C <= 64, and
     // only pay when 256-row tiles still leave every CU several workgroups.
