@@ -118,32 +118,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     const bf16_t* bg = nullptr;
     if (DENSE) bg = (const bf16_t*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * M;
 
-    // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout).  Rows past N
-    // read row N-1 (finite values) and are never stored.
-    bf16x8 qreg[QB][K::KS];
-#pragma unroll
-    for (int qb = 0; qb < QB; qb++) {
-        const int qi = min(qw0 + qb * 32 + l32, N - 1);
-#pragma unroll
-        for (int ks = 0; ks < K::KS; ks++) {
-            bf16x8 val;
-            if (ks < C / 16) {
-                if (ks * 16 < CG) {
-                    const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qi * CG + ks * 16 + 8 * hf));
-#pragma unroll
-                    for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
-                }
-            } else {
-                const int c8 = (ks - C / 16) * 2 + hf;
-                if (PM == 4) val = phi_chunk_from_pair(c8, -slope * (float)(qi - q0), slope);
-                else val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
-            }
-            qreg[qb][ks] = val;
-        }
-    }
+    bf16x8 qreg[QB][K::KS];     // query operand, filled in the prologue below
 
     f32x16 oacc[QB][C / 32];
     float mref[QB], lsum[QB];
@@ -179,10 +154,23 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 
     // ---- block staging: global -> registers -> LDS.  Rows past M are clamped to row M-1; the
     // keys they stand for are masked to -inf before the softmax, so their values never count.
-    u32x4 kraw[K::KIT], vraw[K::KIT];
-    u32x4 praw[K::PIT > 0 ? K::PIT : 1];
+    struct Stage {                       // one block in flight between global memory and LDS
+        u32x4 kraw[K::KIT], vraw[K::KIT];
+        u32x4 praw[K::PIT > 0 ? K::PIT : 1];
+        float fraw[K::FIT];              // fp32 factors: one (key row, rank) item
+    };
+    auto init_stage = [&](Stage& g) {    // chunks and items a thread never loads stay zero
+#pragma unroll
+        for (int it = 0; it < K::KIT; it++) {
+            g.kraw[it] = u32x4{0u, 0u, 0u, 0u};
+            g.vraw[it] = u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int it = 0; it < K::FIT; it++) g.fraw[it] = 0.f;
+    };
+    Stage st;
+    init_stage(st);
     // fp32 factors: item e = (key row, rank r) of a block, spread evenly over the four waves
-    float fraw[K::FIT];
     int fitem_row[K::FIT], fitem_r[K::FIT];
     bool fitem_ok[K::FIT];
     const float* pkf = (const float*)pkg;
@@ -193,7 +181,6 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             fitem_ok[it] = e < BK * R;
             fitem_row[it] = fitem_ok[it] ? e / R : 0;
             fitem_r[it] = fitem_ok[it] ? e - fitem_row[it] * R : 0;
-            fraw[it] = 0.f;
         }
         // the columns past 6R of every ring slot stay zero for the whole kernel
         for (int e = tid; e < NBUF * BK * (RP / 2); e += kThreads) {
@@ -216,8 +203,6 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         grow[it] = (unsigned)((e / (C / 8)) * CG * 2);
         gcol[it] = (unsigned)((e % (C / 8)) * 16);
         gok[it] = (K::KCH % kThreads == 0 || e < K::KCH) && (CG == C || (e % (C / 8)) * 8 < CG);
-        kraw[it] = u32x4{0u, 0u, 0u, 0u};
-        vraw[it] = u32x4{0u, 0u, 0u, 0u};
     }
     const unsigned char* kgb = (const unsigned char*)kg;
     const unsigned char* vgb = (const unsigned char*)vg;
@@ -233,15 +218,15 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         }
     }
 
-    auto load_block = [&](int t) {
+    auto load_block = [&](int t, Stage& g) {
         const int k0 = blk_of(t) * BK;
         const unsigned boff = (unsigned)k0 * (unsigned)(CG * 2);
 #pragma unroll
         for (int it = 0; it < K::KIT; it++) {
             if ((CG == C && K::KCH % kThreads == 0) || gok[it]) {
                 const unsigned off = min(boff + grow[it], kv_last) + gcol[it];
-                kraw[it] = *(const u32x4*)(kgb + off);
-                vraw[it] = *(const u32x4*)(vgb + off);
+                g.kraw[it] = *(const u32x4*)(kgb + off);
+                g.vraw[it] = *(const u32x4*)(vgb + off);
             }
         }
         const unsigned pboff = (unsigned)k0 * phi_rb;
@@ -249,11 +234,11 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
                 if (fitem_ok[it])
-                    fraw[it] = *(const float*)(pkg + (min(pboff + fitem_off[it], phi_last) + fitem_col[it]));
+                    g.fraw[it] = *(const float*)(pkg + (min(pboff + fitem_off[it], phi_last) + fitem_col[it]));
         } else if (PM == 4) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
-                fraw[it] = fitem_r[it] == 0 ? 1.f : (float)(k0 + fitem_row[it] - q0);
+                g.fraw[it] = fitem_r[it] == 0 ? 1.f : (float)(k0 + fitem_row[it] - q0);
         } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
@@ -264,9 +249,9 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                     const int row = e / (RP / 8), c8 = e % (RP / 8);
                     const unsigned char* src = pkg + min(pboff + __umul24((unsigned)row, phi_rb), phi_last);
                     if (PM == 1) {
-                        praw[it] = (c8 * 8 < R) ? *(const u32x4*)(src + c8 * 16) : u32x4{0u, 0u, 0u, 0u};
+                        g.praw[it] = (c8 * 8 < R) ? *(const u32x4*)(src + c8 * 16) : u32x4{0u, 0u, 0u, 0u};
                     } else {
-                        praw[it] = phi_chunk_raw(src, c8, R, phi_f32, true);
+                        g.praw[it] = phi_chunk_raw(src, c8, R, phi_f32, true);
                     }
                 }
             }
@@ -274,7 +259,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     };
 
     // t is the block whose registers are being stored (the rotation must match load_block)
-    auto store_block = [&](int buf, int t) {
+    auto store_block = [&](int buf, int t, const Stage& g) {
         bf16_t* kdst = kt + buf * K::KBLK;
         bf16_t* vdst = vt + buf * K::VBLK;
 #pragma unroll
@@ -282,21 +267,21 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             const int e = tid + it * kThreads;
             if (K::KCH % kThreads == 0 || e < K::KCH) {
                 const int row = e / (C / 8), c8 = e % (C / 8);
-                *(u32x4*)(kdst + row * K::KP + c8 * 8) = kraw[it];
-                *(u32x4*)(vdst + row * K::VP + c8 * 8) = vraw[it];
+                *(u32x4*)(kdst + row * K::KP + c8 * 8) = g.kraw[it];
+                *(u32x4*)(vdst + row * K::VP + c8 * 8) = g.vraw[it];
             }
         }
         if (ITEMS) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
-                if (fitem_ok[it]) phi_item_store_k(kdst + fitem_row[it] * K::KP + C + 6 * fitem_r[it], fraw[it]);
+                if (fitem_ok[it]) phi_item_store_k(kdst + fitem_row[it] * K::KP + C + 6 * fitem_r[it], g.fraw[it]);
         } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
                 const int e = ((tid + (PM == 2 ? 64 * t : 0)) & (kThreads - 1)) + it * kThreads;
                 if (K::PCH % kThreads == 0 || e < K::PCH) {
                     const int row = e / (RP / 8), c8 = e % (RP / 8);
-                    const u32x4 v = PM == 1 ? praw[it] : as_uint4(phi_chunk_finish<false>(praw[it], c8, phi_f32));
+                    const u32x4 v = PM == 1 ? g.praw[it] : as_uint4(phi_chunk_finish<false>(g.praw[it], c8, phi_f32));
                     *(u32x4*)(kdst + row * K::KP + C + c8 * 8) = v;
                 }
             }
@@ -371,11 +356,42 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     };
 
     // ---- prologue: blocks 0 and 1 into LDS, block 2 in flight, K operands of block 0 ----
-    load_block(0);
-    store_block(0, 0);
-    load_block(1);
-    store_block(1, 1);
-    load_block(2);
+    // Blocks 0 and 1 and the query rows are requested together, so the tile's set-up costs one
+    // global round trip instead of three.
+    {
+        Stage st1;
+        init_stage(st1);
+        load_block(0, st);
+        load_block(1, st1);
+        // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout).  Rows past N
+        // read row N-1 (finite values) and are never stored.
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) {
+            const int qi = min(qw0 + qb * 32 + l32, N - 1);
+#pragma unroll
+            for (int ks = 0; ks < K::KS; ks++) {
+                bf16x8 val;
+                if (ks < C / 16) {
+                    if (ks * 16 < CG) {
+                        const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qi * CG + ks * 16 + 8 * hf));
+#pragma unroll
+                        for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
+                    }
+                } else {
+                    const int c8 = (ks - C / 16) * 2 + hf;
+                    if (PM == 4) val = phi_chunk_from_pair(c8, -slope * (float)(qi - q0), slope);
+                    else val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
+                }
+                qreg[qb][ks] = val;
+            }
+        }
+        store_block(0, 0, st);
+        store_block(1, 1, st1);
+    }
+    load_block(2, st);
     load_bias(0);
     stage_bias();
     load_bias(1);
@@ -435,8 +451,8 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         }
 
         // ---- staging: block t+2 registers -> LDS, block t+3 global -> registers ----
-        store_block(buf2, t + 2);
-        load_block(t + 3);
+        store_block(buf2, t + 2, st);
+        load_block(t + 3, st);
         stage_bias();                   // block t+1 (loaded one iteration ago) -> wave-private LDS
         load_bias(t + 2);
         __builtin_amdgcn_sched_barrier(0);
