@@ -199,7 +199,8 @@ def fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R, dtype_code=FB_BF1
 
 
 def fb_lowrank_mulbias_attn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, causal=False, scale: float = 0.0,
-                                phi_batch_broadcast: Optional[bool] = None, workspace=None, stream=None):
+                                phi_batch_broadcast: Optional[bool] = None, workspace=None, grads=None,
+                                stream=None):
     """dq, dk, dv, dphi_q, dphi_k of the multiplicative-bias attention (dphi_*: [B,H,N,R] in the
     factors' dtype, per batch element)."""
     lib = load_library()
@@ -210,9 +211,12 @@ def fb_lowrank_mulbias_attn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, causal=Fa
     need = fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    dpq = torch.empty((B, H, N, R), dtype=phi_q.dtype, device=q.device)
-    dpk = torch.empty((B, H, N, R), dtype=phi_k.dtype, device=q.device)
+    if grads is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        dpq = torch.empty((B, H, N, R), dtype=phi_q.dtype, device=q.device)
+        dpk = torch.empty((B, H, N, R), dtype=phi_k.dtype, device=q.device)
+    else:
+        dq, dk, dv, dpq, dpk = grads
     st = lib.fb_lowrank_mulbias_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(phi_q), _ptr(phi_k), _ptr(out), _ptr(lse),
                                          _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dpq), _ptr(dpk),
                                          B, H, N, C, R, int(bool(causal)), _dtype_code(q), _dtype_code(phi_q),
