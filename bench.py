@@ -224,6 +224,18 @@ def main() -> int:
                 "TFLOPs": round(flops / (jit_ms * 1e-3) / 1e12, 2),
                 "vs_factor_tensors": round(kern_ms / jit_ms, 3),
             }
+            if "dout" in d:
+                wsj = torch.empty(api.fb_alibi_attn_bwd_workspace_bytes(w.B, w.H, w.N, w.C), dtype=torch.uint8,
+                                  device="cuda")
+                gj = (torch.empty_like(d["q"]), torch.empty_like(d["q"]), torch.empty_like(d["q"]))
+                jit()
+
+                def jit_bwd():
+                    api.fb_alibi_attn_bwd(d["q"], d["k"], d["v"], slopes, d["out"], d["lse"], d["dout"],
+                                          causal=w.causal, workspace=wsj, grads=gj, stream=stream)
+                _, jit_bwd_ms = time_calls(jit_bwd, n, 3)
+                result["alibi_in_kernel"]["bwd_ms"] = round(jit_bwd_ms, 5)
+                del wsj, gj
 
         ws = torch.empty(max(16, api.fb_lowrank_attn_bwd_workspace_bytes(w.B, w.H, w.N, w.C, w.R)),
                          dtype=torch.uint8, device="cuda")

@@ -154,6 +154,21 @@ int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
                                 float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Backward of fb_alibi_attn_fwd: dq, dk, dv [B,H,N,C] for an upstream gradient dout, with the
+ * ALiBi factors generated in the pre-pass from the slopes and the absolute positions (App. D:
+ * the paper's in-kernel variant is timed for training as well as inference).  The slopes are
+ * constants of the model, so no factor or slope gradient is produced.  Positions are exact fp32
+ * integers: N <= 2^24.  Needs dtype = FB_BF16; workspace as for fb_lowrank_attn_bwd with R = 2.
+ */
+size_t fb_alibi_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype);
+
+int fb_alibi_attn_bwd(const void* q, const void* k, const void* v, const float* slopes,
+                      const void* out, const float* lse, const void* dout,
+                      void* dq, void* dk, void* dv,
+                      int B, int H, int N, int C, int causal, fb_dtype dtype, float scale,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Backward of fb_lowrank_mulbias_attn_fwd (chain rule on App. I's reformulation; the appendix
  * itself stops at the forward): dq, dk, dv [B,H,N,C] dtype and dphi_q, dphi_k [B,H,N,R]
  * phi_dtype, always per batch element.  The pre-pass of the forward is repeated, the

@@ -26,6 +26,7 @@ EXPORTS = (
     "fb_dense_bias_attn_bwd_workspace_bytes", "fb_dense_bias_attn_bwd",
     "fb_lowrank_mulbias_attn_fwd_workspace_bytes", "fb_lowrank_mulbias_attn_fwd",
     "fb_lowrank_mulbias_attn_bwd_workspace_bytes", "fb_lowrank_mulbias_attn_bwd",
+    "fb_alibi_attn_bwd_workspace_bytes", "fb_alibi_attn_bwd",
 )
 
 
@@ -79,6 +80,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_lowrank_mulbias_attn_bwd_workspace_bytes.argtypes = [ci] * 5 + [ci]
     lib.fb_lowrank_mulbias_attn_bwd.restype = ci
     lib.fb_lowrank_mulbias_attn_bwd.argtypes = [vp] * 13 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
+    lib.fb_alibi_attn_bwd_workspace_bytes.restype = sz
+    lib.fb_alibi_attn_bwd_workspace_bytes.argtypes = [ci] * 4 + [ci]
+    lib.fb_alibi_attn_bwd.restype = ci
+    lib.fb_alibi_attn_bwd.argtypes = [vp] * 10 + [ci] * 5 + [ci, cf, vp, sz, vp]
     if path is None:
         _lib_handle = lib
     return lib
@@ -163,6 +168,30 @@ def fb_lowrank_xattn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, scale: float
                                   int(bool(phi_batch_broadcast)), float(scale), _stream(stream))
     _check(st, "fb_lowrank_xattn_fwd")
     return out, lse
+
+
+def fb_alibi_attn_bwd_workspace_bytes(B, H, N, C, dtype_code=FB_BF16) -> int:
+    return int(load_library().fb_alibi_attn_bwd_workspace_bytes(B, H, N, C, dtype_code))
+
+
+def fb_alibi_attn_bwd(q, k, v, slopes, out, lse, dout, causal=False, scale: float = 0.0, workspace=None,
+                      grads=None, stream=None):
+    """dq, dk, dv of the attention with the in-kernel ALiBi bias -slopes[h] * (i - j)."""
+    lib = load_library()
+    B, H, N, C = q.shape
+    if slopes.dtype != torch.float32 or slopes.numel() != H:
+        raise FlashBiasError("slopes must be a float32 tensor with one entry per head")
+    need = fb_alibi_attn_bwd_workspace_bytes(B, H, N, C)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    if grads is None:
+        grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+    dq, dk, dv = grads
+    st = lib.fb_alibi_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(slopes), _ptr(out), _ptr(lse), _ptr(dout),
+                               _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, C, int(bool(causal)), _dtype_code(q),
+                               float(scale), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "fb_alibi_attn_bwd")
+    return dq, dk, dv
 
 
 def fb_lowrank_mulbias_attn_fwd_workspace_bytes(B, H, N, C, R, dtype_code=FB_BF16) -> int:

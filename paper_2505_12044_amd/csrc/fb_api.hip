@@ -366,6 +366,40 @@ static int lowrank_bwd_impl(const void* q, const void* k, const void* v,
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
+size_t fb_alibi_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype) {
+    (void)dtype;
+    return bwd_ws_impl(B, H, N, N, C, 2);
+}
+
+int fb_alibi_attn_bwd(const void* q, const void* k, const void* v, const float* slopes,
+                      const void* out, const float* lse, const void* dout,
+                      void* dq, void* dk, void* dv,
+                      int B, int H, int N, int C, int causal, fb_dtype dtype, float scale,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !slopes || !out || !lse || !dout || !dq || !dk || !dv) return FB_ERR_NULL;
+    if (int st = check_common(B, H, N, C, 2)) return st;
+    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (N > (1 << 24)) return FB_ERR_UNSUPPORTED;          // positions are carried as fp32 integers
+    const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
+    for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(slopes) & 3u) != 0) return FB_ERR_ALIGN;
+    if (!workspace || workspace_bytes < bwd_ws_impl(B, H, N, N, C, 2)) return FB_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FB_ERR_ALIGN;
+
+    BwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.phi_q = nullptr; p.phi_k = nullptr; p.slopes = slopes;
+    p.out = out; p.lse = lse; p.dout = dout;
+    p.dq = dq; p.dk = dk; p.dv = dv; p.dphi_q = nullptr; p.dphi_k = nullptr;
+    p.workspace = workspace;
+    p.B = B; p.H = H; p.N = N; p.M = N; p.R = 2; p.Cg = C; p.causal = causal != 0;
+    p.phi_f32 = 1;
+    p.phi_bstride = 0;
+    p.phik_bstride = 0;
+    p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    const int rc = fb_launch_bwd_bf16(p, C, 16, (hipStream_t)stream);
+    return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
+}
+
 size_t fb_dense_bias_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype) {
     (void)dtype;
     return bwd_ws_impl(B, H, N, N, C, 0);

@@ -149,8 +149,17 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __re
         const long long bh = row / len;
         const int i = (int)(row - bh * len);
         const int bb = (int)(bh / p.H), h = (int)(bh - (long long)bb * p.H);
-        const size_t off = ((size_t)bb * (QSIDE ? p.phi_bstride : p.phik_bstride) + ((size_t)h * len + i) * p.R) * esz;
-        a = phi_chunk_switch<QSIDE>((const unsigned char*)(QSIDE ? p.phi_q : p.phi_k) + off, c - C / 8, p.R, f32);
+        if (p.slopes != nullptr) {
+            // ALiBi factors of Example 3.4 from the head's slope and the row's position (App. D)
+            const float m = p.slopes[h];
+            float pair[2];
+            pair[0] = QSIDE ? -m * (float)i : 1.f;
+            pair[1] = QSIDE ? m : (float)i;
+            a = phi_chunk_switch<QSIDE>(pair, c - C / 8, 2, true);
+        } else {
+            const size_t off = ((size_t)bb * (QSIDE ? p.phi_bstride : p.phik_bstride) + ((size_t)h * len + i) * p.R) * esz;
+            a = phi_chunk_switch<QSIDE>((const unsigned char*)(QSIDE ? p.phi_q : p.phi_k) + off, c - C / 8, p.R, f32);
+        }
     }
     *(u32x4*)(dst + row * K::W + c * 8) = as_uint4(a);
 }
@@ -772,7 +781,8 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         const size_t esz = f32 ? 4 : 2;
         float* scratch = (float*)smem + wave * 32 * (K::RP2 + 1);
         unsigned char* dst = nullptr;
-        if (rok) dst = (unsigned char*)(DKV ? p.dphi_k : p.dphi_q) + ((size_t)bh * NL + ri) * R * esz;
+        unsigned char* const dphi = (unsigned char*)(DKV ? p.dphi_k : p.dphi_q);     // NULL: factor gradients not wanted
+        if (rok && dphi != nullptr) dst = dphi + ((size_t)bh * NL + ri) * R * esz;
         // the key-side limb order applies to the key's own gradient and vice versa
         store_dphi<K::RP2, !DKV>(&acc1[K::MBC], scratch, dst, R, f32, l32, hf);
     }

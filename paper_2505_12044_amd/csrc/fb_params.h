@@ -35,6 +35,8 @@ struct BwdParams {
     const void* phi_q; const void* phi_k;
     const void* out; const float* lse; const void* dout;
     void* dq; void* dk; void* dv; void* dphi_q; void* dphi_k;
+    const float* slopes;  // [H] ALiBi slopes: factors phi_q(i) = [-m i, m], phi_k(j) = [1, j] are generated in the
+                          // pre-pass instead of read (phi_q, phi_k, dphi_q, dphi_k NULL, R = 2, phi_f32 = 1); else NULL
     const void* bias;     // [Bb,H,N,M] dense-bias backward only
     void* dbias;          // [B,H,N,M]
     long long bias_bstride;  // elements between batch items of bias (0 when shared)

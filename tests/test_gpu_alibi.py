@@ -83,3 +83,51 @@ def test_alibi_long_sequence_sampled_rows():
             el = max(el, max_abs(host(lse[0, h, r]), rl[0]))
     print(f"alibi in-kernel N{N} sampled rows: out err {eo:.3e}, lse err {el:.3e}", flush=True)
     assert eo <= TOL["bf16"] and el <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("C", [16, 64, 128])
+@pytest.mark.parametrize("N,causal", [(1, True), (200, True), (515, True), (384, False)])
+def test_alibi_backward_small(N, C, causal):
+    """fb_alibi_attn_bwd (factors generated in the pre-pass) against the oracle's gradients on the
+    dense ALiBi bias; 5e-2, scaled with the data where the reference exceeds 2.5."""
+    from tests._gpu_util import GRAD_TOL
+    B, H = 2, 3
+    q, k, v = _inputs(B, H, N, C, seed=4500 + N + C)
+    dout = W.round_bf16(np.random.default_rng(4600 + N).standard_normal((B, H, N, C)).astype(np.float32))
+    slopes = np.array([0.5, 2.0 ** -6, 0.0123], dtype=np.float32)
+    if not causal:
+        slopes = slopes * np.float32(0.05)
+    ts = torch.from_numpy(slopes).cuda()
+    d = [dev(x, "bf16") for x in (q, k, v)]
+    out, lse = api.fb_alibi_attn_fwd(*d, ts, causal=causal)
+    grads = api.fb_alibi_attn_bwd(*d, ts, out, lse, dev(dout, "bf16"), causal=causal)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for b in range(B):
+        for h in range(H):
+            bias = O.alibi_bias(float(slopes[h]), N)
+            ref = O.attention_with_bias_grads(q[b, h], k[b, h], v[b, h], bias, dout[b, h], causal=causal)
+            for name, g, r in zip(("dq", "dk", "dv"), grads, ref):
+                gh = host(g[b, h])
+                assert np.isfinite(gh).all(), name
+                worst = max(worst, max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5))
+    print(f"alibi in-kernel bwd N{N} C{C} causal={causal}: worst scaled err {worst:.3e}", flush=True)
+    assert worst <= GRAD_TOL
+
+
+def test_alibi_backward_matches_factor_tensor_path_at_full_size():
+    """Headline shape: same dq, dk, dv as fb_lowrank_attn_bwd with the explicit fp32 factors (both
+    carry the positions as three bf16 limbs; they differ only in the forward's lse/out they are
+    given and in fp32 rounding of -m i)."""
+    w = W.make_workload("alibi_causal", with_dout=True)
+    slopes = torch.from_numpy(W.alibi_slopes_f32(w.H)).cuda()
+    d = [dev(x, "bf16") for x in (w.q, w.k, w.v)]
+    pq, pk, do = dev(w.phi_q, "f32"), dev(w.phi_k, "f32"), dev(w.dout, "bf16")
+    out, lse = api.fb_lowrank_attn_fwd(*d, pq, pk, causal=True)
+    g1 = api.fb_lowrank_attn_bwd(*d, pq, pk, out, lse, do, causal=True)
+    g2 = api.fb_alibi_attn_bwd(*d, slopes, out, lse, do, causal=True)
+    torch.cuda.synchronize()
+    for name, a, b in zip(("dq", "dk", "dv"), g1, g2):
+        diff = float((a.float() - b.float()).abs().max())
+        print(f"alibi bwd in-kernel vs factor tensors, {name}: max diff {diff:.3e}", flush=True)
+        assert diff <= 2e-2

@@ -140,6 +140,23 @@ def test_mulbias_backward_argument_errors(lib):
     assert call(w=None) == 5
 
 
+def test_alibi_backward_argument_errors(lib):
+    f = lib.fb_alibi_attn_bwd
+    need = lib.fb_alibi_attn_bwd_workspace_bytes(1, 2, 100, 64, api.FB_BF16)
+    assert need == lib.fb_lowrank_attn_bwd_workspace_bytes(1, 2, 100, 64, 2, api.FB_BF16)
+
+    def call(ptrs=None, C=64, dtype=api.FB_BF16, w=64, wb=need, N=100):
+        ptrs = ptrs or [64] * 10
+        return f(*ptrs, 1, 2, N, C, 1, dtype, 0.0, w, wb, None)
+
+    assert call(ptrs=[64, 64, 64, None] + [64] * 6) == 1       # slopes
+    assert call(N=0) == 2
+    assert call(C=48) == 3
+    assert call(dtype=api.FB_F32) == 3
+    assert call(ptrs=[64, 64, 64, 66] + [64] * 6) == 4
+    assert call(wb=need - 1) == 5
+
+
 def test_tune_knob(lib):
     assert lib.fb_tune_set(b"fwd_qb", 2) == 0
     assert lib.fb_tune_set(b"fwd_qb", 0) == 0
