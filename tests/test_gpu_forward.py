@@ -89,6 +89,18 @@ def test_bf16_head_dim_16(N, causal):
     _check_lowrank(W.make_workload("long_train", B=1, H=2, N=N, C=16, R=5, causal=causal))
 
 
+@pytest.mark.parametrize("N", [1, 33, 100, 256, 257, 383, 384])
+def test_bf16_short_c32_automatic_choice(N):
+    """C = 32, N <= 384, non-causal: the automatic choice is the direct-to-LDS kernel where it
+    takes the shape (whole 16-byte factor rows, N % 32 == 0 for a dense bias) and the four-wave
+    kernel otherwise; both must give the oracle's result."""
+    for R, phi_dtype in ((16, "bf16"), (8, "bf16"), (5, "bf16"), (0, "bf16"), (2, "f32")):
+        w = W.make_workload("long_train", dense=True, B=2, H=2, N=N, C=32, R=R, phi_dtype=phi_dtype)
+        _check_lowrank(w)
+        if R == 16:
+            _check_dense(w)
+
+
 @pytest.mark.parametrize("up", [0, 1])
 @pytest.mark.parametrize("N", [100, 640, 1000])
 def test_causal_walk_orders(N, up):
