@@ -191,7 +191,8 @@ int fb_lowrank_mulbias_attn_bwd(const void* q, const void* k, const void* v,
 /*
  * Backward of fb_lowrank_attn_fwd for an upstream gradient dout (loss L = sum(dout * out)):
  * dq, dk, dv [B,H,N,C] dtype; dphi_q, dphi_k [B,H,N,R] phi_dtype, always per batch element
- * (a caller whose factors are shared over the batch sums them over B).  The factor
+ * (a caller whose factors are shared over the batch sums them over B); either may be NULL when
+ * that gradient is not wanted (fixed biases).  The factor
  * gradients are the trailing R columns of the same contractions that give dq and dk
  * (Sec. 3.2 "Speed up training"; Sec. 4.1 "Implementation choices").
  * `out` and `lse` are the forward's results.  Needs dtype = FB_BF16.

@@ -339,14 +339,14 @@ static int lowrank_bwd_impl(const void* q, const void* k, const void* v,
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return FB_ERR_NULL;
     if (int st = check_common(B, H, N > M ? N : M, C, R)) return st;
     if (N <= 0 || M <= 0) return FB_ERR_SHAPE;
-    if (R > 0 && (!phi_q || !phi_k || !dphi_q || !dphi_k)) return FB_ERR_NULL;
+    if (R > 0 && (!phi_q || !phi_k)) return FB_ERR_NULL;       // dphi_q / dphi_k may be NULL: not wanted
     if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (N != M && causal) return FB_ERR_UNSUPPORTED;
     const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
     for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
     if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k) || !aligned16(dphi_q) || !aligned16(dphi_k)))
-        return FB_ERR_ALIGN;
+        return FB_ERR_ALIGN;                                    // a NULL gradient pointer counts as aligned
     const int rp = padded_rank(R, dtype, phi_dtype);
     if (rp > 64) return FB_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < bwd_ws_impl(B, H, N, M, C, R)) return FB_ERR_WORKSPACE;

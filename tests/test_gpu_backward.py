@@ -104,3 +104,18 @@ def test_bwd_constant_key_column_has_zero_query_gradient():
     w.phi_k[..., 0] = 1.0
     _, _, grads = _run_bwd(w)
     assert float(host(grads[3])[..., 0].__abs__().max()) <= GRAD_TOL
+
+
+def test_bwd_without_factor_gradients():
+    """NULL dphi_q / dphi_k (fixed bias): dq, dk, dv are bit-identical to the full call and nothing
+    else is written."""
+    w = W.make_workload("long_train", with_dout=True, B=1, H=2, N=300, R=8)
+    d = workload_to_device(w)
+    out, lse = api.fb_lowrank_attn_fwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"])
+    full = api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out, lse, d["dout"])
+    g = (torch.empty_like(d["q"]), torch.empty_like(d["q"]), torch.empty_like(d["q"]), None, None)
+    part = api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out, lse, d["dout"], grads=g)
+    torch.cuda.synchronize()
+    assert part[3] is None and part[4] is None
+    for a, b in zip(full[:3], part[:3]):
+        assert torch.equal(a, b)
