@@ -811,16 +811,6 @@ __global__ __launch_bounds__(kThreads, (DKV || DENSE || (C == 128 && RP > 32)) ?
     }
 }
 
-template <typename KernT>
-bool set_lds(KernT kern, size_t bytes, bool* done) {
-    if (*done) return true;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) !=
-        hipSuccess)
-        return false;
-    *done = true;
-    return true;
-}
-
 template <int C, int RP, bool CAUSAL>
 int launch(const BwdParams& pin, hipStream_t stream) {
     using K = Cfg<C, RP>;
@@ -830,8 +820,9 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     constexpr size_t lds_dkv = ring_dkv > K::kEpiLds ? ring_dkv : K::kEpiLds;
     auto kdq = bwd_main_kernel<C, RP, CAUSAL, false>;
     auto kdkv = bwd_main_kernel<C, RP, CAUSAL, true>;
-    static bool done_dq = false, done_dkv = false;
-    if (!set_lds(kdq, lds_dq, &done_dq) || !set_lds(kdkv, lds_dkv, &done_dkv)) return 1;
+    static FbLdsOnce once_dq, once_dkv;
+    if (!fb_raise_lds_limit((const void*)kdq, lds_dq, once_dq) || !fb_raise_lds_limit((const void*)kdkv, lds_dkv, once_dkv))
+        return 1;
 
     const long long rows = (long long)pin.B * pin.H * pin.N;      // query rows
     const long long rowsk = (long long)pin.B * pin.H * pin.M;     // key rows
@@ -901,8 +892,9 @@ int launch_dense(const BwdParams& pin, hipStream_t stream) {
     constexpr size_t lds_dkv = (size_t)NSLOT_DKV * (slot + K::kVecBytes);
     auto kdq = bwd_main_kernel<C, 0, CAUSAL, false, true>;
     auto kdkv = bwd_main_kernel<C, 0, CAUSAL, true, true>;
-    static bool done_dq = false, done_dkv = false;
-    if (!set_lds(kdq, lds_dq, &done_dq) || !set_lds(kdkv, lds_dkv, &done_dkv)) return 1;
+    static FbLdsOnce once_dq, once_dkv;
+    if (!fb_raise_lds_limit((const void*)kdq, lds_dq, once_dq) || !fb_raise_lds_limit((const void*)kdkv, lds_dkv, once_dkv))
+        return 1;
 
     const long long rows = (long long)pin.B * pin.H * pin.N;
     const long long rowsk = (long long)pin.B * pin.H * pin.M;

@@ -464,13 +464,8 @@ template <int C, int RP, int PM, bool CAUSAL, bool DENSE>
 int launch(const FwdParams& pin, hipStream_t stream) {
     using K = Cfg<C, RP>;
     auto kern = fwd_bf16_il_kernel<C, RP, PM, CAUSAL, DENSE>;
-    static bool attr_done = false;   // benign race: the call is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)K::kLds) != hipSuccess)
-            return 1;
-        attr_done = true;
-    }
+    static FbLdsOnce once;
+    if (!fb_raise_lds_limit((const void*)kern, K::kLds, once)) return 1;
     FwdParams p = pin;
     p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
     p.total_tiles = p.B * p.H * p.n_qtiles;

@@ -616,13 +616,8 @@ template <int C, int RP, int QB, int PM, bool CAUSAL, bool DENSE, int CG = C>
 int launch(const FwdParams& pin, hipStream_t stream) {
     using K = Cfg<C, RP, QB>;
     auto kern = fwd_bf16_kernel<C, RP, QB, PM, CAUSAL, DENSE, CG>;
-    static bool attr_done = false;   // benign race: the call is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(K::kLds + (DENSE ? K::kBiasLds : 0) + 64 * 1024)) != hipSuccess)
-            return 1;
-        attr_done = true;
-    }
+    static FbLdsOnce once;
+    if (!fb_raise_lds_limit((const void*)kern, K::kLds + (DENSE ? K::kBiasLds : 0) + 64 * 1024, once)) return 1;
     FwdParams p = pin;
     p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
     p.n_units = CAUSAL ? (p.n_qtiles + 1) / 2 : p.n_qtiles;

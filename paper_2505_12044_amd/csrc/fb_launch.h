@@ -30,6 +30,20 @@ int fb_launch_mulbias_fold(const void* x, const void* phi, const void* g_head, c
                            void* dphi, int B, long long rows_per_batch, int C, int R, int phi_f32,
                            long long phi_bstride, float mul, hipStream_t stream);
 
+// A kernel's dynamic-LDS limit is an attribute of the (kernel, device) pair: raise it on the
+// first launch on each device.  Racing first launches all set the same value.
+constexpr int kFbMaxDevices = 64;
+struct FbLdsOnce { bool done[kFbMaxDevices] = {}; };
+inline bool fb_raise_lds_limit(const void* kern, size_t bytes, FbLdsOnce& once) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const bool tracked = dev >= 0 && dev < kFbMaxDevices;
+    if (tracked && once.done[dev]) return true;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return false;
+    if (tracked) once.done[dev] = true;
+    return true;
+}
+
 // Extra dynamic LDS bytes added to forward launches (experiments on occupancy; normally 0).
 size_t fb_debug_lds_pad();
 
