@@ -348,11 +348,14 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     const int i16 = lane & 15, blk = l32 >> 4;
     const int vlane_off = (4 * hf + (i16 >> 2)) * K::VP + 16 * blk + 4 * (i16 & 3);
 
+    // k-steps over channels the caller's rows do not have (CG < C) are all zero on both sides
+    auto kstep_live = [](int ks) constexpr { return !(ks < C / 16 && ks * 16 >= CG); };
     bf16x8 ka[K::KS];
     auto read_k = [&](int buf) {
         const bf16_t* krow = kt + buf * K::KBLK + krow_off;
 #pragma unroll
-        for (int ks = 0; ks < K::KS; ks++) ka[ks] = as_bf16x8(*(const u32x4*)(krow + ks * 16));
+        for (int ks = 0; ks < K::KS; ks++)
+            if (kstep_live(ks)) ka[ks] = as_bf16x8(*(const u32x4*)(krow + ks * 16));
     };
 
     // ---- prologue: blocks 0 and 1 into LDS, block 2 in flight, K operands of block 0 ----
@@ -437,7 +440,8 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             for (int ks = 0; ks < K::KS; ks++) {
                 if (!skip) {
 #pragma unroll
-                    for (int qb = 0; qb < QB; qb++) s[qb] = mfma32(ka[ks], qreg[qb][ks], s[qb]);
+                    for (int qb = 0; qb < QB; qb++)
+                        if (kstep_live(ks)) s[qb] = mfma32(ka[ks], qreg[qb][ks], s[qb]);
                 }
                 // distribute the NV reads over the KS steps
 #pragma unroll
@@ -529,7 +533,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 }
 #pragma unroll
                 for (int ks = (i * K::KS) / NM; ks < ((i + 1) * K::KS) / NM; ks++)
-                    ka[ks] = as_bf16x8(*(const u32x4*)(krow + ks * 16));
+                    if (kstep_live(ks)) ka[ks] = as_bf16x8(*(const u32x4*)(krow + ks * 16));
                 __builtin_amdgcn_sched_barrier(0);
             }
             __builtin_amdgcn_s_setprio(0);
