@@ -45,8 +45,11 @@ int pick_qb(int B, int H, int N, int C, int rp, bool dense, bool causal) {
     // only pay when 256-row tiles still leave every CU several workgroups.
     if (C == 128 || dense) return 1;
     if (N % 256 != 0 && N < 1024) return 1;
+    // (measured: from four full rounds of 512 resident workgroups on; for full attention over
+    // long sequences from two)
     const long long tiles256 = (long long)B * H * ((N + 255) / 256);
-    return tiles256 >= 2048 ? 2 : 1;
+    if (tiles256 >= 2048) return 2;
+    return (!causal && N >= 2048 && tiles256 >= 1000) ? 2 : 1;
 }
 
 }  // namespace
