@@ -518,6 +518,14 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         return tr_read(tb, kOffT2, T2::NP64, (n - NA - NO1) >> 1, (n - NA - NO1) & 1);
     };
 
+    // Head dimension 16 on the 32-channel operand rows: channels 16..31 are zero on both sides, so the
+    // second k-step of the S chain and of the dP chain contribute nothing (the operand is still read,
+    // which keeps the rolling window's positions).
+    const bool narrow = C == 32 && p.Cg == 16;          // wave-uniform
+    auto dead_step = [&](int n) __attribute__((always_inline)) {
+        return C == 32 && narrow && (n == 1 || n == K::KS + 1);
+    };
+
     // P and dS of one accumulator element r (streamed row sb0 + 8*(r/4) + 4*hf + (r%4), lane row ri)
     auto elem = [&](int r, const f32x16& s, const f32x16& dp, float lvx, float dvx, bool need_mask, int sb0,
                     bf16x8 (&pb)[2], bf16x8 (&dsb)[2]) __attribute__((always_inline)) {
@@ -559,6 +567,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
             for (int n = 0; n < NA; n++) {
                 const bf16x8 o = read_op(r0, t0, n);
+                if (dead_step(n)) continue;
                 if (n < K::KS) sA = mfma32(o, l1reg[n], sA);
                 else dA = mfma32(o, l2reg[n - K::KS], dA);
             }
@@ -598,8 +607,10 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
             for (int n = 0; n < NA; n++) {
                 opr[(n + LA) % (LA + 1)] = read_op(rb1, tb0, n + LA);   // past NA: output operands of block i
-                if (n < K::KS) sn = mfma32(opr[n % (LA + 1)], l1reg[n], n == 0 ? sinit : sn);
-                else dn = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], n == K::KS ? zero : dn);
+                if (!dead_step(n)) {
+                    if (n < K::KS) sn = mfma32(opr[n % (LA + 1)], l1reg[n], n == 0 ? sinit : sn);
+                    else dn = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], n == K::KS ? zero : dn);
+                }
 #pragma unroll
                 for (int e = (n * 16) / NA; e < ((n + 1) * 16) / NA; e++)
                     elem(e, sc, dc, vq[e >> 2][e & 3], vd[e >> 2][e & 3], false, sb0, pb, dsb);
@@ -675,6 +686,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
             for (int n = 0; n < NA; n++) {
                 opr[(n + LA) % (LA + 1)] = read_op(rb0, tb0, n + LA);   // n + LA < NOPS: the output operands follow
+                if (dead_step(n)) continue;
                 if (n < K::KS) s = mfma32(opr[n % (LA + 1)], l1reg[n], s);
                 else dp = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], dp);
             }
