@@ -341,6 +341,17 @@ def main() -> int:
             "dense_bias_bytes_avoided": int(wp.H * wp.N * wp.N * 2)}
         del ws, d
         torch.cuda.empty_cache()
+        # the same bias as five merged columns (|x|^2 + |y|^2 - 2 x.y): padded factor width 32 instead of 64
+        wp5 = W.make_pde_workload(rank5=True)
+        d = to_device(wp5)
+        ws = torch.empty(api.fb_lowrank_attn_bwd_workspace_bytes(wp5.B, wp5.H, wp5.N, wp5.C, wp5.R),
+                         dtype=torch.uint8, device="cuda")
+        _, ms_f5 = time_calls(f3, 10, 2)
+        _, ms_b5 = time_calls(b3, 5, 1)
+        others["pde_distance"]["rank5_fwd_ms"] = round(ms_f5, 4)
+        others["pde_distance"]["rank5_bwd_ms"] = round(ms_b5, 4)
+        del ws, d
+        torch.cuda.empty_cache()
 
         # multiplicative bias cos(i - j) as rank-2 factors (App. I): pre-pass + forward on 2C channels
         Bm, Hm, Nm, Cm = 4, 16, 4096, 64

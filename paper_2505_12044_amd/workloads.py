@@ -26,7 +26,7 @@ import numpy as np
 
 __all__ = ["Workload", "make_workload", "CONFIG_NAMES", "round_bf16", "f32_to_bf16_bits",
            "bf16_bits_to_f32", "alibi_factors", "swin_table_bias", "pair_bias", "distance_factors",
-           "make_pde_workload"]
+           "distance_factors_rank5", "make_pde_workload"]
 
 CONFIG_NAMES = ("tiny_fp32", "alibi_causal", "vision_relpos", "pairformer", "long_train")
 
@@ -96,6 +96,22 @@ def distance_factors(x: np.ndarray, alpha: np.ndarray, strength: float):
     w = -float(strength) * np.asarray(alpha, dtype=np.float64)          # [H, n]
     phi_q = (w[:, :, None] * uq[None]).astype(np.float32)[None]
     phi_k = np.broadcast_to(uk.astype(np.float32), (1, w.shape[0], n, 9)).copy()
+    return phi_q, phi_k
+
+
+def distance_factors_rank5(x: np.ndarray, alpha: np.ndarray, strength: float):
+    """The same bias as distance_factors with the per-axis constants merged:
+    ||x - y||^2 = |x|^2 + |y|^2 - 2 x.y, i.e. [|x|^2, 1, -2 x_0, -2 x_1, -2 x_2] against
+    [1, |y|^2, y_0, y_1, y_2] (rank 5 instead of the nine printed columns of Example 3.5).
+    Returns float32 [1,H,n,5] each."""
+    x = np.asarray(x, dtype=np.float64)
+    n = x.shape[0]
+    n2 = np.sum(x * x, axis=1)
+    uq = np.concatenate([n2[:, None], np.ones((n, 1)), -2.0 * x], axis=1)
+    uk = np.concatenate([np.ones((n, 1)), n2[:, None], x], axis=1)
+    w = -float(strength) * np.asarray(alpha, dtype=np.float64)
+    phi_q = (w[:, :, None] * uq[None]).astype(np.float32)[None]
+    phi_k = np.broadcast_to(uk.astype(np.float32), (1, w.shape[0], n, 5)).copy()
     return phi_q, phi_k
 
 
@@ -273,18 +289,18 @@ def make_workload(name: str, dense: bool = False, with_dout: Optional[bool] = No
 
 
 def make_pde_workload(B: int = 1, H: int = 8, N: int = 32186, C: int = 16, strength: float = 4.0,
-                      seed: int = 1006) -> Workload:
+                      seed: int = 1006, rank5: bool = False) -> Workload:
     """The shape of the paper's PDE-solver attention (Sec. 4.3): N = 32186 mesh points, 8 heads
     of 16 channels, bias -s alpha_i ||x_i - x_j||^2 as rank-9 fp32 factors shared over the
     batch.  Points are uniform in the unit cube, alpha ~ U(0.5, 1.5) per head and point;
     q, k, v, dout ~ N(0,1) rounded to bf16.  A stand-in for the mesh of the paper's dataset,
-    which is not reproduced."""
+    which is not reproduced.  rank5 supplies the same bias as five merged columns."""
     rng = np.random.default_rng(seed)
     q, k, v = (_store(rng.standard_normal((B, H, N, C)), "bf16") for _ in range(3))
     x = rng.random((N, 3))
     alpha = 0.5 + rng.random((H, N))
-    phi_q, phi_k = distance_factors(x, alpha, strength)
+    phi_q, phi_k = (distance_factors_rank5 if rank5 else distance_factors)(x, alpha, strength)
     dout = _store(rng.standard_normal((B, H, N, C)), "bf16")
-    return Workload(name="pde_distance", B=B, H=H, N=N, C=C, R=9, causal=False, dtype="bf16",
+    return Workload(name="pde_distance", B=B, H=H, N=N, C=C, R=phi_q.shape[-1], causal=False, dtype="bf16",
                     phi_dtype="f32", q=q, k=k, v=v, phi_q=phi_q, phi_k=phi_k, dout=dout,
                     notes={"x": x, "alpha": alpha, "strength": strength})

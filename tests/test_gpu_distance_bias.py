@@ -57,3 +57,21 @@ def test_distance_bias_forward_and_alpha_gradient(N, C):
     print(f"distance bias N{N} C{C}: out {eo:.3e} lse {el:.3e} dq/dk/dv {eg:.3e} dalpha (rel) {ea:.3e}", flush=True)
     assert eo <= TOL["bf16"] and el <= TOL["bf16"]
     assert eg <= GRAD_TOL and ea <= GRAD_TOL
+
+
+def test_distance_bias_rank5_factors():
+    """The merged rank-5 form of the same bias (|x|^2 + |y|^2 - 2 x.y): 30 limb columns, padded
+    width 32 instead of 64.  Forward and gradients against the oracle on the dense bias."""
+    w = W.make_pde_workload(N=1100, H=2, rank5=True)
+    x, alpha, s = w.notes["x"], w.notes["alpha"], w.notes["strength"]
+    d = [dev(a, "bf16") for a in (w.q, w.k, w.v)] + [dev(w.phi_q, "f32"), dev(w.phi_k, "f32")]
+    out, lse = api.fb_lowrank_attn_fwd(*d)
+    grads = api.fb_lowrank_attn_bwd(*d, out, lse, dev(w.dout, "bf16"))
+    torch.cuda.synchronize()
+    for h in range(2):
+        bias = -s * alpha[h][:, None] * O.squared_distance_bias(x, x)
+        ro, rl = O.attention_with_bias(w.q[0, h], w.k[0, h], w.v[0, h], bias)
+        assert max_abs(host(out[0, h]), ro) <= TOL["bf16"] and max_abs(host(lse[0, h]), rl) <= TOL["bf16"]
+        rdq, rdk, rdv, _ = O.attention_with_bias_grads(w.q[0, h], w.k[0, h], w.v[0, h], bias, w.dout[0, h])
+        for g, r in ((grads[0], rdq), (grads[1], rdk), (grads[2], rdv)):
+            assert max_abs(host(g[0, h]), r) / max(1.0, float(np.abs(r).max()) / 2.5) <= GRAD_TOL

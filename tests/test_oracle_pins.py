@@ -427,6 +427,12 @@ def test_pde_workload_factors_equal_dense_definition():
         ref = -s * alpha[h][:, None] * O.squared_distance_bias(x, x)
         got = O.lowrank_bias(w.phi_q[0, h], w.phi_k[0, h])
         assert np.max(np.abs(got - ref)) < 5e-6      # fp32 storage of factors of magnitude <= 12
+    w5 = W.make_pde_workload(N=300, H=2, rank5=True)
+    assert w5.R == 5 and w5.phi_k.shape == (1, 2, 300, 5)
+    np.testing.assert_array_equal(w5.q, w.q)
+    for h in range(2):
+        ref = -s * alpha[h][:, None] * O.squared_distance_bias(x, x)
+        assert np.max(np.abs(O.lowrank_bias(w5.phi_q[0, h], w5.phi_k[0, h]) - ref)) < 1e-5
 
 
 def test_bf16_rounding_helper():
