@@ -37,7 +37,8 @@
  *     enqueue work: they never synchronise and never block on the device.
  *   - Return value: FB_OK or an fb_status for errors detectable on the host (bad argument,
  *     unsupported shape, misalignment, workspace too small, launch failure).  Outputs are
- *     fully overwritten on success and untouched on error.  No global state; thread-safe.
+ *     fully overwritten on success and untouched on error.  Thread-safe; the only process-wide
+ *     state is the set of fb_tune_set knobs.
  */
 #ifndef FLASHBIAS_H_
 #define FLASHBIAS_H_
