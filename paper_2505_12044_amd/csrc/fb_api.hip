@@ -27,6 +27,7 @@ int padded_rank(int R, fb_dtype dtype, fb_dtype phi_dtype) {
 int check_common(int B, int H, int N, int C, int R) {
     if (B <= 0 || H <= 0 || N <= 0 || R < 0) return FB_ERR_SHAPE;
     if ((long long)B * H * N * (long long)(C > R ? C : R) >= (1LL << 31)) return FB_ERR_SHAPE;
+    if ((long long)N * R * 4 >= (1LL << 32)) return FB_ERR_SHAPE;     // 32-bit byte offsets inside a head's factor rows
     if (C != 16 && C != 32 && C != 64 && C != 128) return FB_ERR_UNSUPPORTED;
     return FB_OK;
 }
