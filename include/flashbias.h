@@ -73,7 +73,6 @@ const char* fb_status_string(int status);
  * FB_ERR_UNSUPPORTED (unknown name).  Not synchronised with concurrent calls.
  *   "fwd_qb"      bf16 forward kernel variant; 0 restores the automatic choice.
  *                 1, 2 = four-wave kernel with that many 32-row query blocks per wave
- *                 4    = in-wave interleaved kernel (falls back to 1 for padded rank > 32)
  *                 8    = eight-wave ping-pong kernel
  *                 16   = direct-to-LDS kernel (falls back to 1 for shapes it does not take)
  *   "fwd_causal_up" 1 (default): of the two query tiles a workgroup of the causal four-wave

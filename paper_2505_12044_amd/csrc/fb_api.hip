@@ -34,7 +34,7 @@ int check_common(int B, int H, int N, int C, int R) {
 
 int pick_qb(int B, int H, int N, int C, int rp, bool dense, bool causal) {
     const int forced = g_fwd_qb.load(std::memory_order_relaxed);
-    if (forced == 1 || forced == 2 || forced == 4 || forced == 8 || forced == 16) return forced;
+    if (forced == 1 || forced == 2 || forced == 8 || forced == 16) return forced;
     (void)rp;
     // Long non-causal C = 128 sequences: the eight-wave ping-pong kernel (256-row tiles).
     if (C == 128 && !dense && !causal && N >= 8192) return 8;
@@ -77,7 +77,7 @@ const char* fb_status_string(int status) {
 int fb_tune_set(const char* name, int value) {
     if (name == nullptr) return FB_ERR_NULL;
     if (std::strcmp(name, "fwd_qb") == 0) {
-        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return FB_ERR_SHAPE;
+        if (value != 0 && value != 1 && value != 2 && value != 8 && value != 16) return FB_ERR_SHAPE;
         g_fwd_qb.store(value, std::memory_order_relaxed);
         return FB_OK;
     }

@@ -1,12 +1,19 @@
-// bf16 MFMA forward, direct-to-LDS variant of the in-wave interleaved kernel.
+// bf16 MFMA forward, direct-to-LDS variant with the matrix / vector overlap written into one
+// wave's instruction stream.
 //
-// Same schedule as fb_fwd_bf16_il.h (one workgroup = 4 waves = 128 query rows, one 32-row query
-// block per wave; region 1: S_{t+1} chain interleaved with the exponentiation of block t;
-// region 2: O chain interleaved with the row maxima of S_{t+1}), but nothing on the key side
-// passes through registers on its way from HBM: every wave issues 128-bit global loads that
-// write LDS directly (global_load_lds_dwordx4), several blocks ahead.  Measured on the
-// register-staged kernel, the LDS stores cost ~14 % and waiting for global loads issued only
-// one block ahead another ~14 % of the run time; both disappear here.
+// One workgroup = 4 waves = 128 query rows, one 32-row query block per wave.  Each iteration
+// has two regions, every MFMA followed by its share of the vector / LDS work and a scheduling
+// barrier, so the order in the source is the order executed:
+//   region 1 :  S_{t+1} = K_{t+1} . Q   (MFMA chain)  interleaved with exp / sum / convert of
+//               block t (P_t) and the V_t transpose reads
+//   region 2 :  O += V_t P_t            (MFMA chain)  interleaved with the row maxima of
+//               S_{t+1} and the K_{t+2} operand reads
+//   barrier
+// Orientation, operand layouts, factor handling, masking and the lazy rescale are those of the
+// four-wave kernel in fb_fwd_bf16_impl.h.  Nothing on the key side passes through registers on
+// its way from HBM: every wave issues 128-bit global loads that write LDS directly
+// (global_load_lds_dwordx4), several blocks ahead, so there are neither staging registers nor
+// LDS stores, and a tile's set-up is short.
 //
 // The direct loads are issued from inline assembly.  The compiler therefore does not know
 // that LDS is written asynchronously (with the builtin it makes every later LDS transpose read

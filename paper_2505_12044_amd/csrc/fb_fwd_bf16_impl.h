@@ -35,7 +35,6 @@
 
 #include "fb_device.h"
 #include "fb_fwd_bf16_dma.h"
-#include "fb_fwd_bf16_il.h"
 #include "fb_fwd_bf16_pp.h"
 #include "fb_launch.h"
 #include "fb_params.h"
@@ -653,8 +652,8 @@ int dispatch_pm(const FwdParams& p, int qb, hipStream_t stream) {
 }
 
 // rp: padded factor width (multiple of 16, <= 64); qb: 32-row query blocks per wave of the
-// four-wave kernel (1 or 2; 2 exists for C <= 64 only and falls back to 1 otherwise), or 8 for
-// the eight-wave ping-pong kernel.
+// four-wave kernel (1 or 2; 2 exists for C <= 64 only and falls back to 1 otherwise), 8 for the
+// eight-wave ping-pong kernel, 16 for the direct-to-LDS kernel.
 // Returns 0 on success, 1 on launch failure, -1 when no instantiation fits.
 template <int C>
 int fwd_bf16_dispatch(const FwdParams& p, int rp, bool dense, int qb, hipStream_t stream) {
@@ -663,10 +662,6 @@ int fwd_bf16_dispatch(const FwdParams& p, int rp, bool dense, int qb, hipStream_
         const int rc = fbdma::dispatch<C>(p, rp, dense, stream);
         if (rc >= 0) return rc;
         qb = 1;   // shapes the direct-to-LDS kernel does not take
-    }
-    if (qb == 4) {
-        if (rp <= 32) return fbil::dispatch<C>(p, rp, dense, stream);
-        qb = 1;
     }
     if (dense) return dispatch_qb<C, 0, 0, true>(p, qb, stream);
     switch (rp) {

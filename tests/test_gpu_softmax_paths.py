@@ -52,7 +52,7 @@ def test_reference_replacement_paths(kind, causal):
         bias = O.lowrank_bias(pq[0, h], pk[0, h])
         ref.append(O.attention_with_bias(q[0, h], k[0, h], v[0, h], bias, causal=causal))
     worst = 0.0
-    for qb in (1, 2, 4, 8, 16):
+    for qb in (1, 2, 8, 16):
         api.fb_tune_set("fwd_qb", qb)
         try:
             out, lse = api.fb_lowrank_attn_fwd(*d, causal=causal)

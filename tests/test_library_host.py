@@ -161,6 +161,7 @@ def test_tune_knob(lib):
     assert lib.fb_tune_set(b"fwd_qb", 2) == 0
     assert lib.fb_tune_set(b"fwd_qb", 0) == 0
     assert lib.fb_tune_set(b"fwd_qb", 3) == 2
+    assert lib.fb_tune_set(b"fwd_qb", 4) == 2
     assert lib.fb_tune_set(b"fwd_qb", 8) == 0
     assert lib.fb_tune_set(b"fwd_qb", 0) == 0
     assert lib.fb_tune_set(b"fwd_causal_up", 0) == 0
