@@ -72,3 +72,77 @@ def test_backward_random_shape(B, H, N, C, R, phi_dtype, causal, shared, seed):
         assert np.isfinite(gh).all(), name
         err = max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5)
         assert err <= GRAD_TOL, (name, err)
+
+
+def _xcases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        C = int(rng.choice([16, 32, 64, 128]))
+        f32 = bool(rng.integers(0, 2))
+        R = int(rng.integers(0, 11)) if f32 else int(rng.integers(0, 65))
+        N, M = int(rng.integers(1, 500)), int(rng.integers(1, 900))
+        out.append((int(rng.integers(1, 3)), int(rng.integers(1, 3)), N, M, C, R, "f32" if f32 else "bf16",
+                    int(rng.integers(1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("B,H,N,M,C,R,phi_dtype,seed", _xcases(16, 779))
+def test_xattn_random_shape(B, H, N, M, C, R, phi_dtype, seed):
+    print(f"xattn B{B} H{H} N{N} M{M} C{C} R{R} {phi_dtype}", flush=True)
+    rng = np.random.default_rng(seed)
+    rd = lambda *s: W.round_bf16(rng.standard_normal(s).astype(np.float32))
+    q, dout, k, v = rd(B, H, N, C), rd(B, H, N, C), rd(B, H, M, C), rd(B, H, M, C)
+    pq = pk = None
+    if R:
+        pq = (R ** -0.25 * rng.standard_normal((B, H, N, R))).astype(np.float32)
+        pk = (R ** -0.25 * rng.standard_normal((B, H, M, R))).astype(np.float32)
+        if phi_dtype == "bf16":
+            pq, pk = W.round_bf16(pq), W.round_bf16(pk)
+    d = [dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), dev(pq, phi_dtype), dev(pk, phi_dtype)]
+    out, lse = api.fb_lowrank_xattn_fwd(*d)
+    grads = api.fb_lowrank_xattn_bwd(*d, out, lse, dev(dout, "bf16"))
+    torch.cuda.synchronize()
+    for b in range(B):
+        for h in range(H):
+            fq = pq[b, h] if R else np.zeros((N, 0))
+            fk = pk[b, h] if R else np.zeros((M, 0))
+            ro, rl = O.attention_lowrank(q[b, h], k[b, h], v[b, h], fq, fk)
+            assert max_abs(host(out[b, h]), ro) <= TOL["bf16"] and max_abs(host(lse[b, h]), rl) <= TOL["bf16"]
+            ref = O.attention_lowrank_grads(q[b, h], k[b, h], v[b, h], fq, fk, dout[b, h])
+            for name, g, r in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), grads, ref):
+                if g is None:
+                    continue
+                err = max_abs(host(g[b, h]), r) / max(1.0, float(np.abs(r).max()) / 2.5)
+                assert err <= GRAD_TOL, (name, err)
+
+
+def _dcases(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, 3)), int(rng.integers(1, 3)), 8 * int(rng.integers(1, 70)),
+             int(rng.choice([32, 64, 128])), bool(rng.integers(0, 2)), bool(rng.integers(0, 2)),
+             int(rng.integers(1 << 30))) for _ in range(n)]
+
+
+@pytest.mark.parametrize("B,H,N,C,causal,shared,seed", _dcases(12, 780))
+def test_dense_random_shape(B, H, N, C, causal, shared, seed):
+    print(f"dense B{B} H{H} N{N} C{C} causal={causal} shared={shared}", flush=True)
+    rng = np.random.default_rng(seed)
+    rd = lambda *s: W.round_bf16(rng.standard_normal(s).astype(np.float32))
+    q, k, v, dout = rd(B, H, N, C), rd(B, H, N, C), rd(B, H, N, C), rd(B, H, N, C)
+    bias = rd(1 if shared else B, H, N, N)
+    d = [dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), dev(bias, "bf16")]
+    out, lse = api.fb_dense_bias_attn_fwd(*d, causal=causal)
+    grads = api.fb_dense_bias_attn_bwd(*d, out, lse, dev(dout, "bf16"), causal=causal)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for h in range(H):
+            bb = bias[0 if shared else b, h]
+            ro, rl = O.attention_with_bias(q[b, h], k[b, h], v[b, h], bb, causal=causal)
+            assert max_abs(host(out[b, h]), ro) <= TOL["bf16"] and max_abs(host(lse[b, h]), rl) <= TOL["bf16"]
+            ref = O.attention_with_bias_grads(q[b, h], k[b, h], v[b, h], bb, dout[b, h], causal=causal)
+            for name, g, r in zip(("dq", "dk", "dv", "dbias"), grads, ref):
+                if name == "dbias" and causal:
+                    r = np.tril(r)
+                err = max_abs(host(g[b, h]), r) / max(1.0, float(np.abs(r).max()) / 2.5)
+                assert err <= GRAD_TOL, (name, err)
