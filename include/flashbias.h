@@ -27,7 +27,7 @@
  *     into three bf16 limbs inside the kernel (six product columns per rank), which keeps
  *     ~24 bits of each factor (needed e.g. for ALiBi positions up to N).  With
  *     dtype = FB_F32 everything is fp32 FMA and phi_dtype must be FB_F32.
- *   - Supported: C in {16, 32, 64, 128} (fb_dense_bias_attn_bwd: not 16); 0 <= R, with the
+ *   - Supported: C in {16, 32, 64, 128}; 0 <= R, with the
  *     padded factor width (R for bf16 factors, 6R for fp32 factors in a bf16 run, rounded up
  *     to 16) at most 64; fp32 forward: R <= 64.  R = 0 (phi pointers may be NULL) is plain
  *     attention.  C = 16 (the PDE-solver head dimension of Sec. 4.3) runs on the 32-channel
@@ -220,7 +220,7 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
  * to write the dense gradient dbias [B,H,N,N] (= dL/dS, storage type `dtype`, always per batch
  * element), the N x N object that the factorised form never materialises (Sec. 4.3, "record
  * the gradient of the bias matrix").  Entries above the diagonal are zero when causal.
- * Needs dtype = FB_BF16, N % 8 == 0 and C >= 32.  Workspace as for fb_lowrank_attn_bwd.
+ * Needs dtype = FB_BF16 and N % 8 == 0.  Workspace as for fb_lowrank_attn_bwd with R = 0.
  */
 size_t fb_dense_bias_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype);
 

@@ -823,15 +823,18 @@ __global__ __launch_bounds__(kThreads, (DKV || DENSE || (C == 128 && RP > 32)) ?
     }
 }
 
-template <int C, int RP, bool CAUSAL>
+// Pre-pass and the two main kernels.  DENSE: the bias is a dense matrix streamed tile by tile
+// (RP = 0) and the dq kernel also writes dBias.
+template <int C, int RP, bool CAUSAL, bool DENSE = false>
 int launch(const BwdParams& pin, hipStream_t stream) {
     using K = Cfg<C, RP>;
-    constexpr size_t ring_dq = (size_t)NSLOT * (K::T1::BYTES + K::T2::BYTES);
-    constexpr size_t ring_dkv = (size_t)NSLOT_DKV * (K::T1::BYTES + K::T2::BYTES + K::kVecBytes);
+    constexpr size_t slot = K::T1::BYTES + K::T2::BYTES + (DENSE ? (size_t)kWaves * 32 * 32 * 2 : 0);
+    constexpr size_t ring_dq = (size_t)NSLOT * slot;
+    constexpr size_t ring_dkv = (size_t)NSLOT_DKV * (slot + K::kVecBytes);
     constexpr size_t lds_dq = ring_dq > K::kEpiLds ? ring_dq : K::kEpiLds;
     constexpr size_t lds_dkv = ring_dkv > K::kEpiLds ? ring_dkv : K::kEpiLds;
-    auto kdq = bwd_main_kernel<C, RP, CAUSAL, false>;
-    auto kdkv = bwd_main_kernel<C, RP, CAUSAL, true>;
+    auto kdq = bwd_main_kernel<C, RP, CAUSAL, false, DENSE>;
+    auto kdkv = bwd_main_kernel<C, RP, CAUSAL, true, DENSE>;
     static FbLdsOnce once_dq, once_dkv;
     if (!fb_raise_lds_limit((const void*)kdq, lds_dq, once_dq) || !fb_raise_lds_limit((const void*)kdkv, lds_dkv, once_dkv))
         return 1;
@@ -895,52 +898,6 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
-// Dense-bias backward: same pre-pass and kernels with RP = 0 and the bias tiles streamed.
-template <int C, bool CAUSAL>
-int launch_dense(const BwdParams& pin, hipStream_t stream) {
-    using K = Cfg<C, 0>;
-    constexpr size_t slot = K::T1::BYTES + K::T2::BYTES + (size_t)kWaves * 32 * 32 * 2;
-    constexpr size_t lds_dq = (size_t)NSLOT * slot;
-    constexpr size_t lds_dkv = (size_t)NSLOT_DKV * (slot + K::kVecBytes);
-    auto kdq = bwd_main_kernel<C, 0, CAUSAL, false, true>;
-    auto kdkv = bwd_main_kernel<C, 0, CAUSAL, true, true>;
-    static FbLdsOnce once_dq, once_dkv;
-    if (!fb_raise_lds_limit((const void*)kdq, lds_dq, once_dq) || !fb_raise_lds_limit((const void*)kdkv, lds_dkv, once_dkv))
-        return 1;
-
-    const long long rows = (long long)pin.B * pin.H * pin.N;
-    const long long rowsk = (long long)pin.B * pin.H * pin.M;
-    unsigned char* ws = (unsigned char*)pin.workspace;
-    MainArgs a;
-    a.vec = (const float2*)ws;
-    bf16_t* aq = (bf16_t*)(ws + (((size_t)rows * 8 + 15) & ~(size_t)15));
-    bf16_t* ak = aq + (size_t)rows * K::W;
-    a.aq = aq;
-    a.ak = ak;
-    hipLaunchKernelGGL((bwd_vec_kernel<C>), dim3((unsigned)((rows * (C / 8) + 255) / 256)), dim3(256), 0, stream,
-                       (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
-    if (hipGetLastError() != hipSuccess) return 1;
-    hipLaunchKernelGGL((bwd_prep_kernel<C, 0, true>), dim3((unsigned)((rows * (K::W / 8) + 255) / 256)),
-                       dim3(256), 0, stream, pin, aq);
-    if (hipGetLastError() != hipSuccess) return 1;
-    hipLaunchKernelGGL((bwd_prep_kernel<C, 0, false>), dim3((unsigned)((rowsk * (K::W / 8) + 255) / 256)),
-                       dim3(256), 0, stream, pin, ak);
-    if (hipGetLastError() != hipSuccess) return 1;
-    auto set_tiles = [](BwdParams& p, int lane_rows) {
-        p.n_tiles = (lane_rows + 127) / 128;
-        const int n_units = CAUSAL ? (p.n_tiles + 1) / 2 : p.n_tiles;
-        p.total_tiles = p.B * p.H * n_units;
-        p.tiles_per_xcd = (p.total_tiles + 7) / 8;
-    };
-    BwdParams p = pin;
-    set_tiles(p, p.M);
-    hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p, a);
-    if (hipGetLastError() != hipSuccess) return 1;
-    set_tiles(p, p.N);
-    hipLaunchKernelGGL(kdq, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dq, stream, p, a);
-    return hipGetLastError() == hipSuccess ? 0 : 1;
-}
-
 template <int C, int RP>
 int dispatch_causal(const BwdParams& p, hipStream_t stream) {
     return p.causal ? launch<C, RP, true>(p, stream) : launch<C, RP, false>(p, stream);
@@ -969,9 +926,10 @@ size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R) 
 
 int fb_launch_bwd_dense_bf16(const BwdParams& p, int C, hipStream_t stream) {
     switch (C) {
-        case 32: return p.causal ? launch_dense<32, true>(p, stream) : launch_dense<32, false>(p, stream);
-        case 64: return p.causal ? launch_dense<64, true>(p, stream) : launch_dense<64, false>(p, stream);
-        case 128: return p.causal ? launch_dense<128, true>(p, stream) : launch_dense<128, false>(p, stream);
+        case 16: return p.causal ? launch<32, 0, true, true>(p, stream) : launch<32, 0, false, true>(p, stream);   // p.Cg = 16
+        case 32: return p.causal ? launch<32, 0, true, true>(p, stream) : launch<32, 0, false, true>(p, stream);
+        case 64: return p.causal ? launch<64, 0, true, true>(p, stream) : launch<64, 0, false, true>(p, stream);
+        case 128: return p.causal ? launch<128, 0, true, true>(p, stream) : launch<128, 0, false, true>(p, stream);
         default: return -1;
     }
 }

@@ -18,12 +18,15 @@ CASES = [
     (1, 1, 8, 64, False, False),
     (2, 2, 512, 128, True, True),      # bias shared over the batch
     (2, 1, 200, 64, False, True),
+    (2, 2, 264, 16, True, False),      # head dimension 16: 32-channel tiles, upper half zero-filled
+    (1, 3, 200, 16, False, True),
+    (1, 1, 8, 16, False, False),
 ]
 
 
 @pytest.mark.parametrize("B,H,N,C,causal,shared", CASES)
 def test_dense_backward(B, H, N, C, causal, shared):
-    rng = np.random.default_rng(7000 + N + C)
+    rng = np.random.default_rng(7000 + N + C + (3 if causal else 0))
     rd = lambda shape: W.round_bf16(rng.standard_normal(shape).astype(np.float32))
     q, k, v, dout = rd((B, H, N, C)), rd((B, H, N, C)), rd((B, H, N, C)), rd((B, H, N, C))
     bias = rd((1 if shared else B, H, N, N))

@@ -120,7 +120,7 @@ def test_xattn_random_shape(B, H, N, M, C, R, phi_dtype, seed):
 def _dcases(n, seed):
     rng = np.random.default_rng(seed)
     return [(int(rng.integers(1, 3)), int(rng.integers(1, 3)), 8 * int(rng.integers(1, 70)),
-             int(rng.choice([32, 64, 128])), bool(rng.integers(0, 2)), bool(rng.integers(0, 2)),
+             int(rng.choice([16, 32, 64, 128])), bool(rng.integers(0, 2)), bool(rng.integers(0, 2)),
              int(rng.integers(1 << 30))) for _ in range(n)]
 
 

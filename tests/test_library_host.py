@@ -73,6 +73,8 @@ def test_dense_and_backward_argument_errors(lib):
     db = lib.fb_dense_bias_attn_bwd
     wsd = lib.fb_dense_bias_attn_bwd_workspace_bytes(1, 1, 64, 64, api.FB_BF16)
     assert wsd == 64 * 8 + 2 * 64 * 64 * 2
+    # head dimension 16: 32-channel operand rows plus widened copies of v and dO
+    assert lib.fb_dense_bias_attn_bwd_workspace_bytes(1, 1, 64, 16, api.FB_BF16) == 64 * 8 + 2 * 64 * (32 + 32) * 2
     assert db(*([64] * 10), None, 1, 1, 64, 64, 0, api.FB_BF16, 0, 0.0, 64, wsd, None) == 1         # dbias NULL
     assert db(*([64] * 11), 1, 1, 60, 64, 0, api.FB_BF16, 0, 0.0, 64, wsd, None) == 3               # N % 8 != 0
     assert db(*([64] * 11), 1, 1, 64, 64, 0, api.FB_BF16, 0, 0.0, 64, wsd - 1, None) == 5
