@@ -124,8 +124,9 @@ FB_DEV void phi_item_store_k(bf16_t* dst, float x) {
 // Eight consecutive columns [8*c8, 8*c8+8) of a factor row widened to the padded layout.
 //   bf16 factors: column j holds phi[j] for j < R, else 0.
 //   fp32 factors: column j holds limb (slot j % 6) of phi[j / 6] for j / 6 < R, else 0.
+// `mul` scales an fp32 factor before it is split.
 template <bool QSIDE>
-FB_DEV bf16x8 phi_chunk_gather(const void* row, int c8, int R, bool f32) {
+FB_DEV bf16x8 phi_chunk_gather(const void* row, int c8, int R, bool f32, float mul = 1.f) {
     bf16x8 out;
 #pragma unroll
     for (int e = 0; e < 8; e++) {
@@ -136,7 +137,7 @@ FB_DEV bf16x8 phi_chunk_gather(const void* row, int c8, int R, bool f32) {
         } else {
             const int r = j / 6, slot = j - 6 * r;
             if (r < R) {
-                const float x = ((const float*)row)[r];
+                const float x = ((const float*)row)[r] * mul;
                 val = bf16_limb(x, QSIDE ? q_limb_of_slot(slot) : k_limb_of_slot(slot));
             }
         }

@@ -93,7 +93,16 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     const int N = p.N, M = p.M, R = PM == 4 ? 2 : p.R;   // N queries, M keys
     const bool phi_f32 = PM == 3 || PM == 4;
     const bool ITEMS = PM == 3 || PM == 4;     // key-side factors handled as (key, rank) items
-    const float slope = PM == 4 ? p.slopes[h] : 0.f;
+    // fp32 factors are split into limbs here anyway, so the query operand can carry the log2 e
+    // of the exponential (q * scale * log2 e, phi_q * log2 e) and the score accumulator can start
+    // at minus the row's reference maximum: the softmax then needs no multiply-add per score.
+    // bf16 factors are copied as they are (a rescaled copy would round them again), so those
+    // modes keep the multiply-add.  The start value takes 16 registers per query block: used on
+    // the 32-channel tiles, where the vector ALU is the bound (-7 % on the C = 16 point-cloud
+    // shape) and the registers are free; at C = 128 it changed nothing and at C = 64 it spills.
+    constexpr bool FOLD = !DENSE && (PM == 3 || PM == 4) && C == 32;
+    const float qmul = FOLD ? kLog2e : 1.f;
+    const float slope = PM == 4 ? p.slopes[h] * qmul : 0.f;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -122,8 +131,13 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     f32x16 oacc[QB][C / 32];
     float mref[QB], lsum[QB];
     bool ref_ok[QB];      // wave-uniform: every row of the wave has a finite reference maximum
+    f32x16 sinit[QB];   // FOLD: minus the reference maximum, the score chain's start value
 #pragma unroll
     for (int qb = 0; qb < QB; qb++) {
+        if (FOLD) {
+#pragma unroll
+            for (int r = 0; r < 16; r++) sinit[qb][r] = 0.f;
+        }
         mref[qb] = -INFINITY;
         lsum[qb] = 0.f;
         ref_ok[qb] = false;
@@ -367,6 +381,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         load_block(1, st1);
         // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout).  Rows past N
         // read row N-1 (finite values) and are never stored.
+        const float qscale = p.scale * qmul;
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) {
             const int qi = min(qw0 + qb * 32 + l32, N - 1);
@@ -377,7 +392,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                     if (ks * 16 < CG) {
                         const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qi * CG + ks * 16 + 8 * hf));
 #pragma unroll
-                        for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
+                        for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * qscale);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
@@ -385,7 +400,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 } else {
                     const int c8 = (ks - C / 16) * 2 + hf;
                     if (PM == 4) val = phi_chunk_from_pair(c8, -slope * (float)(qi - q0), slope);
-                    else val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32);
+                    else val = phi_chunk_gather<true>(pqg + (size_t)qi * R * phi_esz, c8, R, phi_f32, qmul);
                 }
                 qreg[qb][ks] = val;
             }
@@ -423,6 +438,8 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 #pragma unroll
                     for (int x = 0; x < 4; x++) s[qb][4 * g + x] = (float)bv[x];
                 }
+            } else if (FOLD) {
+                s[qb] = sinit[qb];
             } else {
 #pragma unroll
                 for (int r = 0; r < 16; r++) s[qb][r] = 0.f;
@@ -472,13 +489,14 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                     if (key >= M || (CAUSAL && key > qi)) s[qb][r] = -INFINITY;
                 }
             }
-            // P = exp2(S log2e - mref), packed to bf16, and this lane's partial row sum
+            // P = exp2(S log2e - mref), packed to bf16, and this lane's partial row sum (FOLD: the
+            // scores arrive as S log2e - mref)
             auto exps = [&](float nm) __attribute__((always_inline)) {
                 float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
-                    const bf16x2 pr2 = {(bf16_t)fast_exp2(fmaf(s[qb][r], kLog2e, nm)),
-                                        (bf16_t)fast_exp2(fmaf(s[qb][r + 1], kLog2e, nm))};
+                    const bf16x2 pr2 = {(bf16_t)fast_exp2(FOLD ? s[qb][r] : fmaf(s[qb][r], kLog2e, nm)),
+                                        (bf16_t)fast_exp2(FOLD ? s[qb][r + 1] : fmaf(s[qb][r + 1], kLog2e, nm))};
                     ps[(r >> 1) & 3] = pair_sum(pr2, ps[(r >> 1) & 3]);
                     pb[qb][r / 8][r % 8] = pr2[0];
                     pb[qb][r / 8][r % 8 + 1] = pr2[1];
@@ -499,7 +517,9 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 // first visible blocks of a tile, or the scores outgrew the reference: take the true
                 // row maximum, rescale what has been accumulated, and redo the exponentials
                 asm volatile("" ::: "memory");   // keep this a real (rarely taken) branch
-                const float mx = half_max(max16(s[qb])) * kLog2e;
+                // FOLD: what the scores already carry (0 while the row has no reference)
+                const float emb = mref[qb] == -INFINITY ? 0.f : mref[qb];
+                const float mx = FOLD ? half_max(max16(s[qb])) + emb : half_max(max16(s[qb])) * kLog2e;
                 if (__any(mx > mref[qb])) {
                     const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
                     const float alpha = fast_exp2(mref[qb] - mnew);
@@ -511,7 +531,15 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                         for (int r = 0; r < 16; r++) oacc[qb][cb][r] *= alpha;
                 }
                 // a row that has not met a visible key yet (causal, reverse order) keeps p = 0
-                psum = exps(mref[qb] == -INFINITY ? 0.f : -mref[qb]);
+                const float emb2 = mref[qb] == -INFINITY ? 0.f : mref[qb];
+                if (FOLD) {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        s[qb][r] += emb - emb2;     // masked scores stay -inf
+                        sinit[qb][r] = -emb2;
+                    }
+                }
+                psum = exps(-emb2);
                 if (!ref_ok[qb]) ref_ok[qb] = !__any(mref[qb] == -INFINITY);
             }
             lsum[qb] += psum;
