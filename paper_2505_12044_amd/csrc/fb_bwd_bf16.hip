@@ -485,9 +485,14 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     //   [0, KS)            S   k-step n          row read of T1
     //   [KS, KS+CS)        dP  k-step n-KS       row read of T2
     //   then NO1 = 2*MB    output 1, (mb, kk)    transpose read of T1
-    //   then NO2 = 2*MBC   output 2 (DKV only)   transpose read of T2
+    //   then NO2 = 2*MBC   output 2 (DKV only)   transpose read of T2   (LAZY_DS: output 2 before output 1)
     constexpr int NO1 = 2 * K::MB, NO2 = DKV ? 2 * K::MBC : 0;
     constexpr int NA = K::KS + K::CS;          // operands of the first half
+    // dkv kernel, one wave per SIMD: a wave hides about five vector instructions under each MFMA.
+    // With eight or more dV MFMAs (C = 128) the dS arithmetic of a block (sub, mul, convert: 40
+    // instructions) fits under them, which leaves only the exponentials under the S / dP chains;
+    // smaller head dimensions have too few dV MFMAs and keep everything under the first half.
+    constexpr bool LAZY_DS = DKV && NO2 >= 8;
     constexpr int NOPS = NA + NO1 + NO2;
     // LDS operand reads run LA MFMAs ahead of their use; the first half never reads past its own block
     // (measured: look-ahead 2..4 for dq and 5..12 for dkv all run within 1 %)
@@ -514,6 +519,12 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     auto read_op = [&](const RowBase& rb, const TrBase& tb, int n) __attribute__((always_inline)) {
         if (n < K::KS) return row_read(rb, 0, T1::NP64, n);
         if (n < NA) return row_read(rb, kOffT2, T2::NP64, n - K::KS);
+        if (LAZY_DS) {
+            // the P-side output (dV) first: its operand is complete when the first half ends, while dS
+            // is still being formed under these MFMAs
+            if (n < NA + NO2) return tr_read(tb, kOffT2, T2::NP64, (n - NA) >> 1, (n - NA) & 1);
+            return tr_read(tb, 0, T1::NP64, (n - NA - NO2) >> 1, (n - NA - NO2) & 1);
+        }
         if (n < NA + NO1) return tr_read(tb, 0, T1::NP64, (n - NA) >> 1, (n - NA) & 1);
         return tr_read(tb, kOffT2, T2::NP64, (n - NA - NO1) >> 1, (n - NA - NO1) & 1);
     };
@@ -548,6 +559,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         //     S, dP chains of block i+1  ||  P, dS of block i
         //     wait, barrier, issue block i+4
         //     output chains of block i, first operand reads of block i+2, (lse2, D) of block i+1
+        // (LAZY_DS: only P under the first chains, dS under the dV chains, then the dK chains)
         // Ring of five slots: blocks i (transpose reads), i+1 (row reads), i+2 (prefetch),
         // i+3 (landing), i+4 (being issued).
         static_assert(NSLOT_DKV == 5, "slot arithmetic below assumes five slots");
@@ -601,6 +613,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             const int sb0 = blk_of(i) * BT;
             const bool need_mask = (sb0 + BT > NS) || (CAUSAL && sb0 < rw0 + 31);
             bf16x8 pb[2], dsb[2];
+            float prf[16];                                      // P of block i in fp32, until dS is formed
             f32x16 sinit = zero;
             if (DENSE) bias_init(sinit, sl1 * kSlotBytes);      // S of block i+1 starts from its bias tile
             __builtin_amdgcn_sched_barrier(0);
@@ -612,22 +625,32 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
                     else dn = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], n == K::KS ? zero : dn);
                 }
 #pragma unroll
-                for (int e = (n * 16) / NA; e < ((n + 1) * 16) / NA; e++)
-                    elem(e, sc, dc, vq[e >> 2][e & 3], vd[e >> 2][e & 3], false, sb0, pb, dsb);
+                for (int e = (n * 16) / NA; e < ((n + 1) * 16) / NA; e++) {
+                    if (LAZY_DS) {
+                        prf[e] = fast_exp2(fmaf(sc[e], kLog2e, -vq[e >> 2][e & 3]));
+                        pb[e / 8][e % 8] = (bf16_t)prf[e];
+                    } else {
+                        elem(e, sc, dc, vq[e >> 2][e & 3], vd[e >> 2][e & 3], false, sb0, pb, dsb);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (need_mask) {
                 // rare (diagonal blocks, sequence end): zero the dead elements afterwards, behind a real
                 // branch, so the common path carries no compares and selects.  NaNs from filler rows
-                // past N are discarded here as well.
+                // past N are discarded here as well.  LAZY_DS: with P zeroed, dS = P (dP - D) formed
+                // later is zero too; the (lse, D) pair of a filler row past the sequence end is whatever
+                // follows in memory, so its D is replaced to keep 0 * (dP - D) at 0.
                 asm volatile("" ::: "memory");
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int srow = sb0 + 8 * (r / 4) + 4 * hf + (r % 4);
                     if (srow >= NS || (CAUSAL && srow < ri)) {
                         pb[r / 8][r % 8] = (bf16_t)0.f;
-                        dsb[r / 8][r % 8] = (bf16_t)0.f;
+                        if (LAZY_DS) prf[r] = 0.f;
+                        else dsb[r / 8][r % 8] = (bf16_t)0.f;
                     }
+                    if (LAZY_DS && srow >= NS) vd[r >> 2][r & 3] = 0.f;
                 }
             }
             // block i+2 has landed; everyone has left block i-1
@@ -641,8 +664,19 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
                 if (n + LA < NOPS) opr[(n + LA) % (LA + 1)] = read_op(rb1, tb0, n + LA);
                 else nxt[n + LA - NOPS] = read_op(rb2, tb0, n + LA - NOPS);   // row operands of block i+2
                 const int m = n - NA;
-                if (m < NO1) acc1[m >> 1] = mfma32(opr[n % (LA + 1)], dsb[m & 1], acc1[m >> 1]);
-                else acc2[(m - NO1) >> 1] = mfma32(opr[n % (LA + 1)], pb[(m - NO1) & 1], acc2[(m - NO1) >> 1]);
+                if (!LAZY_DS) {
+                    if (m < NO1) acc1[m >> 1] = mfma32(opr[n % (LA + 1)], dsb[m & 1], acc1[m >> 1]);
+                    else acc2[(m - NO1) >> 1] = mfma32(opr[n % (LA + 1)], pb[(m - NO1) & 1], acc2[(m - NO1) >> 1]);
+                } else if (m < NO2) {
+                    acc2[m >> 1] = mfma32(opr[n % (LA + 1)], pb[m & 1], acc2[m >> 1]);
+                    // dS of block i under the dV MFMAs, 16 / NO2 elements per MFMA
+#pragma unroll
+                    for (int e = (m * 16) / NO2; e < ((m + 1) * 16) / NO2; e++)
+                        dsb[e / 8][e % 8] = (bf16_t)(prf[e] * (dc[e] - vd[e >> 2][e & 3]));
+                    __builtin_amdgcn_sched_barrier(0);
+                } else {
+                    acc1[(m - NO2) >> 1] = mfma32(opr[n % (LA + 1)], dsb[(m - NO2) & 1], acc1[(m - NO2) >> 1]);
+                }
             }
 #pragma unroll
             for (int n = 0; n < LA; n++) opr[n] = nxt[n];
