@@ -99,8 +99,10 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     // bf16 factors are copied as they are (a rescaled copy would round them again), so those
     // modes keep the multiply-add.  The start value takes 16 registers per query block: used on
     // the 32-channel tiles, where the vector ALU is the bound (-7 % on the C = 16 point-cloud
-    // shape) and the registers are free; at C = 128 it changed nothing and at C = 64 it spills.
-    constexpr bool FOLD = !DENSE && (PM == 3 || PM == 4) && C == 32;
+    // shape) and the registers are free, and at C = 128 with the narrowest factor block (ALiBi:
+    // -0.8 % with factor tensors, -2.4 % with in-kernel factors, measured back to back on one
+    // device); wider factor blocks at C = 128 and two query blocks at C = 64 would spill.
+    constexpr bool FOLD = !DENSE && (PM == 3 || PM == 4) && (C == 32 || (C == 128 && RP == 16));
     const float qmul = FOLD ? kLog2e : 1.f;
     const float slope = PM == 4 ? p.slopes[h] * qmul : 0.f;
 
