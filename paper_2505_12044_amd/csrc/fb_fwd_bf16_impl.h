@@ -99,10 +99,11 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     // bf16 factors are copied as they are (a rescaled copy would round them again), so those
     // modes keep the multiply-add.  The start value takes 16 registers per query block: used on
     // the 32-channel tiles, where the vector ALU is the bound (-7 % on the C = 16 point-cloud
-    // shape) and the registers are free, and at C = 128 with the narrowest factor block (ALiBi:
-    // -0.8 % with factor tensors, -2.4 % with in-kernel factors, measured back to back on one
-    // device); wider factor blocks at C = 128 and two query blocks at C = 64 would spill.
-    constexpr bool FOLD = !DENSE && (PM == 3 || PM == 4) && (C == 32 || (C == 128 && RP == 16));
+    // shape) and the registers are free.  At C = 128 it gains 1-2 % at most, and it rounds
+    // q * scale * log2 e where the backward rounds q * scale: scores that differ by one bf16
+    // rounding between the passes leave the rows of dS summing to ~1e-3 D instead of zero, which
+    // factor gradients of absolute positions (ALiBi) multiply by up to N.  Not used there.
+    constexpr bool FOLD = !DENSE && (PM == 3 || PM == 4) && C == 32;
     const float qmul = FOLD ? kLog2e : 1.f;
     const float slope = PM == 4 ? p.slopes[h] * qmul : 0.f;
 
