@@ -29,6 +29,9 @@ the rank-9 squared-distance factorisation (Example 3.5), the channel-concatenati
 identity (Eq. 3), closed forms for q = 0, softmax invariants, a library cross-check
 against torch's float64 scaled_dot_product_attention, Eckart-Young for truncated SVD
 (Remark 3.8's "energy"), and central finite differences plus invariants for gradients.
+The batched wrappers are pinned slice by slice against the single-head functions and, as whole
+[B,H,N,.] tensors, against torch float64 autograd / scaled_dot_product_attention with shared
+factors or bias as one broadcast parameter.
 The paper prints no worked numeric example of attention outputs, so output values are
 pinned only through those identities, closed forms and the library cross-check.
 

@@ -443,3 +443,114 @@ def test_bf16_rounding_helper():
     rng = np.random.default_rng(0)
     y = rng.standard_normal(10000).astype(np.float32) * 100
     np.testing.assert_array_equal(W.round_bf16(y), torch.from_numpy(y).to(torch.bfloat16).float().numpy())
+
+
+# ---------------------------------------------------------------- batched wrappers, pinned
+def _torch_batched_scores(q, k, phi_q, phi_k, bias, causal):
+    """scale q k^T + b on whole [B,H,N,.] tensors with torch broadcasting (batch size 1 of the
+    factors / bias expands over B): an independent batched formulation for the pins below."""
+    c = q.shape[-1]
+    s = torch.einsum("bhic,bhjc->bhij", q, k) / math.sqrt(c)
+    if phi_q is not None:
+        s = s + torch.einsum("bhir,bhjr->bhij", phi_q, phi_k)
+    if bias is not None:
+        s = s + bias
+    if causal:
+        n = q.shape[2]
+        s = s.masked_fill(torch.triu(torch.ones(n, n, dtype=torch.bool), 1), -math.inf)
+    return s
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("shared", [False, True])
+def test_batched_lowrank_grads_pinned(shared, causal):
+    """batched_attention_lowrank / batched_attention_lowrank_grads on B = 3, H = 2 with distinct
+    data in every (b, h): (1) each slice equals the single-head function on that slice with the
+    factors of batch 0 (shared) or b (per batch); (2) torch float64 autograd on the whole batched
+    tensors, where a shared factor is ONE parameter broadcast over the batch: its gradient is the
+    sum over b of the per-batch dphi the wrapper returns.  A swapped batch / head index, a wrong
+    broadcast choice or a summed instead of per-batch dphi fails here."""
+    rng = np.random.default_rng(31 + int(shared) + 2 * int(causal))
+    B, H, n, c, r = 3, 2, 19, 6, 3
+    q, k, v, dout = (_rand(rng, B, H, n, c) for _ in range(4))
+    bp = 1 if shared else B
+    pq, pk = _rand(rng, bp, H, n, r), _rand(rng, bp, H, n, r)
+    out, lse = O.batched_attention_lowrank(q, k, v, pq, pk, causal=causal)
+    grads = O.batched_attention_lowrank_grads(q, k, v, pq, pk, dout, causal=causal)
+    assert grads[3].shape == (B, H, n, r) and grads[4].shape == (B, H, n, r)
+    for b in range(B):
+        for h in range(H):
+            bb = 0 if shared else b
+            o1, l1 = O.attention_lowrank(q[b, h], k[b, h], v[b, h], pq[bb, h], pk[bb, h], causal=causal)
+            np.testing.assert_array_equal(out[b, h], o1)
+            np.testing.assert_array_equal(lse[b, h], l1)
+            g1 = O.attention_lowrank_grads(q[b, h], k[b, h], v[b, h], pq[bb, h], pk[bb, h], dout[b, h],
+                                           causal=causal)
+            for a, g in zip(grads, g1):
+                np.testing.assert_array_equal(a[b, h], g)
+    tq, tk, tv, tpq, tpk = (torch.tensor(x, requires_grad=True) for x in (q, k, v, pq, pk))
+    s = _torch_batched_scores(tq, tk, tpq, tpk, None, causal)
+    to = torch.softmax(s, dim=-1) @ tv
+    np.testing.assert_allclose(out, to.detach().numpy(), atol=1e-12)
+    np.testing.assert_allclose(lse, torch.logsumexp(s, dim=-1).detach().numpy(), atol=1e-12)
+    (to * torch.from_numpy(dout)).sum().backward()
+    for a, t in zip(grads[:3], (tq, tk, tv)):
+        np.testing.assert_allclose(a, t.grad.numpy(), atol=1e-11)
+    for a, t in zip(grads[3:], (tpq, tpk)):
+        ref = t.grad.numpy()
+        got = a.sum(axis=0, keepdims=True) if shared else a
+        np.testing.assert_allclose(got, ref, atol=1e-11)
+    # distinct data per (b, h): no two slices of the result coincide
+    flat = out.reshape(B * H, -1)
+    assert all(np.max(np.abs(flat[i] - flat[j])) > 1e-3 for i in range(B * H) for j in range(i))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("shared", [False, True])
+def test_batched_dense_pinned(shared, causal):
+    """batched_attention_dense on B = 3, H = 2: every (b, h) slice against the single-head
+    function, and the whole batch against torch's float64 scaled_dot_product_attention with the
+    bias as a broadcast attn_mask."""
+    rng = np.random.default_rng(41 + int(shared) + 2 * int(causal))
+    B, H, n, c = 3, 2, 17, 8
+    q, k, v = (_rand(rng, B, H, n, c) for _ in range(3))
+    bias = 2.0 * _rand(rng, 1 if shared else B, H, n, n)
+    out, lse = O.batched_attention_dense(q, k, v, bias, causal=causal)
+    for b in range(B):
+        for h in range(H):
+            o1, l1 = O.attention_with_bias(q[b, h], k[b, h], v[b, h], bias[0 if shared else b, h], causal=causal)
+            np.testing.assert_array_equal(out[b, h], o1)
+            np.testing.assert_array_equal(lse[b, h], l1)
+    mask = torch.from_numpy(bias)
+    if causal:
+        mask = mask.masked_fill(torch.triu(torch.ones(n, n, dtype=torch.bool), 1), -math.inf)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q), torch.from_numpy(k), torch.from_numpy(v), attn_mask=mask.expand(B, H, n, n))
+    np.testing.assert_allclose(out, ref.numpy(), atol=1e-10)
+    s = _torch_batched_scores(torch.from_numpy(q), torch.from_numpy(k), None, None, torch.from_numpy(bias), causal)
+    np.testing.assert_allclose(lse, torch.logsumexp(s, dim=-1).numpy(), atol=1e-12)
+    # heads and batch items are distinguishable: swapping either changes the result
+    assert np.max(np.abs(out[0, 0] - out[0, 1])) > 1e-3 and np.max(np.abs(out[0, 0] - out[1, 0])) > 1e-3
+
+
+def test_lowrank_storage_matches_printed_count():
+    """Proof of Theorem 3.2: a rank-R N x N matrix has 2NR - R^2 degrees of freedom.  Pinned on
+    lowrank_bias: the Jacobian of (phi_q, phi_k) -> phi_q phi_k^T at a generic point has exactly
+    that rank (the R^2 missing directions are the invertible mixings that leave the product
+    unchanged — which is also why tests never compare factors, only their product)."""
+    g = _golden()
+    rng = np.random.default_rng(51)
+    for N, R in ((6, 2), (7, 3), (5, 5)):
+        expect = int(eval(g["lowrank_storage"], {"__builtins__": {}}, {"N": N, "R": R}))
+        pq, pk = _rand(rng, N, R), _rand(rng, N, R)
+        base = O.lowrank_bias(pq, pk)
+        cols = []
+        eps = 1e-6
+        for arr in (pq, pk):
+            for idx in np.ndindex(arr.shape):
+                old = arr[idx]
+                arr[idx] = old + eps
+                cols.append(((O.lowrank_bias(pq, pk) - base) / eps).ravel())
+                arr[idx] = old
+        sv = np.linalg.svd(np.stack(cols, axis=1), compute_uv=False)
+        assert int(np.sum(sv > 1e-4 * sv[0])) == expect == 2 * N * R - R * R
