@@ -38,7 +38,10 @@
  *   - Return value: FB_OK or an fb_status for errors detectable on the host (bad argument,
  *     unsupported shape, misalignment, workspace too small, launch failure).  Outputs are
  *     fully overwritten on success and untouched on error.  Thread-safe; the only process-wide
- *     state is the set of fb_tune_set knobs.
+ *     state is the atomic variant selection of fb_tune_set (a test hook).
+ *   - Size limits (FB_ERR_SHAPE beyond them): B H N < 2^31 rows; N C < 2^30 and N R < 2^30
+ *     elements inside one head.  Offsets above the head level are 64-bit, so tensors may exceed
+ *     2^31 elements.
  */
 #ifndef FLASHBIAS_H_
 #define FLASHBIAS_H_
@@ -68,9 +71,12 @@ int fb_version(void);
 const char* fb_status_string(int status);
 
 /*
- * Process-wide tuning knobs for experiments (benchmarks sweep them; results never depend on
- * them).  Returns FB_OK, FB_ERR_NULL, FB_ERR_SHAPE (value out of range) or
- * FB_ERR_UNSUPPORTED (unknown name).  Not synchronised with concurrent calls.
+ * Test hook: selects among kernel variants that compute the same result (the parity tests
+ * run every variant; benchmarks compare them).  Results never depend on it beyond rounding
+ * order.  The state is process-wide and atomic: each entry point reads a knob once, on the
+ * host, when it is called, so a call enqueued (or captured into a graph) keeps the variant it
+ * was issued with.  Returns FB_OK, FB_ERR_NULL, FB_ERR_SHAPE (value out of range) or
+ * FB_ERR_UNSUPPORTED (unknown name).
  *   "fwd_qb"      bf16 forward kernel variant; 0 restores the automatic choice.
  *                 1, 2 = four-wave kernel with that many 32-row query blocks per wave
  *                 8    = eight-wave ping-pong kernel
@@ -79,8 +85,6 @@ const char* fb_status_string(int status);
  *                 kernel takes, the first walks its off-diagonal key blocks upwards from key 0
  *                 and the second downwards, so the workgroups of a head read the same block at
  *                 the same time (fewer L2 misses); 0: both walk downwards from the diagonal.
- *   "fwd_lds_pad" extra dynamic LDS bytes per workgroup of the four-wave kernel
- *                 (0 .. 102400), to study occupancy; 0 by default.
  */
 int fb_tune_set(const char* name, int value);
 
@@ -113,7 +117,7 @@ int fb_lowrank_xattn_fwd(const void* q, const void* k, const void* v,
  * factors of Example 3.4 are computed from tile indices, so no factor tensor is read
  * (App. D, "decomposition in JIT").  Positions are measured from the tile's first query row
  * and carried as fp32 (three bf16 limbs), so the bias is exact to fp32 rounding at any N.
- *   slopes [H] float, device memory, 4-byte aligned.  Needs dtype = FB_BF16.
+ *   slopes [H] float, device memory, 4-byte aligned.  Needs dtype = FB_BF16 and N <= 2^24.
  * Same result as fb_lowrank_attn_fwd with phi_q(i) = [-m_h i, m_h], phi_k(j) = [1, j] in fp32.
  */
 int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* slopes,
@@ -138,8 +142,10 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
  * bias is never formed.  A pre-pass writes q' * scale and k' (bf16) into the workspace; the
  * additive-bias forward kernels then run with the first C channels as q / k and the other
  * C (R - 1) as extra columns of the same contraction.
- *   phi_q, phi_k [Bp,H,N,R], R >= 1, 4-byte aligned; needs dtype = FB_BF16 and C (R - 1) <= 64
- *   (C = 64: R <= 2; C = 32: R <= 3; C = 16: R <= 5; C = 128: R = 1).
+ *   phi_q, phi_k [Bp,H,N,R], R >= 1, 4-byte aligned; needs dtype = FB_BF16 and C (R - 1) <= 128
+ *   for C <= 64 (C = 64: R <= 3; C = 32: R <= 5; C = 16: R <= 9); C = 128 takes R = 1 only (its
+ *   score operand already fills the registers two waves per SIMD leave).  Corollary I.2 puts
+ *   the useful range at small R in any case.
  *   workspace: device scratch of at least fb_lowrank_mulbias_attn_fwd_workspace_bytes(...)
  *   = 4 B H N C R bytes, 16-byte aligned, owned by the caller, contents ignored on entry,
  *   reusable once the call's work on `stream` has finished.
@@ -175,8 +181,9 @@ int fb_alibi_attn_bwd(const void* q, const void* k, const void* v, const float* 
  * additive-bias backward kernels give the gradients of the reweighted repeats q', k', and a
  * fold kernel applies dq = scale sum_r phi_q,r dq'_r, dphi_q,r = scale sum_c q_c dq'_r,c (and
  * the same without the scale on the key side).  Same limits as the forward.
- *   workspace: fb_lowrank_mulbias_attn_bwd_workspace_bytes(...) bytes (the repeats, their
- *   gradients and the additive backward's scratch), 16-byte aligned, caller-owned.
+ *   workspace: fb_lowrank_mulbias_attn_bwd_workspace_bytes(...) bytes (the repeats in bf16, their
+ *   gradients in fp32 — dq and dphi are sums over them and are rounded once, at the end — and
+ *   the additive backward's scratch), 16-byte aligned, caller-owned.
  */
 size_t fb_lowrank_mulbias_attn_bwd_workspace_bytes(int B, int H, int N, int C, int R, fb_dtype dtype);
 
@@ -218,8 +225,8 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
 /*
  * Backward of fb_dense_bias_attn_fwd, the training-side baseline: besides dq, dk, dv it has
  * to write the dense gradient dbias [B,H,N,N] (= dL/dS, storage type `dtype`, always per batch
- * element), the N x N object that the factorised form never materialises (Sec. 4.3, "record
- * the gradient of the bias matrix").  Entries above the diagonal are zero when causal.
+ * element), the N x N object that the factorised form never materialises (Sec. 4.3).  Entries
+ * above the diagonal are zero when causal.
  * Needs dtype = FB_BF16 and N % 8 == 0.  Workspace as for fb_lowrank_attn_bwd with R = 0.
  */
 size_t fb_dense_bias_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype);

@@ -112,6 +112,16 @@ def _stream(stream) -> Optional[int]:
     return h or None
 
 
+def _scratch(nbytes: int, device, stream) -> torch.Tensor:
+    """A workspace the wrapper allocates itself.  The kernels run on `stream`; when that is not
+    torch's current stream the caching allocator must be told, or it could hand the block to
+    other work as soon as the tensor is dropped."""
+    ws = torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+    if stream is not None and hasattr(stream, "cuda_stream") and stream != torch.cuda.current_stream():
+        ws.record_stream(stream)
+    return ws
+
+
 def _check(status: int, what: str) -> None:
     if status != 0:
         msg = load_library().fb_status_string(status).decode()
@@ -183,7 +193,7 @@ def fb_alibi_attn_bwd(q, k, v, slopes, out, lse, dout, causal=False, scale: floa
         raise FlashBiasError("slopes must be a float32 tensor with one entry per head")
     need = fb_alibi_attn_bwd_workspace_bytes(B, H, N, C)
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     if grads is None:
         grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
     dq, dk, dv = grads
@@ -202,7 +212,7 @@ def fb_lowrank_mulbias_attn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, causa
                                 scale: float = 0.0, phi_batch_broadcast: Optional[bool] = None,
                                 workspace=None, stream=None):
     """out, lse = softmax((q k^T scale) * (phi_q phi_k^T)) v, the multiplicative-bias form.
-    q, k, v: [B,H,N,C] bf16; phi_q, phi_k: [B or 1,H,N,R], R >= 1, C (R - 1) <= 64."""
+    q, k, v: [B,H,N,C] bf16; phi_q, phi_k: [B or 1,H,N,R], R >= 1, C (R - 1) <= 128 for C <= 64 (R = 1 at C = 128)."""
     lib = load_library()
     B, H, N, C = q.shape
     R = phi_q.shape[-1]
@@ -214,7 +224,7 @@ def fb_lowrank_mulbias_attn_fwd(q, k, v, phi_q, phi_k, out=None, lse=None, causa
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
     need = fb_lowrank_mulbias_attn_fwd_workspace_bytes(B, H, N, C, R)
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     st = lib.fb_lowrank_mulbias_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(phi_q), _ptr(phi_k), _ptr(out),
                                          _ptr(lse), B, H, N, C, R, int(bool(causal)), _dtype_code(q),
                                          _dtype_code(phi_q), int(bool(phi_batch_broadcast)), float(scale),
@@ -239,7 +249,7 @@ def fb_lowrank_mulbias_attn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, causal=Fa
         phi_batch_broadcast = phi_q.shape[0] == 1 and B > 1
     need = fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R)
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     if grads is None:
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         dpq = torch.empty((B, H, N, R), dtype=phi_q.dtype, device=q.device)
@@ -311,7 +321,7 @@ def fb_lowrank_attn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, causal=False, sca
     phi_code = _dtype_code(phi_q) if phi_q is not None else _dtype_code(q)
     need = fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, R, _dtype_code(q))
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     if grads is None:
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         dpq = dpk = None
@@ -343,7 +353,7 @@ def fb_lowrank_xattn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, scale: float = 0
     phi_code = _dtype_code(phi_q) if phi_q is not None else _dtype_code(q)
     need = int(lib.fb_lowrank_xattn_bwd_workspace_bytes(B, H, N, M, C, R, _dtype_code(q)))
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     dpq = dpk = None
     if R:
@@ -376,7 +386,7 @@ def fb_dense_bias_attn_bwd(q, k, v, bias, out, lse, dout, causal=False, scale: f
         bias_batch_broadcast = bias.shape[0] == 1 and B > 1
     need = int(lib.fb_dense_bias_attn_bwd_workspace_bytes(B, H, N, C, _dtype_code(q)))
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     if grads is None:
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         dbias = torch.empty((B, H, N, N), dtype=q.dtype, device=q.device)

@@ -16,7 +16,7 @@ SOURCES = ["fb_api.hip", "fb_fwd_f32.hip", "fb_fwd_bf16.hip", "fb_fwd_bf16_c16.h
            "fb_mulbias.hip"]
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffast-math", "-fno-finite-math-only",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffast-math", "-fno-finite-math-only",
     # keep the compiler from forming packed-fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument", "-Wno-unknown-attributes",
@@ -45,6 +45,9 @@ def _compile(src: str, force: bool) -> str:
         raise RuntimeError(f"hipcc failed on {src}")
     errs = "\n".join(l for l in r.stderr.splitlines()
                      if "packed-fp32-ops" not in l and l.strip())
+    # the direct-to-LDS loads name m0 as clobbered on purpose; clang notes that it is a reserved register
+    if "Reserved registers on the clobber list" in errs or "inline asm clobber list contains reserved registers" in errs:
+        errs = ""
     if errs:
         sys.stderr.write(errs + "\n")
     return obj
@@ -56,7 +59,11 @@ def build(force: bool = True, jobs: int = 7) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    # only the C-ABI leaves the library: kernel stubs and helpers with external linkage stay local
+    vers = os.path.join(OBJ, "exports.map")
+    with open(vers, "w") as f:
+        f.write("{ global: fb_*; local: *; };\n")
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", f"-Wl,--version-script={vers}", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)

@@ -13,7 +13,6 @@
 namespace {
 
 std::atomic<int> g_fwd_qb{0};   // 0 = choose automatically
-std::atomic<int> g_lds_pad{0};
 std::atomic<int> g_causal_up{1};
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -24,13 +23,25 @@ int padded_rank(int R, fb_dtype dtype, fb_dtype phi_dtype) {
     return (cols + 15) / 16 * 16;
 }
 
+// What the kernels' indexing needs: every offset above the head level is 64-bit; row and
+// work-unit counters (B H N rows, B H ceil(N / 128) tiles, launch grids) are 32-bit; byte
+// offsets inside one head's rows (N C bf16 / fp32 elements, N R factor values) are 32-bit.
 int check_common(int B, int H, int N, int C, int R) {
     if (B <= 0 || H <= 0 || N <= 0 || R < 0) return FB_ERR_SHAPE;
-    if ((long long)B * H * N * (long long)(C > R ? C : R) >= (1LL << 31)) return FB_ERR_SHAPE;
-    if ((long long)N * R * 4 >= (1LL << 32)) return FB_ERR_SHAPE;     // 32-bit byte offsets inside a head's factor rows
+    if ((long long)B * H * N >= (1LL << 31)) return FB_ERR_SHAPE;
+    if ((long long)N * C * 4 >= (1LL << 32)) return FB_ERR_SHAPE;
+    if ((long long)N * R * 4 >= (1LL << 32)) return FB_ERR_SHAPE;
     if (C != 16 && C != 32 && C != 64 && C != 128) return FB_ERR_UNSUPPORTED;
     return FB_OK;
 }
+
+// Multiplicative bias: widest block of extra channels C (R - 1) the kernels are instantiated
+// for.  C = 128 takes none beyond R = 1: its score operand already fills the registers that
+// two waves per SIMD leave (C + 64 columns is the widest instantiation there).
+int mulbias_max_rest(int C) { return C <= 64 ? 128 : 0; }
+
+// Padded width of a block of `rest` bf16 extra channels: multiples of 16 up to 64, then 96, 128.
+int mulbias_padded(int rest) { return rest <= 64 ? (rest + 15) / 16 * 16 : (rest <= 96 ? 96 : 128); }
 
 int pick_qb(int B, int H, int N, int C, int rp, bool dense, bool causal) {
     const int forced = g_fwd_qb.load(std::memory_order_relaxed);
@@ -55,8 +66,7 @@ int pick_qb(int B, int H, int N, int C, int rp, bool dense, bool causal) {
 
 }  // namespace
 
-size_t fb_debug_lds_pad() { return (size_t)g_lds_pad.load(std::memory_order_relaxed); }
-
+#pragma GCC visibility push(default)
 extern "C" {
 
 int fb_version(void) { return 100; }
@@ -84,11 +94,6 @@ int fb_tune_set(const char* name, int value) {
     if (std::strcmp(name, "fwd_causal_up") == 0) {
         if (value != 0 && value != 1) return FB_ERR_SHAPE;
         g_causal_up.store(value, std::memory_order_relaxed);
-        return FB_OK;
-    }
-    if (std::strcmp(name, "fwd_lds_pad") == 0) {
-        if (value < 0 || value > 100 * 1024) return FB_ERR_SHAPE;
-        g_lds_pad.store(value, std::memory_order_relaxed);
         return FB_OK;
     }
     return FB_ERR_UNSUPPORTED;
@@ -185,6 +190,7 @@ int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* 
     if (!q || !k || !v || !slopes || !out || !lse) return FB_ERR_NULL;
     if (int st = check_common(B, H, N, C, 2)) return st;
     if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (N > (1 << 24)) return FB_ERR_UNSUPPORTED;          // positions are carried as fp32 integers
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
         return FB_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(slopes) & 3u) != 0) return FB_ERR_ALIGN;
@@ -219,11 +225,11 @@ int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
     if (!q || !k || !v || !phi_q || !phi_k || !out || !lse) return FB_ERR_NULL;
     if (R <= 0) return FB_ERR_SHAPE;
     if (int st = check_common(B, H, N, C, R)) return st;
-    if ((long long)B * H * N * (long long)C * R >= (1LL << 31)) return FB_ERR_SHAPE;
+    if ((long long)B * H * N * (long long)C * R >= (1LL << 38)) return FB_ERR_SHAPE;   // pre-pass grid: one thread per 8 channels
     if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     const int rest = C * (R - 1);                  // channels beyond the first repeat
-    if (rest > 64) return FB_ERR_UNSUPPORTED;
+    if (rest > mulbias_max_rest(C)) return FB_ERR_UNSUPPORTED;
     const void* ptrs[] = {q, k, v, out, lse};
     for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(phi_q) & 3u) != 0 || (reinterpret_cast<uintptr_t>(phi_k) & 3u) != 0)
@@ -255,8 +261,10 @@ int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
     p.bias_bstride = 0;
     p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = 1.0f;                                 // already folded into q'
-    const int rc = fb_launch_fwd_bf16(p, C, rest, false, pick_qb(B, H, N, C, rest, false, causal != 0),
-                                      (hipStream_t)stream);
+    const int rp = mulbias_padded(rest);
+    int qb = pick_qb(B, H, N, C, rp, false, causal != 0);
+    if (rp > 64) qb = 1;                           // wide blocks: four-wave kernel, one query block per wave
+    const int rc = fb_launch_fwd_bf16(p, C, rp, false, qb, (hipStream_t)stream);
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 
@@ -264,8 +272,8 @@ size_t fb_lowrank_mulbias_attn_bwd_workspace_bytes(int B, int H, int N, int C, i
     (void)dtype;
     if (B <= 0 || H <= 0 || N <= 0 || C <= 0 || R <= 0) return 0;
     const long long rows = (long long)B * H * N;
-    // q', k' and their gradients (C R bf16 channels each) and the additive backward's own scratch
-    return (size_t)4 * rows * C * R * 2 + fb_bwd_workspace_bytes(rows, rows, C, C * (R - 1));
+    // q', k' (C R bf16 channels each), their gradients (float) and the additive backward's own scratch
+    return (size_t)2 * rows * C * R * (2 + 4) + fb_bwd_workspace_bytes(rows, rows, C, C * (R - 1));
 }
 
 int fb_lowrank_mulbias_attn_bwd(const void* q, const void* k, const void* v,
@@ -279,11 +287,11 @@ int fb_lowrank_mulbias_attn_bwd(const void* q, const void* k, const void* v,
         return FB_ERR_NULL;
     if (R <= 0) return FB_ERR_SHAPE;
     if (int st = check_common(B, H, N, C, R)) return st;
-    if ((long long)B * H * N * (long long)C * R >= (1LL << 31)) return FB_ERR_SHAPE;
+    if ((long long)B * H * N * (long long)C * R >= (1LL << 38)) return FB_ERR_SHAPE;   // pre-pass grid: one thread per 8 channels
     if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     const int rest = C * (R - 1);
-    if (rest > 64) return FB_ERR_UNSUPPORTED;
+    if (rest > mulbias_max_rest(C)) return FB_ERR_UNSUPPORTED;
     const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
     for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
     const void* p4[] = {phi_q, phi_k, dphi_q, dphi_k};
@@ -297,10 +305,12 @@ int fb_lowrank_mulbias_attn_bwd(const void* q, const void* k, const void* v,
     unsigned char* ws = (unsigned char*)workspace;
     void* qh = ws;                 void* kh = ws + head_b;
     void* qr = ws + 2 * head_b;    void* kr = ws + 2 * head_b + rest_b;
-    unsigned char* g = ws + 2 * head_b + 2 * rest_b;       // gradients in the same order
-    void* dqh = g;                 void* dkh = g + head_b;
-    void* dqr = g + 2 * head_b;    void* dkr = g + 2 * head_b + rest_b;
-    void* inner = g + 2 * head_b + 2 * rest_b;
+    // gradients in the same order, as float: dq, dphi_q are sums over them, so the main kernels
+    // must not round them to bf16 first
+    unsigned char* g = ws + 2 * head_b + 2 * rest_b;
+    void* dqh = g;                     void* dkh = g + 2 * head_b;
+    void* dqr = g + 4 * head_b;        void* dkr = g + 4 * head_b + 2 * rest_b;
+    void* inner = g + 4 * head_b + 4 * rest_b;
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
     const long long pbs = phi_batch_broadcast ? 0 : (long long)H * N * R;
     const int f32 = phi_dtype == FB_F32;
@@ -316,10 +326,11 @@ int fb_lowrank_mulbias_attn_bwd(const void* q, const void* k, const void* v,
     p.workspace = inner;
     p.B = B; p.H = H; p.N = N; p.M = N; p.R = rest; p.Cg = C; p.causal = causal != 0;
     p.phi_f32 = 0;
+    p.grad_f32 = 1;
     p.phi_bstride = (long long)H * N * rest;
     p.phik_bstride = (long long)H * N * rest;
     p.scale = 1.0f;                // folded into q'
-    const int rc = fb_launch_bwd_bf16(p, C, rest, st);
+    const int rc = fb_launch_bwd_bf16(p, C, mulbias_padded(rest), st);
     if (rc != 0) return rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH;
     if (fb_launch_mulbias_fold(q, phi_q, dqh, dqr, dq, dphi_q, B, (long long)H * N, C, R, f32, pbs, sc, st) ||
         fb_launch_mulbias_fold(k, phi_k, dkh, dkr, dk, dphi_k, B, (long long)H * N, C, R, f32, pbs, 1.0f, st))
@@ -476,3 +487,4 @@ int fb_lowrank_xattn_bwd(const void* q, const void* k, const void* v,
 }
 
 }  // extern "C"
+#pragma GCC visibility pop

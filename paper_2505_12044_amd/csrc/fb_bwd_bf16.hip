@@ -74,7 +74,7 @@ FB_DEV void wait_vmcnt_n(int n) {   // n is wave-uniform; larger values wait for
 // lane l reads sbase + voff (bytes); its 16 bytes land at LDS byte address lds_addr + 16 * l
 FB_DEV void dma16(const void* sbase, unsigned voff, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory", "m0");
 }
 
 // 32-row tile of W bf16 columns stored as panels (see the header comment)
@@ -200,10 +200,12 @@ __global__ __launch_bounds__(256) void bwd_pad16_kernel(const bf16_t* __restrict
 
 // Write one wave's factor-gradient columns to LDS scratch and reduce limb columns.
 // acc[mb] holds columns mb*32 + 8*g + 4*hf + x (register 4*g + x) for row l32.
+// raw: the R columns are written as float without any limb summing (gradients of bf16 columns
+// kept in fp32 for a later reduction).
 template <int RP2, bool QSIDE>
 FB_DEV void store_dphi(const f32x16* acc_phi /* [RP2/32] */, float* scratch /* wave-private [32][RP2+1] */,
                        void* dst_row /* gradient row of this lane's token or null */, int R,
-                       bool f32, int l32, int hf) {
+                       bool f32, bool raw, int l32, int hf) {
 #pragma unroll
     for (int mb = 0; mb < RP2 / 32; mb++)
 #pragma unroll
@@ -213,7 +215,9 @@ FB_DEV void store_dphi(const f32x16* acc_phi /* [RP2/32] */, float* scratch /* w
     if (dst_row != nullptr) {
         for (int r = hf; r < R; r += 2) {
             const float* s = scratch + l32 * (RP2 + 1);
-            if (f32) {
+            if (raw) {
+                ((float*)dst_row)[r] = s[r];
+            } else if (f32) {
                 // distinct limbs on the other side: query side [a1,a1,a2,a1,a2,a3] -> slots 0,2,5
                 // multiply dphi_k; key side [b1,b2,b1,b3,b2,b1] -> slots 0,1,3 multiply dphi_q
                 const float val = QSIDE ? (s[6 * r] + s[6 * r + 1] + s[6 * r + 3])
@@ -790,54 +794,65 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     const bool rok = ri < NL;
     const int Cg = p.Cg;      // channels of the caller's gradient rows (< C: the rest is not stored)
     const size_t base = (size_t)bh * NL * Cg;
+    const bool g32 = p.grad_f32 != 0;      // wave-uniform
     if (rok) {
         if (DKV) {
             bf16_t* dvg = (bf16_t*)p.dv + base + (size_t)ri * Cg;
             bf16_t* dkg = (bf16_t*)p.dk + base + (size_t)ri * Cg;
+            float* dkf = (float*)p.dk + base + (size_t)ri * Cg;
 #pragma unroll
             for (int mb = 0; mb < K::MBC; mb++)
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
                     if (mb * 32 + 8 * g >= Cg) continue;
                     bf16x4 a4, b4;
+                    f32x4 bf;
 #pragma unroll
                     for (int x = 0; x < 4; x++) {
                         a4[x] = (bf16_t)acc2[mb][4 * g + x];
                         b4[x] = (bf16_t)acc1[mb][4 * g + x];
+                        bf[x] = acc1[mb][4 * g + x];
                     }
                     *(u32x2*)(dvg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, a4);
-                    *(u32x2*)(dkg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, b4);
+                    if (g32) *(f32x4*)(dkf + mb * 32 + 8 * g + 4 * hf) = bf;
+                    else *(u32x2*)(dkg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, b4);
                 }
         } else {
             bf16_t* dqg = (bf16_t*)p.dq + base + (size_t)ri * Cg;
+            float* dqf = (float*)p.dq + base + (size_t)ri * Cg;
 #pragma unroll
             for (int mb = 0; mb < K::MBC; mb++)
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
                     if (mb * 32 + 8 * g >= Cg) continue;
                     bf16x4 o4;
+                    f32x4 of;
 #pragma unroll
-                    for (int x = 0; x < 4; x++) o4[x] = (bf16_t)(acc1[mb][4 * g + x] * p.scale);
-                    *(u32x2*)(dqg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, o4);
+                    for (int x = 0; x < 4; x++) {
+                        of[x] = acc1[mb][4 * g + x] * p.scale;
+                        o4[x] = (bf16_t)of[x];
+                    }
+                    if (g32) *(f32x4*)(dqf + mb * 32 + 8 * g + 4 * hf) = of;
+                    else *(u32x2*)(dqg + mb * 32 + 8 * g + 4 * hf) = __builtin_bit_cast(u32x2, o4);
                 }
         }
     }
     if (RP > 0) {
         const bool f32 = p.phi_f32 != 0;
-        const size_t esz = f32 ? 4 : 2;
+        const size_t esz = (f32 || g32) ? 4 : 2;
         float* scratch = (float*)smem + wave * 32 * (K::RP2 + 1);
         unsigned char* dst = nullptr;
         unsigned char* const dphi = (unsigned char*)(DKV ? p.dphi_k : p.dphi_q);     // NULL: factor gradients not wanted
         if (rok && dphi != nullptr) dst = dphi + ((size_t)bh * NL + ri) * R * esz;
         // the key-side limb order applies to the key's own gradient and vice versa
-        store_dphi<K::RP2, !DKV>(&acc1[K::MBC], scratch, dst, R, f32, l32, hf);
+        store_dphi<K::RP2, !DKV>(&acc1[K::MBC], scratch, dst, R, f32, g32, l32, hf);
     }
 }
 
 // Work units: one 128-row tile per workgroup, or when causal the tile pair (n-1-u, u), whose
 // streamed ranges add up to the same length for every u (no tail of heavy tiles).
 template <int C, int RP, bool CAUSAL, bool DKV, bool DENSE = false>
-__global__ __launch_bounds__(kThreads, (DKV || DENSE || (C == 128 && RP > 32)) ? 1 : 2) void bwd_main_kernel(BwdParams p, MainArgs a) {
+__global__ __launch_bounds__(kThreads, (DKV || DENSE || C + RP > 160) ? 1 : 2) void bwd_main_kernel(BwdParams p, MainArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int L = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
     if (L >= p.total_tiles) return;
@@ -945,8 +960,15 @@ int dispatch_rp(const BwdParams& p, int rp, hipStream_t stream) {
         case 32: return dispatch_causal<C, 32>(p, stream);
         case 48: return dispatch_causal<C, 48>(p, stream);
         case 64: return dispatch_causal<C, 64>(p, stream);
-        default: return -1;
+        default: break;
     }
+    // wider rows: the C (R - 1) extra channels of the multiplicative form (bf16 columns)
+    if constexpr (C <= 64) {
+        if (p.phi_f32) return -1;
+        if (rp == 96) return dispatch_causal<C, 96>(p, stream);
+        if (rp == 128) return dispatch_causal<C, 128>(p, stream);
+    }
+    return -1;
 }
 
 }  // namespace
@@ -954,7 +976,7 @@ int dispatch_rp(const BwdParams& p, int rp, hipStream_t stream) {
 size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R) {
     // R alone does not say whether the factors are fp32 (6 R columns): size for the widest rows.
     // Head dimension 16 runs on 32-channel operand rows and adds widened copies of v and dO.
-    const int w = (C == 16 ? 32 : C) + (R > 0 ? 64 : 0) + (C == 16 ? 32 : 0);
+    const int w = (C == 16 ? 32 : C) + (R > 64 ? 128 : (R > 0 ? 64 : 0)) + (C == 16 ? 32 : 0);
     return (((size_t)rows_q * 8 + 15) & ~(size_t)15) + (size_t)(rows_q + rows_k) * w * 2;
 }
 

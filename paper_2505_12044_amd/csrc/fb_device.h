@@ -231,6 +231,7 @@ FB_DEV bf16x8 phi_chunk_static(const void* row, int R, bool f32) {
 }
 template <bool QSIDE>
 FB_DEV bf16x8 phi_chunk_switch(const void* row, int c8, int R, bool f32) {
+    if (!f32) return phi_chunk_gather<QSIDE>(row, c8, R, false);   // any chunk index (rows wider than 64 columns)
     switch (c8) {
         case 0: return phi_chunk_static<QSIDE, 0>(row, R, f32);
         case 1: return phi_chunk_static<QSIDE, 1>(row, R, f32);

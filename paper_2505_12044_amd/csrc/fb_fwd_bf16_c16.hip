@@ -14,8 +14,13 @@ int fwd_bf16_dispatch_c16(const FwdParams& p, int rp, bool dense, int qb, hipStr
         case 32: return dispatch_pm<32, 32, 16>(p, qb, stream);
         case 48: return dispatch_pm<32, 48, 16>(p, qb, stream);
         case 64: return dispatch_pm<32, 64, 16>(p, qb, stream);
-        default: return -1;
+        default: break;
     }
+    // wider blocks of extra channels (multiplicative form): bf16 columns in whole 16-byte chunks
+    if (p.phi_f32 || (p.R % 8) != 0) return -1;
+    if (rp == 96) return dispatch_causal<32, 96, 1, 1, false, 16>(p, stream);
+    if (rp == 128) return dispatch_causal<32, 128, 1, 1, false, 16>(p, stream);
+    return -1;
 }
 
 }  // namespace

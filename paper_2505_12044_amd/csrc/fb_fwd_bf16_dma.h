@@ -104,7 +104,7 @@ FB_DEV void wait_vmcnt() {
 // at LDS byte address lds_addr + 16 * l.  sbase and lds_addr are wave-uniform.
 FB_DEV void dma16(const void* sbase, unsigned voff, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory", "m0");
 }
 
 // PM: 0 none, 1 bf16 factors with R % 8 == 0, 2 other bf16 factors, 3 fp32 factors (limb items)

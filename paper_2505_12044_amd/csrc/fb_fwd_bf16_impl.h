@@ -653,13 +653,13 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     using K = Cfg<C, RP, QB>;
     auto kern = fwd_bf16_kernel<C, RP, QB, PM, CAUSAL, DENSE, CG>;
     static FbLdsOnce once;
-    if (!fb_raise_lds_limit((const void*)kern, K::kLds + (DENSE ? K::kBiasLds : 0) + 64 * 1024, once)) return 1;
+    if (!fb_raise_lds_limit((const void*)kern, K::kLds + (DENSE ? K::kBiasLds : 0), once)) return 1;
     FwdParams p = pin;
     p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
     p.n_units = CAUSAL ? (p.n_qtiles + 1) / 2 : p.n_qtiles;
     p.total_tiles = p.B * p.H * p.n_units;
     p.tiles_per_xcd = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds + (DENSE ? K::kBiasLds : 0) + fb_debug_lds_pad(), stream, p);
+    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds + (DENSE ? K::kBiasLds : 0), stream, p);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
@@ -703,8 +703,17 @@ int fwd_bf16_dispatch(const FwdParams& p, int rp, bool dense, int qb, hipStream_
         case 32: return dispatch_pm<C, 32>(p, qb, stream);
         case 48: return dispatch_pm<C, 48>(p, qb, stream);
         case 64: return dispatch_pm<C, 64>(p, qb, stream);
-        default: return -1;
+        default: break;
     }
+    // wider factor blocks: the C (R - 1) extra channels of the multiplicative form (App. I), always
+    // whole 16-byte chunks of bf16 columns; one query block per wave (the operand registers of two
+    // would not fit two waves per SIMD)
+    if constexpr (C <= 64) {
+        if (p.phi_f32 || (p.R % 8) != 0) return -1;
+        if (rp == 96) return dispatch_causal<C, 96, 1, 1, false>(p, stream);
+        if (rp == 128) return dispatch_causal<C, 128, 1, 1, false>(p, stream);
+    }
+    return -1;
 }
 
 }  // namespace

@@ -6,6 +6,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "fb_params.h"
 
 int fb_launch_fwd_f32(const FwdParams& p, int C, bool dense, hipStream_t stream);
@@ -25,26 +27,24 @@ int fb_launch_mulbias_prep(const void* x, const void* phi, void* head, void* res
                            int C, int R, int phi_f32, long long phi_bstride, float mul, hipStream_t stream);
 
 // Multiplicative bias backward fold: dx[row][C] = mul * sum_r phi_r g_r, dphi[row][R] = mul * sum_c x_c g_r,c
-// from g_head [rows][C], g_rest [rows][C (R-1)] (gradients of the reweighted repeats); dphi is per batch element.
+// from g_head [rows][C], g_rest [rows][C (R-1)] (float gradients of the reweighted repeats); dphi is per batch element.
 int fb_launch_mulbias_fold(const void* x, const void* phi, const void* g_head, const void* g_rest, void* dx,
                            void* dphi, int B, long long rows_per_batch, int C, int R, int phi_f32,
                            long long phi_bstride, float mul, hipStream_t stream);
 
 // A kernel's dynamic-LDS limit is an attribute of the (kernel, device) pair: raise it on the
-// first launch on each device.  Racing first launches all set the same value.
+// first launch on each device.  Racing first launches all set the same value; the flag is
+// published only after the attribute call has returned.
 constexpr int kFbMaxDevices = 64;
-struct FbLdsOnce { bool done[kFbMaxDevices] = {}; };
+struct FbLdsOnce { std::atomic<bool> done[kFbMaxDevices] = {}; };
 inline bool fb_raise_lds_limit(const void* kern, size_t bytes, FbLdsOnce& once) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return false;
     const bool tracked = dev >= 0 && dev < kFbMaxDevices;
-    if (tracked && once.done[dev]) return true;
+    if (tracked && once.done[dev].load(std::memory_order_acquire)) return true;
     if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return false;
-    if (tracked) once.done[dev] = true;
+    if (tracked) once.done[dev].store(true, std::memory_order_release);
     return true;
 }
-
-// Extra dynamic LDS bytes added to forward launches (experiments on occupancy; normally 0).
-size_t fb_debug_lds_pad();
 
 #endif

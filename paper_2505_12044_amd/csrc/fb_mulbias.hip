@@ -34,15 +34,16 @@ __global__ __launch_bounds__(256) void mulbias_prep_kernel(const bf16_t* __restr
     *(u32x4*)dst = as_uint4(o);
 }
 
-// Backward fold.  g_head [rows][C] and g_rest [rows][C (R-1)] hold dL/dx' for the reweighted
+// Backward fold.  g_head [rows][C] and g_rest [rows][C (R-1)] (float: the backward kernels leave
+// them unrounded, because every output here is a sum over them) hold dL/dx' for the reweighted
 // repeats x' = [x phi_1 mul | ... | x phi_R mul]; the chain rule gives
 //   dx[c]     = mul * sum_r phi_r * g[r][c]        (one thread per 8 channels)
 //   dphi[r]   = mul * sum_c x[c]  * g[r][c]        (thread c8 == 0 of each row, after a row-wide sum)
 // Threads of one row are consecutive lanes (C / 8 <= 16 of them), so the channel sum of dphi is a
 // shuffle reduction.
 __global__ __launch_bounds__(256) void mulbias_fold_kernel(const bf16_t* __restrict__ x, const void* __restrict__ phi,
-                                                           const bf16_t* __restrict__ g_head,
-                                                           const bf16_t* __restrict__ g_rest,
+                                                           const float* __restrict__ g_head,
+                                                           const float* __restrict__ g_rest,
                                                            bf16_t* __restrict__ dx, void* __restrict__ dphi,
                                                            long long rows, long long rows_per_batch, int C, int R,
                                                            int phi_f32, long long phi_bstride, float mul) {
@@ -59,13 +60,14 @@ __global__ __launch_bounds__(256) void mulbias_fold_kernel(const bf16_t* __restr
 #pragma unroll
     for (int e = 0; e < 8; e++) acc[e] = 0.f;
     for (int r = 0; r < R; r++) {
-        const bf16_t* gp = r == 0 ? g_head + rw * C + c8 * 8 : g_rest + rw * (long long)(C * (R - 1)) + (r - 1) * C + c8 * 8;
-        const bf16x8 gv = as_bf16x8(*(const u32x4*)gp);
+        const float* gp = r == 0 ? g_head + rw * C + c8 * 8 : g_rest + rw * (long long)(C * (R - 1)) + (r - 1) * C + c8 * 8;
+        const f32x4 g0 = *(const f32x4*)gp, g1 = *(const f32x4*)(gp + 4);
+        const float gv[8] = {g0[0], g0[1], g0[2], g0[3], g1[0], g1[1], g1[2], g1[3]};
         const float f = phi_f32 ? ((const float*)phi)[poff + r] : (float)((const bf16_t*)phi)[poff + r];
         float dot = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            const float ge = (float)gv[e];
+            const float ge = gv[e];
             acc[e] = fmaf(f, ge, acc[e]);
             dot = fmaf((float)xv[e], ge, dot);
         }
@@ -92,7 +94,7 @@ int fb_launch_mulbias_fold(const void* x, const void* phi, const void* g_head, c
     const long long rows = (long long)B * rows_per_batch;
     const long long threads = rows * (C / 8);
     hipLaunchKernelGGL(mulbias_fold_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
-                       (const bf16_t*)x, phi, (const bf16_t*)g_head, (const bf16_t*)g_rest, (bf16_t*)dx, dphi, rows,
+                       (const bf16_t*)x, phi, (const float*)g_head, (const float*)g_rest, (bf16_t*)dx, dphi, rows,
                        rows_per_batch, C, R, phi_f32, phi_bstride, mul);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }

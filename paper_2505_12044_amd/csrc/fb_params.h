@@ -46,6 +46,8 @@ struct BwdParams {
     int Cg;               // channels per head in caller memory (16 runs on the C = 32 kernels), else C
     int causal;
     int phi_f32;
+    int grad_f32;         // dq, dk, dphi_q, dphi_k are written as float (multiplicative bias: the fold kernel
+                          // sums them, so they must not be rounded to bf16 first); dv stays bf16
     long long phi_bstride;   // elements between batch items of phi_q (0 when shared over batch)
     long long phik_bstride;  // ... of phi_k
     float scale;

@@ -9,7 +9,7 @@ import torch
 
 from oracle import fb_oracle as O
 from paper_2505_12044_amd import api, workloads as W
-from tests._gpu_util import TOL, dev, host, max_abs
+from tests._gpu_util import TOL, check_fwd, check_grad, dev, host, max_abs
 
 pytestmark = pytest.mark.gpu
 
@@ -38,17 +38,14 @@ def test_alibi_small(N, C, causal):
     if not causal:
         slopes = slopes * np.float32(0.05)
     out, lse = _run(q, k, v, slopes, causal)
-    go, gl = host(out), host(lse)
-    assert np.isfinite(go).all() and np.isfinite(gl).all()
-    eo = el = 0.0
+    ro = np.empty((B, H, N, C)); rl = np.empty((B, H, N))
     for b in range(B):
         for h in range(H):
             bias = O.alibi_bias(float(slopes[h]), N)
-            ro, rl = O.attention_with_bias(q[b, h], k[b, h], v[b, h], bias, causal=causal)
-            eo = max(eo, max_abs(go[b, h], ro))
-            el = max(el, max_abs(gl[b, h], rl))
-    print(f"alibi in-kernel N{N} C{C} causal={causal}: out err {eo:.3e}, lse err {el:.3e}", flush=True)
-    assert eo <= TOL["bf16"] and el <= TOL["bf16"]
+            ro[b, h], rl[b, h] = O.attention_with_bias(q[b, h], k[b, h], v[b, h], bias, causal=causal)
+    label = f"alibi in-kernel N{N} C{C} causal={causal}"
+    check_fwd(label, "out", host(out), ro)
+    check_fwd(label, "lse", host(lse), rl)
 
 
 def test_alibi_matches_explicit_fp32_factors():
@@ -85,6 +82,9 @@ def test_alibi_long_sequence_sampled_rows():
     assert eo <= TOL["bf16"] and el <= TOL["bf16"]
 
 
+BWD_DATA_SCALED = {}     # (N, C, causal) -> gradients whose bound scales with the data
+
+
 @pytest.mark.parametrize("C", [16, 64, 128])
 @pytest.mark.parametrize("N,causal", [(1, True), (200, True), (515, True), (384, False)])
 def test_alibi_backward_small(N, C, causal):
@@ -102,17 +102,16 @@ def test_alibi_backward_small(N, C, causal):
     out, lse = api.fb_alibi_attn_fwd(*d, ts, causal=causal)
     grads = api.fb_alibi_attn_bwd(*d, ts, out, lse, dev(dout, "bf16"), causal=causal)
     torch.cuda.synchronize()
-    worst = 0.0
+    refs = [np.empty((B, H, N, C)) for _ in range(3)]
     for b in range(B):
         for h in range(H):
             bias = O.alibi_bias(float(slopes[h]), N)
             ref = O.attention_with_bias_grads(q[b, h], k[b, h], v[b, h], bias, dout[b, h], causal=causal)
-            for name, g, r in zip(("dq", "dk", "dv"), grads, ref):
-                gh = host(g[b, h])
-                assert np.isfinite(gh).all(), name
-                worst = max(worst, max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5))
-    print(f"alibi in-kernel bwd N{N} C{C} causal={causal}: worst scaled err {worst:.3e}", flush=True)
-    assert worst <= GRAD_TOL
+            for dst, r in zip(refs, ref):
+                dst[b, h] = r
+    label = f"alibi in-kernel bwd N{N} C{C} causal={causal}"
+    for name, g, r in zip(("dq", "dk", "dv"), grads, refs):
+        check_grad(label, name, host(g), r, data_scaled=name in BWD_DATA_SCALED.get((N, C, causal), ()))
 
 
 def test_alibi_backward_matches_factor_tensor_path_at_full_size():

@@ -14,7 +14,7 @@ import torch
 
 from oracle import fb_oracle as O
 from paper_2505_12044_amd import api, workloads as W
-from tests._gpu_util import GRAD_TOL, host, max_abs, workload_to_device
+from tests._gpu_util import GRAD_TOL, check_grad, host, max_abs, workload_to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -30,25 +30,19 @@ def _run_bwd(w):
     return out, lse, grads
 
 
-def _check(w, relative_phi=False):
+def _check(w, relative_phi=False, data_scaled=()):
+    """data_scaled: names of the gradients of this case whose bound scales with the data (see the
+    module docstring); every other gradient is held to the flat 5e-2."""
     _, _, grads = _run_bwd(w)
     ref = O.batched_attention_lowrank_grads(w.q, w.k, w.v, w.phi_q, w.phi_k, w.dout, causal=w.causal)
-    msgs = []
-    worst = 0.0
+    label = f"bwd {w.name} B{w.B} H{w.H} N{w.N} C{w.C} R{w.R} {w.phi_dtype} causal={w.causal}"
     for name, g, r in zip(NAMES, grads, ref):
         if g is None:
             continue
-        gh = host(g)
-        assert np.isfinite(gh).all(), name
-        err = max_abs(gh, r)
         if relative_phi and name.startswith("dphi"):
-            err = err / max(1.0, float(np.max(np.abs(r))))
+            check_grad(label, name, host(g), r, gain=max(1.0, float(np.max(np.abs(r)))))
         else:
-            err = err / max(1.0, float(np.max(np.abs(r))) / 2.5)
-        msgs.append(f"{name} {err:.3e} (max|ref| {np.max(np.abs(r)):.2f})")
-        worst = max(worst, err)
-    print(f"bwd {w.name} B{w.B} H{w.H} N{w.N} C{w.C} R{w.R} causal={w.causal}: " + ", ".join(msgs), flush=True)
-    assert worst <= GRAD_TOL
+            check_grad(label, name, host(g), r, data_scaled=name in data_scaled)
 
 
 CASES = [
@@ -73,14 +67,24 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("name,ov", CASES)
-def test_bwd_small(name, ov):
-    _check(W.make_workload(name, with_dout=True, **ov))
+# case index -> gradients whose bound scales with the data.  Measured: every dq, dk, dv of every case
+# and the factor gradients of all other cases are inside the flat 5e-2.  The factor gradients of
+# these three short, peaked-attention cases reach magnitudes of 7 to 15 and miss the flat bound by
+# a hair to a factor of two (0.052, 0.051, 0.093: 0.3 - 1.4 % of the largest entry).
+DATA_SCALED = {1: ("dphi_q", "dphi_k"), 2: ("dphi_q", "dphi_k"), 8: ("dphi_q", "dphi_k")}
+
+
+@pytest.mark.parametrize("idx", range(len(CASES)))
+def test_bwd_small(idx):
+    name, ov = CASES[idx]
+    _check(W.make_workload(name, with_dout=True, **ov), data_scaled=DATA_SCALED.get(idx, ()))
 
 
 @pytest.mark.parametrize("N", [1, 33, 129])
 def test_bwd_edge_lengths(N):
-    _check(W.make_workload("long_train", with_dout=True, B=1, H=1, N=N, C=64, R=8, causal=True))
+    # N = 129 causal: dphi_k reaches 8.8 and misses the flat bound by 9 % (0.054)
+    scaled = ("dphi_q", "dphi_k") if N == 129 else ()
+    _check(W.make_workload("long_train", with_dout=True, B=1, H=1, N=N, C=64, R=8, causal=True), data_scaled=scaled)
     _check(W.make_workload("long_train", with_dout=True, B=1, H=1, N=N, C=64, R=8))
 
 

@@ -7,7 +7,7 @@ import torch
 
 from oracle import fb_oracle as O
 from paper_2505_12044_amd import api, workloads as W
-from tests._gpu_util import GRAD_TOL, dev, host, max_abs
+from tests._gpu_util import GRAD_TOL, check_grad, dev, host, max_abs
 
 pytestmark = pytest.mark.gpu
 
@@ -24,8 +24,12 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("B,H,N,C,causal,shared", CASES)
-def test_dense_backward(B, H, N, C, causal, shared):
+DATA_SCALED = {}     # case index -> gradients whose bound scales with the data
+
+
+@pytest.mark.parametrize("idx", range(len(CASES)))
+def test_dense_backward(idx):
+    B, H, N, C, causal, shared = CASES[idx]
     rng = np.random.default_rng(7000 + N + C + (3 if causal else 0))
     rd = lambda shape: W.round_bf16(rng.standard_normal(shape).astype(np.float32))
     q, k, v, dout = rd((B, H, N, C)), rd((B, H, N, C)), rd((B, H, N, C)), rd((B, H, N, C))
@@ -35,17 +39,12 @@ def test_dense_backward(B, H, N, C, causal, shared):
     out, lse = api.fb_dense_bias_attn_fwd(*d, db, causal=causal)
     dq, dk, dv, dbias = api.fb_dense_bias_attn_bwd(*d, db, out, lse, dev(dout, "bf16"), causal=causal)
     torch.cuda.synchronize()
-    worst = 0.0
     for b in range(B):
         for h in range(H):
             ref = O.attention_with_bias_grads(q[b, h], k[b, h], v[b, h], bias[0 if shared else b, h], dout[b, h],
                                               causal=causal)
+            label = f"dense bwd#{idx} B{B} H{H} N{N} C{C} causal={causal} shared={shared} (b,h)=({b},{h})"
             for name, g, r in zip(("dq", "dk", "dv", "dbias"), (dq, dk, dv, dbias), ref):
-                gh = host(g[b, h])
-                assert np.isfinite(gh).all(), name
-                e = max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5)
-                worst = max(worst, e)
+                check_grad(label, name, host(g[b, h]), r, data_scaled=name in DATA_SCALED.get(idx, ()))
             if causal:
                 assert float(np.abs(np.triu(host(dbias[b, h]), 1)).max()) == 0.0
-    print(f"dense bwd B{B} H{H} N{N} C{C} causal={causal} shared={shared}: worst scaled err {worst:.3e}", flush=True)
-    assert worst <= GRAD_TOL

@@ -9,7 +9,7 @@ import torch
 
 from oracle import fb_oracle as O
 from paper_2505_12044_amd import api, workloads as W
-from tests._gpu_util import GRAD_TOL, TOL, dev, host, max_abs
+from tests._gpu_util import GRAD_TOL, TOL, check_fwd, check_grad, dev, host, max_abs
 
 pytestmark = pytest.mark.gpu
 
@@ -24,19 +24,15 @@ def _check(q, k, v, pq, pk, phi_dtype, causal, tag):
     out, lse = api.fb_lowrank_mulbias_attn_fwd(dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"),
                                                dev(pq, phi_dtype), dev(pk, phi_dtype), causal=causal)
     torch.cuda.synchronize()
-    go, gl = host(out), host(lse)
-    assert np.isfinite(go).all() and np.isfinite(gl).all()
-    eo = el = 0.0
+    ro = np.empty((B, H, N, C)); rl = np.empty((B, H, N))
     for b in range(B):
         for h in range(H):
             bp = 0 if pq.shape[0] == 1 else b
             bias = O.lowrank_bias(pq[bp, h], pk[bp, h])
-            ro, rl = O.attention_with_multiplicative_bias(q[b, h], k[b, h], v[b, h], bias, causal=causal)
-            eo = max(eo, max_abs(go[b, h], ro))
-            el = max(el, max_abs(gl[b, h], rl))
-    print(f"mulbias {tag} B{B} H{H} N{N} C{C} R{pq.shape[-1]} {phi_dtype} causal={causal}: "
-          f"out err {eo:.3e}, lse err {el:.3e}", flush=True)
-    assert eo <= TOL["bf16"] and el <= TOL["bf16"]
+            ro[b, h], rl[b, h] = O.attention_with_multiplicative_bias(q[b, h], k[b, h], v[b, h], bias, causal=causal)
+    label = f"mulbias {tag} B{B} H{H} N{N} C{C} R{pq.shape[-1]} {phi_dtype} causal={causal}"
+    check_fwd(label, "out", host(out), ro)
+    check_fwd(label, "lse", host(lse), rl)
 
 
 @pytest.mark.parametrize("causal", [False, True])
@@ -52,7 +48,10 @@ def test_cosine_bias(N, C, causal):
 
 
 @pytest.mark.parametrize("C,R,phi_dtype", [(128, 1, "bf16"), (64, 1, "f32"), (32, 3, "bf16"), (16, 5, "f32"),
-                                           (16, 2, "bf16"), (32, 2, "f32")])
+                                           (16, 2, "bf16"), (32, 2, "f32"),
+                                           # more than 64 extra channels (padded widths 96 and 128)
+                                           (64, 3, "f32"), (32, 4, "bf16"), (32, 5, "f32"), (16, 6, "bf16"),
+                                           (16, 9, "f32")])
 def test_random_factors_rank_range(C, R, phi_dtype):
     B, H, N = 2, 3, 300
     q, k, v, rng = _qkv(B, H, N, C, seed=8100 + C + R)
@@ -94,19 +93,33 @@ def test_workspace_reuse_and_argument_errors():
     assert torch.equal(o1, o2) and torch.equal(l1, l2)
     with pytest.raises(api.FlashBiasError):
         api.fb_lowrank_mulbias_attn_fwd(*args, workspace=ws[:need - 16])
-    pq3 = dev(rng.standard_normal((B, H, N, 3)).astype(np.float32), "f32")
-    with pytest.raises(api.FlashBiasError):      # C (R - 1) = 128 > 64
-        api.fb_lowrank_mulbias_attn_fwd(args[0], args[1], args[2], pq3, pq3)
+    pq4 = dev(rng.standard_normal((B, H, N, 4)).astype(np.float32), "f32")
+    with pytest.raises(api.FlashBiasError):      # C (R - 1) = 192 > 128
+        api.fb_lowrank_mulbias_attn_fwd(args[0], args[1], args[2], pq4, pq4)
+
+
+# (N, C, R, causal) -> gradients whose bound scales with the data.  Every other gradient of every
+# case is inside the flat 5e-2.  The rank-1 causal case: dphi_q reaches 4.4 and lands at 0.057 (1.3 %
+# of the largest entry; D = rowsum(dO o O) from the bf16 output is the source, not the fold, which
+# sums unrounded fp32 gradients of the repeats).
+BWD_DATA_SCALED = {(423, 32, 1, True): ("dphi_q", "dphi_k")}
 
 
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("N,C,R,phi_dtype,shared", [(300, 64, 2, "f32", True), (257, 32, 3, "bf16", False),
                                                     (200, 16, 5, "f32", False), (384, 128, 1, "f32", False),
-                                                    (130, 16, 2, "bf16", True)])
+                                                    (130, 16, 2, "bf16", True),
+                                                    # a rank-1 shape on which folding the factor gradient from
+                                                    # bf16-rounded gradients of the repeats exceeded the bound
+                                                    (423, 32, 1, "f32", False),
+                                                    # more than 64 extra channels
+                                                    (300, 64, 3, "f32", False), (257, 32, 5, "bf16", True),
+                                                    (200, 16, 7, "f32", False), (333, 32, 4, "f32", False)])
 def test_backward(N, C, R, phi_dtype, shared, causal):
-    """dq, dk, dv, dphi_q, dphi_k against the oracle's chain rule on the definition; 5e-2, scaled
-    with the data where the reference exceeds 2.5 (as for the additive backward)."""
+    """dq, dk, dv, dphi_q, dphi_k against the oracle's chain rule on the definition: flat 5e-2
+    unless the case is listed in BWD_DATA_SCALED."""
     B, H = 2, 2
+    data_scaled = BWD_DATA_SCALED.get((N, C, R, causal), ())
     q, k, v, rng = _qkv(B, H, N, C, seed=8400 + N + C)
     dout = W.round_bf16(rng.standard_normal((B, H, N, C)).astype(np.float32))
     Bp = 1 if shared else B
@@ -124,28 +137,23 @@ def test_backward(N, C, R, phi_dtype, shared, causal):
     out, lse = api.fb_lowrank_mulbias_attn_fwd(*d, causal=causal)
     grads = api.fb_lowrank_mulbias_attn_bwd(*d, out, lse, dev(dout, "bf16"), causal=causal)
     torch.cuda.synchronize()
-    worst = 0.0
-    msg = []
+    refs = [np.empty((B, H, N, C)) for _ in range(3)] + [np.empty((B, H, N, R)) for _ in range(2)]
     for b in range(B):
         for h in range(H):
             bp = 0 if shared else b
             ref = O.attention_multiplicative_lowrank_grads(q[b, h], k[b, h], v[b, h], pq[bp, h], pk[bp, h],
                                                            dout[b, h], causal=causal)
-            for name, g, r in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), grads, ref):
-                gh = host(g[b, h])
-                assert np.isfinite(gh).all(), name
-                err = max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5)
-                if err > worst:
-                    worst = err
-                    msg = [name, b, h, err, float(np.abs(r).max())]
-    print(f"mulbias bwd N{N} C{C} R{R} {phi_dtype} shared={shared} causal={causal}: worst {msg}", flush=True)
-    assert worst <= GRAD_TOL
+            for dst, r in zip(refs, ref):
+                dst[b, h] = r
+    label = f"mulbias bwd N{N} C{C} R{R} {phi_dtype} shared={shared} causal={causal}"
+    for name, g, r in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), grads, refs):
+        check_grad(label, name, host(g), r, data_scaled=name in data_scaled)
 
 
 def test_backward_workspace_and_errors():
     B, H, N, C, R = 1, 1, 64, 64, 2
     need = api.fb_lowrank_mulbias_attn_bwd_workspace_bytes(B, H, N, C, R)
-    assert need == 8 * N * C * R + api.fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, C * (R - 1))
+    assert need == 12 * N * C * R + api.fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, C * (R - 1))
     q, k, v, rng = _qkv(B, H, N, C, seed=8500)
     f = dev(rng.uniform(-1, 1, (B, H, N, R)).astype(np.float32), "f32")
     d = [dev(x, "bf16") for x in (q, k, v)] + [f, f]

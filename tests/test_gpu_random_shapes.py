@@ -8,7 +8,7 @@ import torch
 
 from oracle import fb_oracle as O
 from paper_2505_12044_amd import api, workloads as W
-from tests._gpu_util import GRAD_TOL, TOL, dev, host, max_abs
+from tests._gpu_util import GRAD_TOL, TOL, check_fwd, check_grad, dev, host, max_abs
 
 pytestmark = pytest.mark.gpu
 
@@ -65,11 +65,19 @@ def test_forward_random_shape(B, H, N, C, R, phi_dtype, causal, shared, seed):
     torch.cuda.synchronize()
     ro, rl = O.batched_attention_lowrank(q, k, v, pq if R else np.zeros((1, H, N, 0)),
                                          pk if R else np.zeros((1, H, N, 0)), causal=causal)
-    assert max_abs(host(out), ro) <= TOL["bf16"] and max_abs(host(lse), rl) <= TOL["bf16"]
+    label = f"fwd B{B} H{H} N{N} C{C} R{R} {phi_dtype} causal={causal} shared={shared}"
+    check_fwd(label, "out", host(out), ro)
+    check_fwd(label, "lse", host(lse), rl)
 
 
-@pytest.mark.parametrize("B,H,N,C,R,phi_dtype,causal,shared,seed", _cases(24, 778, True))
-def test_backward_random_shape(B, H, N, C, R, phi_dtype, causal, shared, seed):
+BWD_CASES = _cases(24, 778, True)
+# sweep index -> gradients of that case whose bound scales with the data (entries of magnitude 10+)
+BWD_DATA_SCALED = {}
+
+
+@pytest.mark.parametrize("idx", range(len(BWD_CASES)))
+def test_backward_random_shape(idx):
+    B, H, N, C, R, phi_dtype, causal, shared, seed = BWD_CASES[idx]
     print(f"bwd B{B} H{H} N{N} C{C} R{R} {phi_dtype} causal={causal} shared={shared}", flush=True)
     q, k, v, dout, pq, pk = _inputs(B, H, N, C, R, phi_dtype, shared, seed)
     d = [dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), dev(pq, phi_dtype), dev(pk, phi_dtype)]
@@ -78,13 +86,12 @@ def test_backward_random_shape(B, H, N, C, R, phi_dtype, causal, shared, seed):
     torch.cuda.synchronize()
     zero = np.zeros((1, H, N, 0))
     ref = O.batched_attention_lowrank_grads(q, k, v, pq if R else zero, pk if R else zero, dout, causal=causal)
+    label = f"bwd#{idx} B{B} H{H} N{N} C{C} R{R} {phi_dtype} causal={causal} shared={shared}"
     for name, g, r in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), grads, ref):
         if g is None:
             continue
-        gh = host(g)
-        assert np.isfinite(gh).all(), name
-        err = max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5)
-        assert err <= GRAD_TOL * _factor_gain(name, pq, pk), (name, err)
+        check_grad(label, name, host(g), r, data_scaled=name in BWD_DATA_SCALED.get(idx, ()),
+                   gain=_factor_gain(name, pq, pk))
 
 
 def _xcases(n, seed):
@@ -100,8 +107,13 @@ def _xcases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("B,H,N,M,C,R,phi_dtype,seed", _xcases(16, 779))
-def test_xattn_random_shape(B, H, N, M, C, R, phi_dtype, seed):
+X_CASES = _xcases(16, 779)
+X_DATA_SCALED = {}
+
+
+@pytest.mark.parametrize("idx", range(len(X_CASES)))
+def test_xattn_random_shape(idx):
+    B, H, N, M, C, R, phi_dtype, seed = X_CASES[idx]
     print(f"xattn B{B} H{H} N{N} M{M} C{C} R{R} {phi_dtype}", flush=True)
     rng = np.random.default_rng(seed)
     rd = lambda *s: W.round_bf16(rng.standard_normal(s).astype(np.float32))
@@ -121,13 +133,15 @@ def test_xattn_random_shape(B, H, N, M, C, R, phi_dtype, seed):
             fq = pq[b, h] if R else np.zeros((N, 0))
             fk = pk[b, h] if R else np.zeros((M, 0))
             ro, rl = O.attention_lowrank(q[b, h], k[b, h], v[b, h], fq, fk)
-            assert max_abs(host(out[b, h]), ro) <= TOL["bf16"] and max_abs(host(lse[b, h]), rl) <= TOL["bf16"]
+            label = f"xattn#{idx} N{N} M{M} C{C} R{R} {phi_dtype} (b,h)=({b},{h})"
+            check_fwd(label, "out", host(out[b, h]), ro)
+            check_fwd(label, "lse", host(lse[b, h]), rl)
             ref = O.attention_lowrank_grads(q[b, h], k[b, h], v[b, h], fq, fk, dout[b, h])
             for name, g, r in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), grads, ref):
                 if g is None:
                     continue
-                err = max_abs(host(g[b, h]), r) / max(1.0, float(np.abs(r).max()) / 2.5)
-                assert err <= GRAD_TOL * _factor_gain(name, pq, pk), (name, err)
+                check_grad(label, name, host(g[b, h]), r, data_scaled=name in X_DATA_SCALED.get(idx, ()),
+                           gain=_factor_gain(name, pq, pk))
 
 
 def _dcases(n, seed):
@@ -137,8 +151,13 @@ def _dcases(n, seed):
              int(rng.integers(1 << 30))) for _ in range(n)]
 
 
-@pytest.mark.parametrize("B,H,N,C,causal,shared,seed", _dcases(12, 780))
-def test_dense_random_shape(B, H, N, C, causal, shared, seed):
+D_CASES = _dcases(12, 780)
+D_DATA_SCALED = {}
+
+
+@pytest.mark.parametrize("idx", range(len(D_CASES)))
+def test_dense_random_shape(idx):
+    B, H, N, C, causal, shared, seed = D_CASES[idx]
     print(f"dense B{B} H{H} N{N} C{C} causal={causal} shared={shared}", flush=True)
     rng = np.random.default_rng(seed)
     rd = lambda *s: W.round_bf16(rng.standard_normal(s).astype(np.float32))
@@ -152,10 +171,11 @@ def test_dense_random_shape(B, H, N, C, causal, shared, seed):
         for h in range(H):
             bb = bias[0 if shared else b, h]
             ro, rl = O.attention_with_bias(q[b, h], k[b, h], v[b, h], bb, causal=causal)
-            assert max_abs(host(out[b, h]), ro) <= TOL["bf16"] and max_abs(host(lse[b, h]), rl) <= TOL["bf16"]
+            label = f"dense#{idx} N{N} C{C} causal={causal} shared={shared} (b,h)=({b},{h})"
+            check_fwd(label, "out", host(out[b, h]), ro)
+            check_fwd(label, "lse", host(lse[b, h]), rl)
             ref = O.attention_with_bias_grads(q[b, h], k[b, h], v[b, h], bb, dout[b, h], causal=causal)
             for name, g, r in zip(("dq", "dk", "dv", "dbias"), grads, ref):
                 if name == "dbias" and causal:
                     r = np.tril(r)
-                err = max_abs(host(g[b, h]), r) / max(1.0, float(np.abs(r).max()) / 2.5)
-                assert err <= GRAD_TOL, (name, err)
+                check_grad(label, name, host(g[b, h]), r, data_scaled=name in D_DATA_SCALED.get(idx, ()))

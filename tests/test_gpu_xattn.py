@@ -6,7 +6,7 @@ import torch
 
 from oracle import fb_oracle as O
 from paper_2505_12044_amd import api, workloads as W
-from tests._gpu_util import GRAD_TOL, TOL, dev, host, max_abs
+from tests._gpu_util import GRAD_TOL, TOL, check_fwd, check_grad, dev, host, max_abs
 
 pytestmark = pytest.mark.gpu
 
@@ -38,37 +38,38 @@ def test_xattn_forward(B, H, N, M, C, R, phi_dtype):
     out, lse = api.fb_lowrank_xattn_fwd(dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"),
                                         dev(pq, phi_dtype), dev(pk, phi_dtype))
     torch.cuda.synchronize()
-    eo = el = 0.0
+    ro = np.empty((B, H, N, C)); rl = np.empty((B, H, N))
     for b in range(B):
         for h in range(H):
             bias = O.lowrank_bias(pq[b, h], pk[b, h]) if R else None
-            ro, rl = O.attention_with_bias(q[b, h], k[b, h], v[b, h], bias)
-            eo = max(eo, max_abs(host(out[b, h]), ro))
-            el = max(el, max_abs(host(lse[b, h]), rl))
-    print(f"xattn fwd N{N} M{M} C{C} R{R} {phi_dtype}: out {eo:.3e} lse {el:.3e}", flush=True)
-    assert eo <= TOL["bf16"] and el <= TOL["bf16"]
+            ro[b, h], rl[b, h] = O.attention_with_bias(q[b, h], k[b, h], v[b, h], bias)
+    label = f"xattn fwd N{N} M{M} C{C} R{R} {phi_dtype}"
+    check_fwd(label, "out", host(out), ro)
+    check_fwd(label, "lse", host(lse), rl)
 
 
-@pytest.mark.parametrize("B,H,N,M,C,R,phi_dtype", CASES)
-def test_xattn_backward(B, H, N, M, C, R, phi_dtype):
+# case index -> gradients whose bound scales with the data.  Case 5 has a single key: dv is the sum of
+# all 500 rows of dO, entries up to 50, where bf16 storage of the result alone is off by up to 0.12.
+DATA_SCALED = {5: ("dv",)}
+
+
+@pytest.mark.parametrize("idx", range(len(CASES)))
+def test_xattn_backward(idx):
+    B, H, N, M, C, R, phi_dtype = CASES[idx]
     q, k, v, dout, pq, pk = _problem(B, H, N, M, C, R, phi_dtype, seed=6000 + N + M)
     d = [dev(x, "bf16") for x in (q, k, v)]
     dpq, dpk = dev(pq, phi_dtype), dev(pk, phi_dtype)
     out, lse = api.fb_lowrank_xattn_fwd(*d, dpq, dpk)
     grads = api.fb_lowrank_xattn_bwd(*d, dpq, dpk, out, lse, dev(dout, "bf16"))
     torch.cuda.synchronize()
-    worst = 0.0
     for b in range(B):
         for h in range(H):
             if R:
                 ref = O.attention_lowrank_grads(q[b, h], k[b, h], v[b, h], pq[b, h], pk[b, h], dout[b, h])
             else:
                 ref = O.attention_with_bias_grads(q[b, h], k[b, h], v[b, h], None, dout[b, h])[:3]
-            for g, r in zip(grads, ref):
+            label = f"xattn bwd#{idx} N{N} M{M} C{C} R{R} {phi_dtype} (b,h)=({b},{h})"
+            for name, g, r in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), grads, ref):
                 if g is None:
                     continue
-                gh = host(g[b, h])
-                assert np.isfinite(gh).all()
-                worst = max(worst, max_abs(gh, r) / max(1.0, float(np.abs(r).max()) / 2.5))
-    print(f"xattn bwd N{N} M{M} C{C} R{R} {phi_dtype}: worst scaled err {worst:.3e}", flush=True)
-    assert worst <= GRAD_TOL
+                check_grad(label, name, host(g[b, h]), r, data_scaled=name in DATA_SCALED.get(idx, ()))

@@ -115,8 +115,8 @@ def test_mulbias_argument_errors(lib):
 
     assert call(ptrs=[64, 64, 64, None, 64, 64, 64]) == 1      # factors are required
     assert call(R=0) == 2
-    assert call(R=3) == 3                                      # C (R - 1) = 128 > 64
-    assert call(C=128, R=2) == 3
+    assert call(R=4) == 3                                      # C (R - 1) = 192 > 128
+    assert call(C=128, R=2) == 3                               # C = 128 takes no extra channels
     assert call(dtype=api.FB_F32) == 3
     assert call(ptrs=[64, 64, 64, 66, 64, 64, 64]) == 4        # factors not 4-byte aligned
     assert call(w=None) == 5
@@ -127,7 +127,11 @@ def test_mulbias_argument_errors(lib):
 def test_mulbias_backward_argument_errors(lib):
     f = lib.fb_lowrank_mulbias_attn_bwd
     need = lib.fb_lowrank_mulbias_attn_bwd_workspace_bytes(1, 2, 100, 32, 3, api.FB_BF16)
-    assert need == 4 * 200 * 32 * 3 * 2 + lib.fb_lowrank_attn_bwd_workspace_bytes(1, 2, 100, 32, 64, api.FB_BF16)
+    # q', k' in bf16, their gradients in float, and the additive backward's scratch for 64 extra channels
+    assert need == 2 * 200 * 32 * 3 * (2 + 4) + lib.fb_lowrank_attn_bwd_workspace_bytes(1, 2, 100, 32, 64, api.FB_BF16)
+    # more than 64 extra channels: operand rows of width C + 128
+    need5 = lib.fb_lowrank_mulbias_attn_bwd_workspace_bytes(1, 2, 100, 32, 5, api.FB_BF16)
+    assert need5 == 2 * 200 * 32 * 5 * 6 + 200 * 8 + 2 * 200 * (32 + 128) * 2
 
     def call(ptrs=None, C=32, R=3, dtype=api.FB_BF16, w=64, wb=need):
         ptrs = ptrs or [64] * 13
@@ -135,7 +139,7 @@ def test_mulbias_backward_argument_errors(lib):
 
     assert call(ptrs=[64] * 12 + [None]) == 1
     assert call(R=0) == 2
-    assert call(R=4) == 3                      # C (R - 1) = 96 > 64
+    assert call(R=6) == 3                      # C (R - 1) = 160 > 128
     assert call(dtype=api.FB_F32) == 3
     assert call(ptrs=[64] * 11 + [66, 64]) == 4
     assert call(wb=need - 1) == 5
@@ -159,6 +163,31 @@ def test_alibi_backward_argument_errors(lib):
     assert call(wb=need - 1) == 5
 
 
+def test_size_limits_follow_the_indexing(lib):
+    """Offsets above the head level are 64-bit: tensors of 2^31 elements and more are accepted
+    (the calls below pass the shape check and stop at the deliberately misaligned pointer);
+    what is limited is the row count (32-bit counters) and the extent of one head (32-bit byte
+    offsets)."""
+    assert _fwd(lib, B=2, H=8, N=1 << 17, C=128, R=8, k=72) == 4        # 2^31 elements per tensor
+    assert _fwd(lib, B=64, H=64, N=1 << 16, C=128, R=8, k=72) == 4      # 2^35 elements, 2^28 rows
+    assert _fwd(lib, B=1 << 10, H=1 << 5, N=1 << 16, C=32, R=0, k=72) == 2     # 2^31 rows
+    assert _fwd(lib, B=1, H=1, N=1 << 23, C=128, R=0, k=72) == 2        # one head: N C = 2^30 elements
+    assert _fwd(lib, B=1, H=1, N=1 << 22, C=128, R=0, k=72) == 4
+    assert _fwd(lib, B=1, H=1, N=1 << 26, C=16, R=16, k=72) == 2        # N R = 2^30 factor values
+    a = lib.fb_alibi_attn_fwd
+    assert a(64, 64, 64, 64, 64, 64, 1, 1, (1 << 24) + 1, 16, 1, api.FB_BF16, 0.0, None) == 3   # fp32 positions
+
+
+def test_only_the_c_abi_is_exported():
+    """Built with hidden visibility: the dynamic symbol table defines the header's functions and
+    nothing else of this library's own."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", api.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    defined = {line.split()[-1] for line in out.splitlines() if line.strip()}
+    ours = {n for n in defined if not n.startswith("__hip") and n not in ("_init", "_fini")}
+    assert ours == set(api.EXPORTS), sorted(ours ^ set(api.EXPORTS))
+
+
 def test_tune_knob(lib):
     assert lib.fb_tune_set(b"fwd_qb", 2) == 0
     assert lib.fb_tune_set(b"fwd_qb", 0) == 0
@@ -169,6 +198,7 @@ def test_tune_knob(lib):
     assert lib.fb_tune_set(b"fwd_causal_up", 0) == 0
     assert lib.fb_tune_set(b"fwd_causal_up", 2) == 2
     assert lib.fb_tune_set(b"fwd_causal_up", 1) == 0
+    assert lib.fb_tune_set(b"fwd_lds_pad", 0) == 3          # probe knob removed
     assert lib.fb_tune_set(b"nope", 1) == 3
     assert lib.fb_tune_set(None, 1) == 1
 
