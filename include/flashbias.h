@@ -38,7 +38,8 @@
  *   - Return value: FB_OK or an fb_status for errors detectable on the host (bad argument,
  *     unsupported shape, misalignment, workspace too small, launch failure).  Outputs are
  *     fully overwritten on success and untouched on error.  Thread-safe; the only process-wide
- *     state is the atomic variant selection of fb_tune_set (a test hook).
+ *     state is the atomic variant selection of fb_tune_set (a test hook) and the static scratch
+ *     of fb_lowrank_attn_bwd_noalloc.
  *   - Size limits (FB_ERR_SHAPE beyond them): B H N < 2^31 rows; N C < 2^30 and N R < 2^30
  *     elements inside one head.  Offsets above the head level are 64-bit, so tensors may exceed
  *     2^31 elements.
@@ -59,7 +60,8 @@ typedef enum {
     FB_ERR_UNSUPPORTED = 3,  /* C / R / dtype combination has no kernel             */
     FB_ERR_ALIGN = 4,        /* a pointer is not 16-byte aligned                    */
     FB_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than the size query says  */
-    FB_ERR_LAUNCH = 6        /* the HIP runtime rejected a launch                   */
+    FB_ERR_LAUNCH = 6,       /* the HIP runtime rejected a launch                   */
+    FB_ERR_TOO_LARGE = 7     /* problem needs more scratch than the allocation-free entry point owns */
 } fb_status;
 
 typedef enum { FB_F32 = 0, FB_BF16 = 1 } fb_dtype;
@@ -221,6 +223,31 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
                         int B, int H, int N, int C, int R, int causal,
                         fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
                         float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Allocation-free variant of fb_lowrank_attn_bwd, for callers that cannot allocate device
+ * memory or carry a workspace: code under HIP graph capture, tight serving / training loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace, same kernels, same
+ * (bit-identical) results; the scratch that fb_lowrank_attn_bwd takes from the caller lives in
+ * a static device array of FB_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held
+ * from library load until the process ends.  The call allocates and frees nothing.
+ *   Limit: fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, R, dtype) <= FB_STATIC_SCRATCH_BYTES
+ *   (e.g. B H N <= 86480 rows at C = 128 with factors); larger problems return
+ *   FB_ERR_TOO_LARGE and launch nothing.
+ *   Every call on a GPU uses that GPU's one array: calls that overlap on the same GPU (two
+ *   streams, two threads) race on it and must be serialised by the caller.  Nothing in the
+ *   array has to start at zero (the pre-pass rewrites every byte the main kernels read), so
+ *   calls of different sizes may follow each other freely.
+ */
+#define FB_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+
+int fb_lowrank_attn_bwd_noalloc(const void* q, const void* k, const void* v,
+                                const void* phi_q, const void* phi_k,
+                                const void* out, const float* lse, const void* dout,
+                                void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                                int B, int H, int N, int C, int R, int causal,
+                                fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                                float scale, void* stream);
 
 /*
  * Backward of fb_dense_bias_attn_fwd, the training-side baseline: besides dq, dk, dv it has

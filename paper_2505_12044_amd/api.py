@@ -26,8 +26,10 @@ EXPORTS = (
     "fb_dense_bias_attn_bwd_workspace_bytes", "fb_dense_bias_attn_bwd",
     "fb_lowrank_mulbias_attn_fwd_workspace_bytes", "fb_lowrank_mulbias_attn_fwd",
     "fb_lowrank_mulbias_attn_bwd_workspace_bytes", "fb_lowrank_mulbias_attn_bwd",
-    "fb_alibi_attn_bwd_workspace_bytes", "fb_alibi_attn_bwd",
+    "fb_alibi_attn_bwd_workspace_bytes", "fb_alibi_attn_bwd", "fb_lowrank_attn_bwd_noalloc",
 )
+
+FB_STATIC_SCRATCH_BYTES = 64 << 20     # include/flashbias.h
 
 
 class FlashBiasError(RuntimeError):
@@ -64,6 +66,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_lowrank_attn_bwd_workspace_bytes.argtypes = [ci] * 5 + [ci]
     lib.fb_lowrank_attn_bwd.restype = ci
     lib.fb_lowrank_attn_bwd.argtypes = [vp] * 13 + [ci] * 6 + [ci, ci, ci, cf, vp, sz, vp]
+    lib.fb_lowrank_attn_bwd_noalloc.restype = ci
+    lib.fb_lowrank_attn_bwd_noalloc.argtypes = [vp] * 13 + [ci] * 6 + [ci, ci, ci, cf, vp]
     lib.fb_dense_bias_attn_bwd_workspace_bytes.restype = sz
     lib.fb_dense_bias_attn_bwd_workspace_bytes.argtypes = [ci] * 4 + [ci]
     lib.fb_dense_bias_attn_bwd.restype = ci
@@ -337,6 +341,27 @@ def fb_lowrank_attn_bwd(q, k, v, phi_q, phi_k, out, lse, dout, causal=False, sca
                                  _ptr(workspace), workspace.numel() * workspace.element_size(),
                                  _stream(stream))
     _check(st, "fb_lowrank_attn_bwd")
+    return dq, dk, dv, dpq, dpk
+
+
+def fb_lowrank_attn_bwd_noalloc(q, k, v, phi_q, phi_k, out, lse, dout, grads, causal=False, scale: float = 0.0,
+                                phi_batch_broadcast: Optional[bool] = None, stream=None):
+    """fb_lowrank_attn_bwd on the library's static scratch: the caller passes every output tensor
+    (grads = (dq, dk, dv, dphi_q, dphi_k); the last two None when R = 0 or not wanted) and this
+    wrapper allocates nothing either."""
+    lib = load_library()
+    B, H, N, C = q.shape
+    R = 0 if phi_q is None else phi_q.shape[-1]
+    if phi_batch_broadcast is None:
+        phi_batch_broadcast = phi_q is not None and phi_q.shape[0] == 1 and B > 1
+    phi_code = _dtype_code(phi_q) if phi_q is not None else _dtype_code(q)
+    dq, dk, dv, dpq, dpk = grads
+    st = lib.fb_lowrank_attn_bwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(phi_q), _ptr(phi_k), _ptr(out),
+                                         _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dpq),
+                                         _ptr(dpk), B, H, N, C, R, int(bool(causal)), _dtype_code(q),
+                                         phi_code, int(bool(phi_batch_broadcast)), float(scale),
+                                         _stream(stream))
+    _check(st, "fb_lowrank_attn_bwd_noalloc")
     return dq, dk, dv, dpq, dpk
 
 

@@ -15,6 +15,27 @@ namespace {
 std::atomic<int> g_fwd_qb{0};   // 0 = choose automatically
 std::atomic<int> g_causal_up{1};
 
+// Scratch of the allocation-free entry point: one copy per GPU, resident from module load.  In
+// host code the array's name is only a handle for hipGetSymbolAddress; kernels get the device
+// address obtained there.
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[FB_STATIC_SCRATCH_BYTES];
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device; resolved once per device (racing first
+// calls store the same value).  Returns nullptr on failure.
+void* static_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr != nullptr) return ptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return nullptr;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    return ptr;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int padded_rank(int R, fb_dtype dtype, fb_dtype phi_dtype) {
@@ -80,6 +101,7 @@ const char* fb_status_string(int status) {
         case FB_ERR_ALIGN: return "pointer not 16-byte aligned";
         case FB_ERR_WORKSPACE: return "workspace missing or too small";
         case FB_ERR_LAUNCH: return "kernel launch failed";
+        case FB_ERR_TOO_LARGE: return "problem exceeds the static scratch of the allocation-free entry point";
         default: return "unknown status";
     }
 }
@@ -471,6 +493,24 @@ int fb_lowrank_attn_bwd(const void* q, const void* k, const void* v,
                         float scale, void* workspace, size_t workspace_bytes, void* stream) {
     return lowrank_bwd_impl(q, k, v, phi_q, phi_k, out, lse, dout, dq, dk, dv, dphi_q, dphi_k, B, H, N, N, C, R,
                             causal, dtype, phi_dtype, phi_batch_broadcast, scale, workspace, workspace_bytes,
+                            stream);
+}
+
+int fb_lowrank_attn_bwd_noalloc(const void* q, const void* k, const void* v,
+                                const void* phi_q, const void* phi_k,
+                                const void* out, const float* lse, const void* dout,
+                                void* dq, void* dk, void* dv, void* dphi_q, void* dphi_k,
+                                int B, int H, int N, int C, int R, int causal,
+                                fb_dtype dtype, fb_dtype phi_dtype, int phi_batch_broadcast,
+                                float scale, void* stream) {
+    // shape errors first (the size query is meaningless for them), then the size limit
+    if (int st = check_common(B, H, N, C, R)) return st;
+    const size_t need = bwd_ws_impl(B, H, N, N, C, R);
+    if (need > FB_STATIC_SCRATCH_BYTES) return FB_ERR_TOO_LARGE;
+    void* ws = static_scratch();
+    if (ws == nullptr) return FB_ERR_LAUNCH;
+    return lowrank_bwd_impl(q, k, v, phi_q, phi_k, out, lse, dout, dq, dk, dv, dphi_q, dphi_k, B, H, N, N, C, R,
+                            causal, dtype, phi_dtype, phi_batch_broadcast, scale, ws, FB_STATIC_SCRATCH_BYTES,
                             stream);
 }
 

@@ -36,8 +36,8 @@ def test_header_symbols_exported(lib):
 def test_version_and_status_strings(lib):
     assert lib.fb_version() >= 100
     assert lib.fb_status_string(0) == b"ok"
-    seen = {lib.fb_status_string(i) for i in range(7)}
-    assert len(seen) == 7
+    seen = {lib.fb_status_string(i) for i in range(8)}
+    assert len(seen) == 8
     assert lib.fb_status_string(99) == b"unknown status"
 
 
@@ -176,6 +176,22 @@ def test_size_limits_follow_the_indexing(lib):
     assert _fwd(lib, B=1, H=1, N=1 << 26, C=16, R=16, k=72) == 2        # N R = 2^30 factor values
     a = lib.fb_alibi_attn_fwd
     assert a(64, 64, 64, 64, 64, 64, 1, 1, (1 << 24) + 1, 16, 1, api.FB_BF16, 0.0, None) == 3   # fp32 positions
+
+
+def test_noalloc_backward_host_checks(lib):
+    """The allocation-free backward rejects bad shapes and problems beyond its static scratch on
+    the host, before any device call."""
+    g = lib.fb_lowrank_attn_bwd_noalloc
+    ptrs = [64] * 13
+    assert g(*ptrs, 0, 1, 16, 64, 4, 0, api.FB_BF16, api.FB_BF16, 0, 0.0, None) == 2
+    assert g(*ptrs, 1, 1, 16, 48, 4, 0, api.FB_BF16, api.FB_BF16, 0, 0.0, None) == 3
+    B, H, N, C, R = 4, 16, 4096, 128, 2
+    assert lib.fb_lowrank_attn_bwd_workspace_bytes(B, H, N, C, R, api.FB_BF16) > api.FB_STATIC_SCRATCH_BYTES
+    st = g(*ptrs, B, H, N, C, R, 1, api.FB_BF16, api.FB_F32, 1, 0.0, None)
+    assert st == 7 and b"static scratch" in lib.fb_status_string(st)
+    text = open(HEADER).read()
+    m = re.search(r"#define FB_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << (\d+)\)", text)
+    assert m and int(m.group(1)) << int(m.group(2)) == api.FB_STATIC_SCRATCH_BYTES
 
 
 def test_only_the_c_abi_is_exported():
