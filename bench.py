@@ -1,18 +1,29 @@
 #!/usr/bin/env python3
 """Benchmark of the low-rank-bias attention hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extras] [--no-cpu]
 
 A step is one forward of fb_lowrank_attn_fwd over the workload (inputs resident in HBM).
 Prints ONE JSON line: the headline metric (forward TFLOP/s of the low-rank kernel, algorithmic
 flop 2(2C+R) per visible query-key pair), a `roofline` object for that kernel (HIP-event
-duration per launch on the launch stream against the bf16 dense MFMA peak), a `cpu_baseline`
-object (the float64 oracle timed on a bounded sample on this machine's host cores), and, unless
---no-extras, the dense-bias baseline, the backward and the other workloads as extra fields.
+duration per launch on the launch stream against the bf16 dense MFMA peak, plus the ceiling a
+bare MFMA loop reaches on this chip), a `cpu_baseline` object (the float64 oracle timed on a
+bounded sample on this machine's host cores), and, unless --no-extras, the dense-bias baseline, the
+backward and the other workloads as extra fields.
+
+Timing protocol.  Before anything is timed the kernel is launched back to back for
+`settle_s` seconds (untimed): the chip raises its clocks only under sustained load, and a
+short run otherwise measures the ramp (0.37 ms against 0.31 ms per launch on the headline
+workload).  Then W warm-up steps, then exactly K steps between two synchronisations
+(`ms_per_step`, `value`).  Kernel-level figures are the median of five repeats, each the mean
+HIP-event duration of its launches.  Workloads whose working set fits the 256 MB Infinity
+Cache are also timed "cold": the launches rotate over copies of every tensor that together
+exceed 512 MB, so no launch finds its inputs in cache.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import re
@@ -25,17 +36,25 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# fp32 vector rate without packed operations: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz
+PEAK_VALU_TFLOPS = 78.6
+# vector work of the softmax per (query, key) pair, in fp32-flop equivalents: one multiply-add (2),
+# one exponential at a quarter of the vector rate (4), conversion to bf16 and row sum (2)
+SOFTMAX_FLOP_PER_PAIR = 8
 HEADLINE = "alibi_causal"
+SETTLE_S = 0.3
+REPEATS = 5
+COLD_BYTES = 512 << 20
 PAPER_CONTEXT = ("paper (A100, other hardware, context only): >2x fwd vs best dense-bias "
                  "implementation for vision/language attention, 1.5x Pairformer end to end")
 
 
-def _traffic_from_profile(workload: str):
-    """HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/)."""
-    path = os.path.join(ROOT, "profiles", f"fwd_lowrank_{workload}_hbm_traffic.txt")
+def _profile_field(path_stem: str, field: str):
+    """A figure measured offline with rocprofv3 --pmc and kept in profiles/ (None when absent)."""
+    path = os.path.join(ROOT, "profiles", path_stem)
     try:
         with open(path) as f:
-            m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", f.read(), re.M)
+            m = re.search(rf"^{field}:\s*([0-9.eE+]+)", f.read(), re.M)
         return float(m.group(1)) if m else None
     except OSError:
         return None
@@ -62,7 +81,7 @@ def main() -> int:
     import numpy as np
     import torch
 
-    from paper_2505_12044_amd import api, workloads as W
+    from paper_2505_12044_amd import api, build as fb_build, workloads as W
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -70,6 +89,13 @@ def main() -> int:
     torch.cuda.set_device(0)
     api.load_library()   # fails loudly if the HIP library is missing
     stream = torch.cuda.current_stream()
+    probe = None
+    if os.path.exists(fb_build.PROBE_LIB):
+        probe = ctypes.CDLL(fb_build.PROBE_LIB)
+        probe.fbp_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        probe.fbp_mfma_loop_flop.restype = ctypes.c_double
+        probe.fbp_mfma_loop_flop.argtypes = [ctypes.c_int, ctypes.c_int]
+        probe.fbp_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 
     def dev(x, name):
         t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
@@ -93,14 +119,24 @@ def main() -> int:
                         d["bias"][b, h] = (pq[b, h] @ pk[b, h].T).to(d["q"].dtype)
         return d
 
-    def time_calls(fn, steps, warmup):
-        """Per-launch HIP-event timing on the launch stream; returns (total wall ms between
-        synchronisations, mean event ms per launch)."""
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
+    def stream_handle():
+        return stream.cuda_stream or None
+
+    # ------------------------------------------------------------------ timing helpers
+    def settle(fn, seconds=SETTLE_S):
+        """Untimed back-to-back launches for `seconds`: brings the clocks to their loaded state."""
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
+
+    def timed_region(fn, steps):
+        """Exactly `steps` launches between two synchronisations; per-launch HIP events on the launch
+        stream.  Returns (wall ms of the region, mean event ms per launch)."""
         starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
         ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
             starts[i].record(stream)
@@ -108,8 +144,34 @@ def main() -> int:
             ends[i].record(stream)
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
-        ev = [s.elapsed_time(e) for s, e in zip(starts, ends)]
-        return wall_ms, float(np.mean(ev))
+        return wall_ms, float(np.mean([s.elapsed_time(e) for s, e in zip(starts, ends)]))
+
+    def kernel_ms(fn, steps=None, repeats=REPEATS, do_settle=True):
+        """Median over `repeats` of the mean event duration of `steps` launches (steps chosen so that
+        one repeat lasts about 0.1 s when not given)."""
+        if do_settle:
+            settle(fn)
+        if steps is None:
+            _, est = timed_region(fn, 3)
+            steps = int(min(100, max(3, 100.0 / max(est, 1e-3))))
+        vals = [timed_region(fn, steps)[1] for _ in range(repeats)]
+        return float(np.median(vals)), steps
+
+    def rotating(make_call, tensors, bytes_per_set):
+        """Cold-cache variant of a launch: copies of the tensors that together exceed COLD_BYTES,
+        visited round-robin, so no launch finds its operands in the 256 MB Infinity Cache."""
+        nset = int(max(2, -(-COLD_BYTES // max(1, bytes_per_set)) + 1))
+        sets = [tensors] + [{k: (v.clone() if torch.is_tensor(v) else v) for k, v in tensors.items()}
+                            for _ in range(nset - 1)]
+        state = {"i": 0}
+
+        def call():
+            make_call(sets[state["i"]])
+            state["i"] = (state["i"] + 1) % nset
+        return call, nset, sets
+
+    def tensor_bytes(d):
+        return int(sum(v.numel() * v.element_size() for v in d.values() if torch.is_tensor(v)))
 
     # ------------------------------------------------------------------ headline workload
     if args.probe:
@@ -123,7 +185,8 @@ def main() -> int:
                                 lse=d["lse"], causal=w.causal, stream=stream)
 
     if args.probe:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()   # 1 GiB
+        nbytes = 1 << 30
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         for _ in range(3):
@@ -138,17 +201,35 @@ def main() -> int:
             for _ in range(3):
                 api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], d["out"], d["lse"],
                                         d["dout"], causal=w.causal, workspace=wsb, stream=stream)
-        dst.copy_(src)
+        if probe is not None:
+            probe.fbp_copy(src.data_ptr(), dst.data_ptr(), nbytes, stream_handle())
+        else:
+            dst.copy_(src)
         torch.cuda.synchronize()
-        print(json.dumps({"probe": w.name, "copy_bytes_read": src.numel() * 4,
-                          "copy_bytes_written": src.numel() * 4}))
+        print(json.dumps({"probe": w.name, "copy_bytes_read": nbytes, "copy_bytes_written": nbytes,
+                          "copy_kernel": "copy_kernel (fbp_copy)" if probe is not None else "torch copy_"}))
         return 0
 
-    wall_ms, kern_ms = time_calls(fwd, args.steps, args.warmup)
+    settle(fwd)
+    for _ in range(args.warmup):
+        fwd()
+    wall_ms, ev_first = timed_region(fwd, args.steps)        # the contract's timed region: exactly K steps
     ms_per_step = wall_ms / args.steps
+    reps = [ev_first] + [timed_region(fwd, args.steps)[1] for _ in range(REPEATS - 1)]
+    kern_ms = float(np.median(reps))
     flops = w.fwd_flops()
     tflops = flops / (ms_per_step * 1e-3) / 1e12
     kern_tflops = flops / (kern_ms * 1e-3) / 1e12
+
+    ceiling = None
+    if probe is not None:
+        blocks, iters = 512, 4000         # two workgroups per CU: two waves per SIMD; ~2 ms per launch
+        buf = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+
+        def mfma_loop():
+            probe.fbp_mfma_loop(buf.data_ptr(), blocks, iters, stream_handle())
+        c_ms, _ = kernel_ms(mfma_loop, steps=20)     # settled like every other kernel: sustained rate
+        ceiling = probe.fbp_mfma_loop_flop(blocks, iters) / (c_ms * 1e-3) / 1e12
 
     result = {
         "metric": "low-rank-bias attention fwd TFLOP/s",
@@ -166,6 +247,7 @@ def main() -> int:
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "C": w.C, "R": w.R,
                    "causal": w.causal, "phi_dtype": w.phi_dtype,
                    "flop_per_pair": 2 * (2 * w.C + w.R), "pairs": w.pairs},
+        "settle_s": SETTLE_S,
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {
             "kernel": "low-rank bf16 forward (fwd_bf16_kernel; fwd_bf16_pp_kernel for long non-causal sequences)",
@@ -175,22 +257,38 @@ def main() -> int:
             "unit": "TFLOP/s",
             "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4),
             "ms_per_launch": round(kern_ms, 5),
-            "traffic": _traffic_from_profile(w.name),
+            "ms_per_launch_repeats": [round(x, 5) for x in reps],
+            "traffic": _profile_field(f"fwd_lowrank_{w.name}_hbm_traffic.txt", "traffic_bytes_per_launch"),
         },
         "context": PAPER_CONTEXT,
     }
+    if ceiling is not None:
+        result["roofline"]["measured_ceiling"] = round(ceiling, 1)
+        result["roofline"]["measured_ceiling_kernel"] = ("back-to-back v_mfma_f32_32x32x16_bf16, two waves per "
+                                                         "SIMD, no memory traffic (libfb_bench_probe.so)")
+        result["roofline"]["frac_of_measured_ceiling"] = round(kern_tflops / ceiling, 4)
 
     # ------------------------------------------------------------------ extras
     if not args.no_extras:
+        def unique_bias_bytes(wl):
+            per = wl.N * (wl.N + 1) // 2 if wl.causal else wl.N * wl.N
+            bb = 1 if (wl.bias is not None and wl.bias.shape[0] == 1) else wl.B
+            return bb * wl.H * per * 2
+
         def dense():
             api.fb_dense_bias_attn_fwd(d["q"], d["k"], d["v"], d["bias"], out=d["out"], lse=d["lse"],
                                        causal=w.causal, stream=stream)
-        n = max(10, args.steps // 4)
-        _, dense_ms = time_calls(dense, n, 3)
+        dense_ms, _ = kernel_ms(dense)
         result["dense_bias"] = {
             "ms": round(dense_ms, 5),
-            "bias_GBps": round(w.pairs * 2 / (dense_ms * 1e-3) / 1e9, 1),
-            "pct_of_hbm_peak": round(100 * w.pairs * 2 / (dense_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 2),
+            # bytes of distinct bias entries the launch has to fetch at least once (a bias shared over the
+            # batch counts once), over the launch time: a lower bound on the HBM rate, not a counter
+            "unique_bias_bytes": unique_bias_bytes(w),
+            "unique_bias_GBps": round(unique_bias_bytes(w) / (dense_ms * 1e-3) / 1e9, 1),
+            # bias elements consumed by the MFMA lanes (every batch item re-reads a shared bias, mostly
+            # from L2 / Infinity Cache): NOT an HBM figure
+            "bias_consumed_GBps": round(w.pairs * 2 / (dense_ms * 1e-3) / 1e9, 1),
+            "hbm_bytes_measured": _profile_field(f"fwd_lowrank_{w.name}_hbm_traffic.txt", "dense_traffic_bytes_per_launch"),
             "speedup_lowrank_vs_dense": round(dense_ms / kern_ms, 3),
         }
         dense_bwd_ms = None
@@ -205,7 +303,7 @@ def main() -> int:
             def dense_bwd():
                 api.fb_dense_bias_attn_bwd(d["q"], d["k"], d["v"], d["bias"], d["out"], d["lse"], d["dout"],
                                            causal=w.causal, workspace=wsd, grads=gd, stream=stream)
-            _, dense_bwd_ms = time_calls(dense_bwd, max(5, n // 2), 2)
+            dense_bwd_ms, _ = kernel_ms(dense_bwd)
             del gd, wsd
         d.pop("bias", None)
         torch.cuda.empty_cache()
@@ -218,7 +316,7 @@ def main() -> int:
             def jit():
                 api.fb_alibi_attn_fwd(d["q"], d["k"], d["v"], slopes, out=d["out"], lse=d["lse"],
                                       causal=w.causal, stream=stream)
-            _, jit_ms = time_calls(jit, n, 3)
+            jit_ms, _ = kernel_ms(jit)
             result["alibi_in_kernel"] = {
                 "ms": round(jit_ms, 5),
                 "TFLOPs": round(flops / (jit_ms * 1e-3) / 1e12, 2),
@@ -233,7 +331,7 @@ def main() -> int:
                 def jit_bwd():
                     api.fb_alibi_attn_bwd(d["q"], d["k"], d["v"], slopes, d["out"], d["lse"], d["dout"],
                                           causal=w.causal, workspace=wsj, grads=gj, stream=stream)
-                _, jit_bwd_ms = time_calls(jit_bwd, n, 3)
+                jit_bwd_ms, _ = kernel_ms(jit_bwd)
                 result["alibi_in_kernel"]["bwd_ms"] = round(jit_bwd_ms, 5)
                 del wsj, gj
 
@@ -247,9 +345,10 @@ def main() -> int:
             api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], d["out"], d["lse"],
                                     d["dout"], causal=w.causal, workspace=ws, grads=grads, stream=stream)
         fwd()
-        _, bwd_ms = time_calls(bwd, n, 3)
+        bwd_ms, _ = kernel_ms(bwd)
         result["backward"] = {"ms": round(bwd_ms, 5),
-                              "TFLOPs": round(w.bwd_flops() / (bwd_ms * 1e-3) / 1e12, 2)}
+                              "TFLOPs": round(w.bwd_flops() / (bwd_ms * 1e-3) / 1e12, 2),
+                              "pct_of_bf16_mfma_peak": round(100 * w.bwd_flops() / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2)}
         if dense_bwd_ms is not None:
             result["backward"]["dense_bias_ms"] = round(dense_bwd_ms, 5)
             result["backward"]["speedup_lowrank_vs_dense"] = round(dense_bwd_ms / bwd_ms, 3)
@@ -266,24 +365,63 @@ def main() -> int:
             d = to_device(wo, dense=True)
             w_ = wo
 
-            def f2():
-                api.fb_lowrank_attn_fwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out=d["out"],
-                                        lse=d["lse"], causal=w_.causal, stream=stream)
+            def f2(t=None):
+                t = t or d
+                api.fb_lowrank_attn_fwd(t["q"], t["k"], t["v"], t["phi_q"], t["phi_k"], out=t["out"],
+                                        lse=t["lse"], causal=w_.causal, stream=stream)
 
-            def d2():
-                api.fb_dense_bias_attn_fwd(d["q"], d["k"], d["v"], d["bias"], out=d["out"], lse=d["lse"],
+            def d2(t=None):
+                t = t or d
+                api.fb_dense_bias_attn_fwd(t["q"], t["k"], t["v"], t["bias"], out=t["out"], lse=t["lse"],
                                            causal=w_.causal, stream=stream)
-            # short kernels: enough untimed launches for the clocks to settle
-            wu = 100 if wo.pairs < (1 << 32) else 3
-            _, ms_lr = time_calls(f2, n, wu)
-            _, ms_de = time_calls(d2, max(5, n // 2), wu)
+            ms_lr, _ = kernel_ms(f2)
+            ms_de, _ = kernel_ms(d2)
+            fl = wo.fwd_flops()
             row = {"B": wo.B, "H": wo.H, "N": wo.N, "C": wo.C, "R": wo.R,
                    "fwd_ms": round(ms_lr, 5),
-                   "fwd_TFLOPs": round(wo.fwd_flops() / (ms_lr * 1e-3) / 1e12, 2),
-                   "pct_of_bf16_mfma_peak": round(100 * wo.fwd_flops() / (ms_lr * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+                   "fwd_TFLOPs": round(fl / (ms_lr * 1e-3) / 1e12, 2),
+                   "pct_of_bf16_mfma_peak": round(100 * fl / (ms_lr * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
                    "dense_ms": round(ms_de, 5),
-                   "dense_bias_GBps": round(wo.pairs * 2 / (ms_de * 1e-3) / 1e9, 1),
+                   "dense_unique_bias_GBps": round(unique_bias_bytes(wo) / (ms_de * 1e-3) / 1e9, 1),
+                   "dense_bias_consumed_GBps": round(wo.pairs * 2 / (ms_de * 1e-3) / 1e9, 1),
                    "speedup_lowrank_vs_dense": round(ms_de / ms_lr, 3)}
+            # algorithmic HBM bytes of the low-rank forward: q, k, v, out, the factors, lse
+            lr_keys = ("q", "k", "v", "out", "lse", "phi_q", "phi_k")
+            alg_bytes = tensor_bytes({k_: d[k_] for k_ in lr_keys})
+            if tensor_bytes(d) < (256 << 20):
+                # fits the Infinity Cache: back-to-back launches are "hot"; time the cold case as well
+                lr_set = {k_: d[k_] for k_ in lr_keys}
+                cold_lr, nset, sets = rotating(f2, lr_set, tensor_bytes(lr_set))
+                ms_lr_cold, _ = kernel_ms(cold_lr)
+                del sets
+                de_set = {k_: d[k_] for k_ in ("q", "k", "v", "out", "lse", "bias")}
+                cold_de, nset_d, sets = rotating(d2, de_set, tensor_bytes(de_set))
+                ms_de_cold, _ = kernel_ms(cold_de)
+                del sets
+                torch.cuda.empty_cache()
+                row.update({"fwd_ms_cold": round(ms_lr_cold, 5), "dense_ms_cold": round(ms_de_cold, 5),
+                            "cold_buffer_sets": [nset, nset_d],
+                            "speedup_lowrank_vs_dense_cold": round(ms_de_cold / ms_lr_cold, 3)})
+            if name == "pairformer":
+                cold = row.get("fwd_ms_cold", ms_lr)
+                row["roofline"] = {"bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS,
+                                   "algorithmic_bytes": alg_bytes,
+                                   "achieved": round(alg_bytes / (cold * 1e-3) / 1e9, 1),
+                                   "frac": round(alg_bytes / (cold * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                   "achieved_hot": round(alg_bytes / (ms_lr * 1e-3) / 1e9, 1),
+                                   "note": "achieved = algorithmic bytes / cold-cache launch time; hot launches "
+                                           "are served from the Infinity Cache"}
+            elif name == "vision_relpos":
+                sm = wo.pairs * SOFTMAX_FLOP_PER_PAIR
+                row["roofline"] = {"bound": "alu", "unit": "TFLOP/s", "peak": PEAK_VALU_TFLOPS,
+                                   "achieved": round(sm / (ms_lr * 1e-3) / 1e12, 2),
+                                   "frac": round(sm / (ms_lr * 1e-3) / 1e12 / PEAK_VALU_TFLOPS, 4),
+                                   "flop_per_pair": SOFTMAX_FLOP_PER_PAIR,
+                                   "note": "softmax vector work (multiply-add, exponential at quarter rate, "
+                                           "convert, row sum) against the fp32 vector rate without packed ops"}
+            else:
+                row["roofline"] = {"bound": "mfma", "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS,
+                                   "achieved": row["fwd_TFLOPs"], "frac": round(row["fwd_TFLOPs"] / PEAK_BF16_TFLOPS, 4)}
             if name == "long_train":
                 f_ms_db = None
                 if wo.N % 8 == 0:
@@ -297,7 +435,7 @@ def main() -> int:
                         api.fb_dense_bias_attn_bwd(d["q"], d["k"], d["v"], d["bias"], d["out"], d["lse"],
                                                    d["dout"], causal=w_.causal, workspace=wsd, grads=gd,
                                                    stream=stream)
-                    _, f_ms_db = time_calls(db2, 3, 1)
+                    f_ms_db, _ = kernel_ms(db2, steps=3, repeats=3)
                     del gd, wsd
                 d.pop("bias", None)
                 torch.cuda.empty_cache()
@@ -309,9 +447,10 @@ def main() -> int:
                     api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], d["out"],
                                             d["lse"], d["dout"], causal=w_.causal, workspace=ws,
                                             stream=stream)
-                _, ms_b = time_calls(b2, 5, 1)
+                ms_b, _ = kernel_ms(b2, steps=5)
                 row["bwd_ms"] = round(ms_b, 4)
                 row["bwd_TFLOPs"] = round(wo.bwd_flops() / (ms_b * 1e-3) / 1e12, 2)
+                row["bwd_pct_of_bf16_mfma_peak"] = round(100 * wo.bwd_flops() / (ms_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2)
                 if f_ms_db is not None:
                     row["dense_bwd_ms"] = round(f_ms_db, 4)
                     row["bwd_speedup_lowrank_vs_dense"] = round(f_ms_db / ms_b, 3)
@@ -332,8 +471,8 @@ def main() -> int:
         def b3():
             api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], d["out"], d["lse"],
                                     d["dout"], workspace=ws, stream=stream)
-        _, ms_f = time_calls(f3, 10, 2)
-        _, ms_b = time_calls(b3, 5, 1)
+        ms_f, _ = kernel_ms(f3)
+        ms_b, _ = kernel_ms(b3)
         others["pde_distance"] = {
             "B": wp.B, "H": wp.H, "N": wp.N, "C": wp.C, "R": wp.R, "phi_dtype": "f32",
             "fwd_ms": round(ms_f, 4), "fwd_TFLOPs": round(wp.fwd_flops() / (ms_f * 1e-3) / 1e12, 2),
@@ -346,8 +485,8 @@ def main() -> int:
         d = to_device(wp5)
         ws = torch.empty(api.fb_lowrank_attn_bwd_workspace_bytes(wp5.B, wp5.H, wp5.N, wp5.C, wp5.R),
                          dtype=torch.uint8, device="cuda")
-        _, ms_f5 = time_calls(f3, 10, 2)
-        _, ms_b5 = time_calls(b3, 5, 1)
+        ms_f5, _ = kernel_ms(f3)
+        ms_b5, _ = kernel_ms(b3)
         others["pde_distance"]["rank5_fwd_ms"] = round(ms_f5, 4)
         others["pde_distance"]["rank5_bwd_ms"] = round(ms_b5, 4)
         del ws, d
@@ -370,8 +509,8 @@ def main() -> int:
 
         def plain():
             api.fb_lowrank_attn_fwd(qm, km, vm, None, None, out=om, lse=lm, stream=stream)
-        _, ms_m = time_calls(fm_, 10, 2)
-        _, ms_p = time_calls(plain, 10, 2)
+        ms_m, _ = kernel_ms(fm_)
+        ms_p, _ = kernel_ms(plain)
         dom = torch.randn((Bm, Hm, Nm, Cm), device="cuda", generator=g).to(torch.bfloat16)
         wsb = torch.empty(api.fb_lowrank_mulbias_attn_bwd_workspace_bytes(Bm, Hm, Nm, Cm, 2), dtype=torch.uint8,
                           device="cuda")
@@ -379,7 +518,7 @@ def main() -> int:
 
         def bm_():
             api.fb_lowrank_mulbias_attn_bwd(qm, km, vm, fm, fm, om, lm, dom, workspace=wsb, stream=stream)
-        _, ms_mb = time_calls(bm_, 5, 1)
+        ms_mb, _ = kernel_ms(bm_)
         del wsb, dom
         pairs_m = Bm * Hm * Nm * Nm
         others["multiplicative_cos"] = {

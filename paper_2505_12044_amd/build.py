@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflashbias.so")
+PROBE_LIB = os.path.join(HERE, "libfb_bench_probe.so")     # bench-only probes, never linked into the product
 
 SOURCES = ["fb_api.hip", "fb_fwd_f32.hip", "fb_fwd_bf16.hip", "fb_fwd_bf16_c16.hip", "fb_fwd_bf16_c32.hip",
            "fb_fwd_bf16_c64.hip", "fb_fwd_bf16_c128.hip", "fb_fwd_bf16_alibi.hip", "fb_bwd_bf16.hip",
@@ -68,6 +69,16 @@ def build(force: bool = True, jobs: int = 7) -> str:
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
         raise RuntimeError("link failed")
+    # the bench-only probe library (MFMA-loop ceiling, calibration copy)
+    pobj = _compile("fb_bench_probe.hip", force)
+    pvers = os.path.join(OBJ, "probe_exports.map")
+    with open(pvers, "w") as f:
+        f.write("{ global: fbp_*; local: *; };\n")
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", f"-Wl,--version-script={pvers}", "-o", PROBE_LIB, pobj]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("probe link failed")
     return LIB
 
 
