@@ -68,11 +68,11 @@ int pick_qb(int B, int H, int N, int C, int rp, bool dense, bool causal) {
     const int forced = g_fwd_qb.load(std::memory_order_relaxed);
     if (forced == 1 || forced == 2 || forced == 8 || forced == 16) return forced;
     (void)rp;
-    // Long non-causal C = 128 sequences: the eight-wave ping-pong kernel (256-row tiles).
-    if (C == 128 && !dense && !causal && N >= 8192) return 8;
-    // Short sequences at C = 32 (a few key blocks per tile, the tile's set-up dominates): the
-    // direct-to-LDS kernel, whose prologue is cheaper; it falls back for shapes it does not take.
-    if (C == 32 && !causal && N <= 384) return 16;
+    // (the eight-wave ping-pong kernel, fwd_qb = 8, was the choice for long non-causal C = 128
+    // sequences until the four-wave kernel got compile-time ring slots and early K operand reads:
+    // 2.00 ms against 2.14 ms on B 2, H 8, N 16384)
+    // (the direct-to-LDS kernel, fwd_qb = 16, was the choice for short C = 32 sequences; the four-wave
+    // kernel is now 6 % faster there: 0.070 ms against 0.074 ms on B 384, H 4, N 384)
     // Two query blocks per wave halve the LDS traffic per MFMA but double the accumulator
     // registers: they fit the 256-register budget (two waves per SIMD) only for C <= 64, and
     // only pay when 256-row tiles still leave every CU several workgroups.

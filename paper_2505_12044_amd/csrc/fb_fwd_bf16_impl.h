@@ -110,6 +110,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it scalar
+
     const int l32 = lane & 31, hf = lane >> 5;
     const int q0 = qt * K::BQ;
     const int qw0 = q0 + wave * (QB * 32);
@@ -237,6 +238,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     auto load_block = [&](int t, Stage& g) {
         const int k0 = blk_of(t) * BK;
         const unsigned boff = (unsigned)k0 * (unsigned)(CG * 2);
+        const unsigned pboff = (unsigned)k0 * phi_rb;
 #pragma unroll
         for (int it = 0; it < K::KIT; it++) {
             if ((CG == C && K::KCH % kThreads == 0) || gok[it]) {
@@ -245,7 +247,6 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 g.vraw[it] = *(const u32x4*)(vgb + off);
             }
         }
-        const unsigned pboff = (unsigned)k0 * phi_rb;
         if (PM == 3) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
@@ -421,11 +422,16 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     int buf = 0;                 // t % NBUF
     // One block.  MASKED instances apply the causal / sequence-end masks and may skip the
     // MFMA chains of a block no row of this wave can see; interior blocks carry none of that.
-    auto body = [&](int t, auto masked_tag) {
+    // slot_tag: the ring slot of block t when it is known at compile time (the steady-state loop is
+    // unrolled by the ring depth, which turns every LDS address of a block into lane offset +
+    // immediate), else -1 and the running `buf` is used.
+    auto body = [&](int t, auto masked_tag, auto slot_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        constexpr int SB = decltype(slot_tag)::value;
         const int kb0 = blk_of(t) * BK;
-        const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;       // (t+1) % NBUF
-        const int buf2 = buf1 == NBUF - 1 ? 0 : buf1 + 1;     // (t+2) % NBUF
+        const int cbuf = SB >= 0 ? SB : buf;                                              // t % NBUF
+        const int buf1 = SB >= 0 ? (SB + 1) % NBUF : (buf == NBUF - 1 ? 0 : buf + 1);     // (t+1) % NBUF
+        const int buf2 = SB >= 0 ? (SB + 2) % NBUF : (buf1 == NBUF - 1 ? 0 : buf1 + 1);   // (t+2) % NBUF
         // wave-uniform: is this block wholly invisible to this wave (causal), or does it need masks?
         const bool skip = MASKED && CAUSAL && kb0 > qw0 + QB * 32 - 1;
 
@@ -452,7 +458,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         // pair per MFMA) so they neither stall the wave in a burst nor wait for the softmax.
         bf16x8 va[C / 32][2];
         {
-            const bf16_t* vbase = vt + buf * K::VBLK + vlane_off;
+            const bf16_t* vbase = vt + cbuf * K::VBLK + vlane_off;
             constexpr int NV = (C / 32) * 2;
             __builtin_amdgcn_s_setprio(kPrioMfma);
 #pragma unroll
@@ -473,6 +479,11 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             __builtin_amdgcn_s_setprio(0);
         }
 
+        // K operands of the next block right behind the score chain: they land during the softmax, so
+        // the wait for all LDS traffic that precedes the barrier finds them done (issued between the
+        // MFMAs of the value contraction they completed only at the barrier: +2-3 % per launch)
+        read_k(buf1);
+        __builtin_amdgcn_sched_barrier(0);
         // ---- staging: block t+2 registers -> LDS, block t+3 global -> registers ----
         store_block(buf2, t + 2, st);
         load_block(t + 3, st);
@@ -549,9 +560,8 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- O^T += V^T . P^T, each MFMA followed by a K operand read of the next block ----
+        // ---- O^T += V^T . P^T ----
         {
-            const bf16_t* krow = kt + buf1 * K::KBLK + krow_off;
             constexpr int NM = (C / 32) * 2;
             __builtin_amdgcn_s_setprio(kPrioMfma);
 #pragma unroll
@@ -561,18 +571,25 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                     for (int qb = 0; qb < QB; qb++)
                         oacc[qb][i >> 1] = mfma32(va[i >> 1][i & 1], pb[qb][i & 1], oacc[qb][i >> 1]);
                 }
-#pragma unroll
-                for (int ks = (i * K::KS) / NM; ks < ((i + 1) * K::KS) / NM; ks++)
-                    if (kstep_live(ks)) ka[ks] = as_bf16x8(*(const u32x4*)(krow + ks * 16));
-                // pinning each MFMA to its operand read pays on the 32-channel tiles and with in-kernel
-                // factors; elsewhere the compiler's own order of this short section measured 1-7 % faster
-                if (C == 32 || PM == 4) __builtin_amdgcn_sched_barrier(0);
             }
             __builtin_amdgcn_s_setprio(0);
         }
         __syncthreads();
-        buf = buf1;
+        if (SB < 0) buf = buf1;
     };
+    using Dyn = std::integral_constant<int, -1>;
+    // blocks [t, t_end) without masks: single steps until the ring is at slot 0, then whole turns of
+    // the ring with compile-time slots, then the remainder
+    auto plain_run = [&](int t, int t_end) {
+        for (; t < t_end && buf != 0; t++) body(t, std::false_type{}, Dyn{});
+        for (; t + NBUF <= t_end; t += NBUF) {
+            body(t, std::false_type{}, std::integral_constant<int, 0>{});
+            body(t + 1, std::false_type{}, std::integral_constant<int, 1>{});
+            body(t + 2, std::false_type{}, std::integral_constant<int, 2>{});
+        }
+        for (; t < t_end; t++) body(t, std::false_type{}, Dyn{});
+    };
+    static_assert(NBUF == 3, "plain_run unrolls three slots");
 
     // leading blocks that need no mask for any row of this wave, then the rest
     int t_plain = M / BK;
@@ -580,12 +597,11 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     t_plain = min(t_plain, nT);
     if (CAUSAL) {   // reverse order: the masked blocks (diagonal, sequence end) come first
         int t = 0;
-        for (; t < nT - t_plain; t++) body(t, std::true_type{});
-        for (; t < nT; t++) body(t, std::false_type{});
+        for (; t < nT - t_plain; t++) body(t, std::true_type{}, Dyn{});
+        plain_run(t, nT);
     } else {
-        int t = 0;
-        for (; t < t_plain; t++) body(t, std::false_type{});
-        for (; t < nT; t++) body(t, std::true_type{});
+        plain_run(0, t_plain);
+        for (int t = t_plain; t < nT; t++) body(t, std::true_type{}, Dyn{});
     }
 
     // ---- epilogue: o = O / l, lse = m + ln l ----
@@ -653,13 +669,14 @@ int launch(const FwdParams& pin, hipStream_t stream) {
     using K = Cfg<C, RP, QB>;
     auto kern = fwd_bf16_kernel<C, RP, QB, PM, CAUSAL, DENSE, CG>;
     static FbLdsOnce once;
-    if (!fb_raise_lds_limit((const void*)kern, K::kLds + (DENSE ? K::kBiasLds : 0), once)) return 1;
+    constexpr size_t lds_bytes = K::kLds + (DENSE ? K::kBiasLds : 0);
+    if (!fb_raise_lds_limit((const void*)kern, lds_bytes, once)) return 1;
     FwdParams p = pin;
     p.n_qtiles = (p.N + K::BQ - 1) / K::BQ;
     p.n_units = CAUSAL ? (p.n_qtiles + 1) / 2 : p.n_qtiles;
     p.total_tiles = p.B * p.H * p.n_units;
     p.tiles_per_xcd = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), K::kLds + (DENSE ? K::kBiasLds : 0), stream, p);
+    hipLaunchKernelGGL(kern, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_bytes, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
