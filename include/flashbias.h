@@ -164,15 +164,20 @@ int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
 /*
  * Backward of fb_alibi_attn_fwd: dq, dk, dv [B,H,N,C] for an upstream gradient dout, with the
  * ALiBi factors generated in the pre-pass from the slopes and the absolute positions (App. D:
- * the paper's in-kernel variant is timed for training as well as inference).  The slopes are
- * constants of the model, so no factor or slope gradient is produced.  Positions are exact fp32
- * integers: N <= 2^24.  Needs dtype = FB_BF16; workspace as for fb_lowrank_attn_bwd with R = 2.
+ * the paper's in-kernel variant is timed for training as well as inference).  Positions are exact
+ * fp32 integers: N <= 2^24.  Needs dtype = FB_BF16; workspace as for fb_lowrank_attn_bwd with R = 2.
+ *   dslope_rows [B,H,N] float, 4-byte aligned, or NULL (slopes that are constants of the model):
+ *   row i receives sum_j dS_ij (j - i), the contribution of query i to dL/dm_h for the bias
+ *   -m_h (i - j) (Example 3.4); a caller that trains the slopes sums it over i and the batch.  It is
+ *   formed from the two factor-gradient columns inside the kernel, where the part of them that
+ *   grows with the position cancels exactly, so it stays accurate at any N (the raw factor
+ *   gradients of absolute positions do not: see fb_lowrank_attn_bwd with such factors).
  */
 size_t fb_alibi_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype);
 
 int fb_alibi_attn_bwd(const void* q, const void* k, const void* v, const float* slopes,
                       const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv,
+                      void* dq, void* dk, void* dv, float* dslope_rows,
                       int B, int H, int N, int C, int causal, fb_dtype dtype, float scale,
                       void* workspace, size_t workspace_bytes, void* stream);
 

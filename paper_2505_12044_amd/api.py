@@ -87,7 +87,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fb_alibi_attn_bwd_workspace_bytes.restype = sz
     lib.fb_alibi_attn_bwd_workspace_bytes.argtypes = [ci] * 4 + [ci]
     lib.fb_alibi_attn_bwd.restype = ci
-    lib.fb_alibi_attn_bwd.argtypes = [vp] * 10 + [ci] * 5 + [ci, cf, vp, sz, vp]
+    lib.fb_alibi_attn_bwd.argtypes = [vp] * 11 + [ci] * 5 + [ci, cf, vp, sz, vp]
     if path is None:
         _lib_handle = lib
     return lib
@@ -189,8 +189,9 @@ def fb_alibi_attn_bwd_workspace_bytes(B, H, N, C, dtype_code=FB_BF16) -> int:
 
 
 def fb_alibi_attn_bwd(q, k, v, slopes, out, lse, dout, causal=False, scale: float = 0.0, workspace=None,
-                      grads=None, stream=None):
-    """dq, dk, dv of the attention with the in-kernel ALiBi bias -slopes[h] * (i - j)."""
+                      grads=None, dslope_rows=None, stream=None):
+    """dq, dk, dv of the attention with the in-kernel ALiBi bias -slopes[h] * (i - j).  dslope_rows: optional
+    [B,H,N] float32 tensor that receives each query row's contribution to dL/dslope[h]."""
     lib = load_library()
     B, H, N, C = q.shape
     if slopes.dtype != torch.float32 or slopes.numel() != H:
@@ -202,8 +203,8 @@ def fb_alibi_attn_bwd(q, k, v, slopes, out, lse, dout, causal=False, scale: floa
         grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
     dq, dk, dv = grads
     st = lib.fb_alibi_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(slopes), _ptr(out), _ptr(lse), _ptr(dout),
-                               _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, C, int(bool(causal)), _dtype_code(q),
-                               float(scale), _ptr(workspace), workspace.numel(), _stream(stream))
+                               _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dslope_rows), B, H, N, C, int(bool(causal)),
+                               _dtype_code(q), float(scale), _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "fb_alibi_attn_bwd")
     return dq, dk, dv
 

@@ -410,7 +410,7 @@ size_t fb_alibi_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dt
 
 int fb_alibi_attn_bwd(const void* q, const void* k, const void* v, const float* slopes,
                       const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv,
+                      void* dq, void* dk, void* dv, float* dslope_rows,
                       int B, int H, int N, int C, int causal, fb_dtype dtype, float scale,
                       void* workspace, size_t workspace_bytes, void* stream) {
     if (!q || !k || !v || !slopes || !out || !lse || !dout || !dq || !dk || !dv) return FB_ERR_NULL;
@@ -420,6 +420,7 @@ int fb_alibi_attn_bwd(const void* q, const void* k, const void* v, const float* 
     const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
     for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(slopes) & 3u) != 0) return FB_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(dslope_rows) & 3u) != 0) return FB_ERR_ALIGN;     // NULL: not wanted
     if (!workspace || workspace_bytes < bwd_ws_impl(B, H, N, N, C, 2)) return FB_ERR_WORKSPACE;
     if (!aligned16(workspace)) return FB_ERR_ALIGN;
 
@@ -427,6 +428,7 @@ int fb_alibi_attn_bwd(const void* q, const void* k, const void* v, const float* 
     p.q = q; p.k = k; p.v = v; p.phi_q = nullptr; p.phi_k = nullptr; p.slopes = slopes;
     p.out = out; p.lse = lse; p.dout = dout;
     p.dq = dq; p.dk = dk; p.dv = dv; p.dphi_q = nullptr; p.dphi_k = nullptr;
+    p.dslope = dslope_rows;
     p.workspace = workspace;
     p.B = B; p.H = H; p.N = N; p.M = N; p.R = 2; p.Cg = C; p.causal = causal != 0;
     p.phi_f32 = 1;

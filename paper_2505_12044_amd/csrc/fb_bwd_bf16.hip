@@ -205,13 +205,22 @@ __global__ __launch_bounds__(256) void bwd_pad16_kernel(const bf16_t* __restrict
 template <int RP2, bool QSIDE>
 FB_DEV void store_dphi(const f32x16* acc_phi /* [RP2/32] */, float* scratch /* wave-private [32][RP2+1] */,
                        void* dst_row /* gradient row of this lane's token or null */, int R,
-                       bool f32, bool raw, int l32, int hf) {
+                       bool f32, bool raw, int l32, int hf, float* dslope = nullptr, float pos = 0.f) {
 #pragma unroll
     for (int mb = 0; mb < RP2 / 32; mb++)
 #pragma unroll
         for (int r = 0; r < 16; r++)
             scratch[l32 * (RP2 + 1) + mb * 32 + 8 * (r / 4) + 4 * hf + (r % 4)] = acc_phi[mb][r];
     __syncthreads();
+    if (QSIDE && dslope != nullptr && hf == 0) {
+        // ALiBi factors phi_q(i) = [-m i, m] against phi_k(j) = [1, j] (fp32 limb columns): the chain rule
+        // onto the slope is dphi_q[i,1] - i dphi_q[i,0] = sum_j dS_ij (j - i).  Both terms come from the same
+        // bf16 dS values through fp32 accumulators, so whatever the rows of dS fail to sum to (the error of
+        // D = rowsum(dO o O)) cancels here instead of being multiplied by the position.
+        const float* s = scratch + l32 * (RP2 + 1);
+        const float g0 = s[0] + s[1] + s[3], g1 = s[6] + s[7] + s[9];
+        *dslope = g1 - pos * g0;
+    }
     if (dst_row != nullptr) {
         for (int r = hf; r < R; r += 2) {
             const float* s = scratch + l32 * (RP2 + 1);
@@ -845,7 +854,9 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         unsigned char* const dphi = (unsigned char*)(DKV ? p.dphi_k : p.dphi_q);     // NULL: factor gradients not wanted
         if (rok && dphi != nullptr) dst = dphi + ((size_t)bh * NL + ri) * R * esz;
         // the key-side limb order applies to the key's own gradient and vice versa
-        store_dphi<K::RP2, !DKV>(&acc1[K::MBC], scratch, dst, R, f32, g32, l32, hf);
+        float* dsl = nullptr;
+        if (!DKV && rok && p.slopes != nullptr && p.dslope != nullptr) dsl = p.dslope + (size_t)bh * NL + ri;
+        store_dphi<K::RP2, !DKV>(&acc1[K::MBC], scratch, dst, R, f32, g32, l32, hf, dsl, (float)ri);
     }
 }
 

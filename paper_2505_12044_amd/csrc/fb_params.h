@@ -37,6 +37,7 @@ struct BwdParams {
     void* dq; void* dk; void* dv; void* dphi_q; void* dphi_k;
     const float* slopes;  // [H] ALiBi slopes: factors phi_q(i) = [-m i, m], phi_k(j) = [1, j] are generated in the
                           // pre-pass instead of read (phi_q, phi_k, dphi_q, dphi_k NULL, R = 2, phi_f32 = 1); else NULL
+    float* dslope;        // [B,H,N] or NULL (with slopes only): per-row gradient of the head's slope, sum_j dS_ij (j - i)
     const void* bias;     // [Bb,H,N,M] dense-bias backward only
     void* dbias;          // [B,H,N,M]
     long long bias_bstride;  // elements between batch items of bias (0 when shared)

@@ -130,3 +130,58 @@ def test_alibi_backward_matches_factor_tensor_path_at_full_size():
         diff = float((a.float() - b.float()).abs().max())
         print(f"alibi bwd in-kernel vs factor tensors, {name}: max diff {diff:.3e}", flush=True)
         assert diff <= 2e-2
+
+
+def _oracle_slope_rows(q, k, v, slope, dout, causal):
+    """sum_j dS_ij (j - i): the derivative of L with respect to the slope m of the bias -m (i - j),
+    row by row, from the oracle's dense bias gradient (dL/db = dS; db_ij/dm = j - i)."""
+    n = q.shape[0]
+    ds = O.attention_with_bias_grads(q, k, v, O.alibi_bias(float(slope), n), dout, causal=causal)[3]
+    pos = np.arange(n, dtype=np.float64)
+    return np.sum(ds * (pos[None, :] - pos[:, None]), axis=1)
+
+
+@pytest.mark.parametrize("N,C,causal", [(515, 64, True), (384, 128, False), (200, 16, True), (1, 64, True)])
+def test_alibi_slope_gradient_small(N, C, causal):
+    """dslope_rows of fb_alibi_attn_bwd against the oracle.  With the small slopes of this test a row
+    attends over hundreds of positions and its slope gradient reaches magnitudes of 200, so the bound
+    scales with the data (observed: 0.4 % of the largest entry, the level of bf16 operands)."""
+    B, H = 2, 3
+    q, k, v = _inputs(B, H, N, C, seed=4700 + N + C)
+    dout = W.round_bf16(np.random.default_rng(4800 + N).standard_normal((B, H, N, C)).astype(np.float32))
+    slopes = np.array([0.5, 2.0 ** -6, 0.0123], dtype=np.float32)
+    if not causal:
+        slopes = slopes * np.float32(0.05)
+    ts = torch.from_numpy(slopes).cuda()
+    d = [dev(x, "bf16") for x in (q, k, v)]
+    out, lse = api.fb_alibi_attn_fwd(*d, ts, causal=causal)
+    dsl = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    g1 = api.fb_alibi_attn_bwd(*d, ts, out, lse, dev(dout, "bf16"), causal=causal, dslope_rows=dsl)
+    g0 = api.fb_alibi_attn_bwd(*d, ts, out, lse, dev(dout, "bf16"), causal=causal)
+    torch.cuda.synchronize()
+    for a, b in zip(g0, g1):        # the extra output changes nothing else
+        assert torch.equal(a, b)
+    ref = np.empty((B, H, N))
+    for b in range(B):
+        for h in range(H):
+            ref[b, h] = _oracle_slope_rows(q[b, h], k[b, h], v[b, h], slopes[h], dout[b, h], causal)
+    check_grad(f"alibi slope gradient N{N} C{C} causal={causal}", "dslope_rows", host(dsl), ref, data_scaled=True)
+
+
+def test_alibi_slope_gradient_full_size():
+    """Headline shape (N = 4096): every row of three heads.  The raw factor gradients of absolute
+    positions are ill-conditioned at this length; the slope gradient formed inside the kernel is not."""
+    w = W.make_workload("alibi_causal", with_dout=True)
+    slopes = W.alibi_slopes_f32(w.H)
+    ts = torch.from_numpy(slopes).cuda()
+    d = [dev(x, "bf16") for x in (w.q, w.k, w.v)]
+    out, lse = api.fb_alibi_attn_fwd(*d, ts, causal=True)
+    dsl = torch.full((w.B, w.H, w.N), float("nan"), dtype=torch.float32, device="cuda")
+    api.fb_alibi_attn_bwd(*d, ts, out, lse, dev(w.dout, "bf16"), causal=True, dslope_rows=dsl)
+    torch.cuda.synchronize()
+    assert torch.isfinite(dsl).all()
+    for (b, h) in [(0, 0), (2, 7), (3, 15)]:
+        ref = _oracle_slope_rows(w.q[b, h], w.k[b, h], w.v[b, h], slopes[h], w.dout[b, h], True)
+        # rows reach magnitudes of 30 (0.4 % of that is 0.12: the bf16 rounding of q * scale moves P by as much)
+        check_grad(f"alibi slope gradient, headline shape, (b,h)=({b},{h})", "dslope_rows", host(dsl[b, h]), ref,
+                   data_scaled=True)

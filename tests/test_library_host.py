@@ -152,10 +152,13 @@ def test_alibi_backward_argument_errors(lib):
     assert need == lib.fb_lowrank_attn_bwd_workspace_bytes(1, 2, 100, 64, 2, api.FB_BF16)
 
     def call(ptrs=None, C=64, dtype=api.FB_BF16, w=64, wb=need, N=100):
-        ptrs = ptrs or [64] * 10
+        ptrs = ptrs or [64] * 10 + [None]                       # dslope_rows NULL: not wanted
+        if len(ptrs) == 10:
+            ptrs = ptrs + [None]
         return f(*ptrs, 1, 2, N, C, 1, dtype, 0.0, w, wb, None)
 
     assert call(ptrs=[64, 64, 64, None] + [64] * 6) == 1       # slopes
+    assert call(ptrs=[64] * 10 + [66]) == 4                    # dslope_rows not 4-byte aligned
     assert call(N=0) == 2
     assert call(C=48) == 3
     assert call(dtype=api.FB_F32) == 3
