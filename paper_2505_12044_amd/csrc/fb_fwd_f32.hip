@@ -6,6 +6,9 @@
 // registers; key/value tiles are staged in LDS and read by all lanes at the same address
 // (a broadcast, conflict-free).  Scores of a tile are [q*scale | phi_q] . [k | phi_k]
 // (FlashBias Eq. 3) followed by an online softmax over tiles.
+// Every global access is coalesced: the query rows, the output rows and the dense bias tile
+// pass through LDS (consecutive lanes touch consecutive addresses in memory, and a thread
+// then picks up or drops its own row in LDS), 32 rows at a time.
 #include <hip/hip_runtime.h>
 
 #include "fb_launch.h"
@@ -19,8 +22,10 @@ constexpr int kTK = 32;        // keys per LDS tile
 template <int C, int RP, bool DENSE>
 __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
     constexpr int W = C + RP;
-    __shared__ float ks[kTK][W];
+    constexpr int WP = W | 1;          // odd pitch: a thread-per-row walk over the tile is conflict-free
+    __shared__ float ks[kTK][WP];
     __shared__ float vs[kTK][C];
+    __shared__ float bs[DENSE ? kThreads : 1][kTK + 1];     // dense mode: bias tile of this block's rows
 
     const int tid = threadIdx.x;
     const int bh = blockIdx.x / p.n_qtiles;
@@ -46,13 +51,28 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
 
     float qr[W];
     float o[C];
+    // query rows [q*scale | phi_q | 0], 32 at a time through the K tile buffer
+    static_assert(kTK == 32 && kThreads % 32 == 0, "row chunks of 32");
+    for (int ch = 0; ch < kThreads / 32; ch++) {
+        __syncthreads();
+        for (int e = tid; e < 32 * W; e += kThreads) {
+            const int rr = e / W, c = e % W;
+            const int row = qt * kThreads + ch * 32 + rr;
+            float x = 0.f;
+            if (row < N) {
+                if (c < C) x = qg[(size_t)row * C + c] * p.scale;
+                else if (c - C < R) x = pqg[(size_t)row * R + (c - C)];
+            }
+            ks[rr][c] = x;
+        }
+        __syncthreads();
+        if (tid / 32 == ch) {
 #pragma unroll
-    for (int c = 0; c < C; c++) {
-        qr[c] = valid ? qg[(size_t)i * C + c] * p.scale : 0.f;
-        o[c] = 0.f;
+            for (int c = 0; c < W; c++) qr[c] = ks[tid % 32][c];
+        }
     }
 #pragma unroll
-    for (int r = 0; r < RP; r++) qr[C + r] = (valid && r < R) ? pqg[(size_t)i * R + r] : 0.f;
+    for (int c = 0; c < C; c++) o[c] = 0.f;
 
     float m = -INFINITY, l = 0.f;
     const int n_keys = p.causal ? min(N, (qt + 1) * kThreads) : N;
@@ -74,6 +94,13 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
             const int j = j0 + jj;
             vs[jj][c] = j < N ? vg[(size_t)j * C + c] : 0.f;
         }
+        if (DENSE) {
+            for (int e = tid; e < kThreads * kTK; e += kThreads) {
+                const int rr = e / kTK, jj = e % kTK;
+                const int row = qt * kThreads + rr, j = j0 + jj;
+                bs[rr][jj] = (row < N && j < N) ? bg[(size_t)row * N + j] : 0.f;
+            }
+        }
         __syncthreads();
 
         float s[kTK];
@@ -84,9 +111,7 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
 #pragma unroll
             for (int c = 0; c < W; c++) acc = fmaf(qr[c], ks[jj][c], acc);
             const int j = j0 + jj;
-            if (DENSE) {
-                if (valid && j < N) acc += bg[(size_t)i * N + j];
-            }
+            if (DENSE) acc += bs[tid][jj];
             if (j >= N || (p.causal && j > i)) acc = -INFINITY;
             s[jj] = acc;
             mt = fmaxf(mt, acc);
@@ -106,12 +131,21 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
         m = m_new;
     }
 
-    if (valid) {
-        const float inv = 1.f / l;
-        float* og = (float*)p.out + base + (size_t)i * C;
+    const float inv = 1.f / l;
+    if (valid) p.lse[(size_t)bh * N + i] = m + logf(l);
+    // output rows, 32 at a time through the V tile buffer
+    for (int ch = 0; ch < kThreads / 32; ch++) {
+        __syncthreads();
+        if (tid / 32 == ch) {
 #pragma unroll
-        for (int c = 0; c < C; c++) og[c] = o[c] * inv;
-        p.lse[(size_t)bh * N + i] = m + logf(l);
+            for (int c = 0; c < C; c++) vs[tid % 32][c] = o[c] * inv;
+        }
+        __syncthreads();
+        for (int e = tid; e < 32 * C; e += kThreads) {
+            const int rr = e / C, c = e % C;
+            const int row = qt * kThreads + ch * 32 + rr;
+            if (row < N) ((float*)p.out)[base + (size_t)row * C + c] = vs[rr][c];
+        }
     }
 }
 
