@@ -52,6 +52,25 @@ constexpr int NBUF = 3;      // LDS ring depth
 // unaffected by the choice of reference.
 constexpr float kSumLimit = 256.0f;   // 2^tau, tau = 8
 
+// A piece of NB = 16, 8 or 4 bytes between global memory / LDS and the low words of a u32x4.
+template <int NB>
+FB_DEV void ld_piece(u32x4& r, const unsigned char* src) {
+    if constexpr (NB == 16) {
+        r = *(const u32x4*)src;
+    } else if constexpr (NB == 8) {
+        const u32x2 t = *(const u32x2*)src;
+        r.x = t.x; r.y = t.y;
+    } else {
+        r.x = *(const unsigned*)src;
+    }
+}
+template <int NB>
+FB_DEV void st_piece(unsigned char* dst, const u32x4& r) {
+    if constexpr (NB == 16) *(u32x4*)dst = r;
+    else if constexpr (NB == 8) *(u32x2*)dst = u32x2{r.x, r.y};
+    else *(unsigned*)dst = r.x;
+}
+
 template <int C, int RP, int QB>
 struct Cfg {
     static constexpr int KS = (C + RP) / 16;          // MFMA k-steps of the score contraction
@@ -62,6 +81,9 @@ struct Cfg {
     static constexpr int KIT = (KCH + kThreads - 1) / kThreads;   // per-thread chunks
     static constexpr int PCH = BK * RP / 8;           // chunks of the factor part
     static constexpr int PIT = (PCH + kThreads - 1) / kThreads;
+    // whole-chunk factor copies (bf16 factors, R % 8 == 0): pieces sized so that every thread has one
+    static constexpr int PPB = RP == 0 ? 16 : ((RP % 64) == 0 ? 16 : ((RP % 32) == 0 ? 8 : 4));
+    static constexpr int PPIT = RP == 0 ? 1 : BK * RP * 2 / (PPB * kThreads);
     static constexpr int FIT = (BK * (RP / 6) + kThreads - 1) / kThreads > 0
                                    ? (BK * (RP / 6) + kThreads - 1) / kThreads : 1;   // fp32 (row, rank) items per thread
     static constexpr int KBLK = BK * KP;              // elements per K block buffer
@@ -103,6 +125,10 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     // q * scale * log2 e where the backward rounds q * scale: scores that differ by one bf16
     // rounding between the passes leave the rows of dS summing to ~1e-3 D instead of zero, which
     // factor gradients of absolute positions (ALiBi) multiply by up to N.  Not used there.
+    // (The same fold for bf16 factors - phi_q * log2 e carried as two bf16 limbs, the factor k-steps
+    // issued twice against the same K operand registers - was measured and lost: the extra MFMA per
+    // block costs more than the sixteen multiply-adds it saves, 0.0695 against 0.0668 ms on the
+    // Pairformer shape.)
     constexpr bool FOLD = !DENSE && (PM == 3 || PM == 4) && C == 32;
     const float qmul = FOLD ? kLog2e : 1.f;
     const float slope = PM == 4 ? p.slopes[h] * qmul : 0.f;
@@ -171,17 +197,31 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 
     // ---- block staging: global -> registers -> LDS.  Rows past M are clamped to row M-1; the
     // keys they stand for are masked to -inf before the softmax, so their values never count.
+    // The K and V rows of a block are copied in pieces of KPB bytes, sized so that every thread
+    // holds at least one piece (16 bytes for C >= 64, 8 for C = 32, 4 for 16-channel rows): no
+    // thread is idle, so the staging code carries no exec-mask branches.
+    constexpr int KBYTES = BK * CG * 2;
+    constexpr int KPB = KBYTES / kThreads >= 16 ? 16 : KBYTES / kThreads;
+    constexpr int KITP = KBYTES / (KPB * kThreads);
+    static_assert(KPB == 16 || KPB == 8 || KPB == 4, "piece size");
+    // Whole-chunk factor copies (PM == 1) in per-thread pieces as well, where 16-byte chunks would leave
+    // threads idle and cost exec-mask branches (C <= 64: -4 % on the Pairformer shape); at C = 128 the
+    // 16-byte chunk copy measured 8 % faster on the long-sequence shape and is kept.
+    constexpr bool PPIECES = PM == 1 && C <= 64;
+    constexpr int PRW = PPIECES ? K::PPIT : (K::PIT > 0 ? K::PIT : 1);
     struct Stage {                       // one block in flight between global memory and LDS
-        u32x4 kraw[K::KIT], vraw[K::KIT];
-        u32x4 praw[K::PIT > 0 ? K::PIT : 1];
+        u32x4 kraw[KITP], vraw[KITP];
+        u32x4 praw[PRW];
         float fraw[K::FIT];              // fp32 factors: one (key row, rank) item
     };
     auto init_stage = [&](Stage& g) {    // chunks and items a thread never loads stay zero
 #pragma unroll
-        for (int it = 0; it < K::KIT; it++) {
+        for (int it = 0; it < KITP; it++) {
             g.kraw[it] = u32x4{0u, 0u, 0u, 0u};
             g.vraw[it] = u32x4{0u, 0u, 0u, 0u};
         }
+#pragma unroll
+        for (int it = 0; it < PRW; it++) g.praw[it] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int it = 0; it < K::FIT; it++) g.fraw[it] = 0.f;
     };
@@ -212,14 +252,38 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     // loaded and stay zero.  All offsets inside one head fit 32 bits (the entry points reject
     // larger problems).  A row past M is clamped to row M-1 by a minimum on the byte offset,
     // so one code path serves whole and partial blocks without a multiply.
-    unsigned grow[K::KIT], gcol[K::KIT];
-    bool gok[K::KIT];
+    unsigned grow[KITP], gcol[KITP], klds[KITP], vlds[KITP];
 #pragma unroll
-    for (int it = 0; it < K::KIT; it++) {
-        const int e = tid + it * kThreads;
-        grow[it] = (unsigned)((e / (C / 8)) * CG * 2);
-        gcol[it] = (unsigned)((e % (C / 8)) * 16);
-        gok[it] = (K::KCH % kThreads == 0 || e < K::KCH) && (CG == C || (e % (C / 8)) * 8 < CG);
+    for (int it = 0; it < KITP; it++) {
+        const int byte = (tid + it * kThreads) * KPB;
+        const int row = byte / (CG * 2), colb = byte % (CG * 2);
+        grow[it] = (unsigned)(row * CG * 2);
+        gcol[it] = (unsigned)colb;
+        klds[it] = (unsigned)(row * K::KP * 2 + colb);     // byte offsets inside a ring slot
+        vlds[it] = (unsigned)(row * K::VP * 2 + colb);
+    }
+    if (CG < C) {
+        // channels the caller's rows do not have: zero in every ring slot, once (no piece ever lands there)
+        constexpr int ZW = (C - CG) / 2;      // dwords per row
+        for (int e = tid; e < NBUF * BK * ZW; e += kThreads) {
+            const int row = e / ZW, c2 = e % ZW;
+            *(unsigned*)(kt + (size_t)row * K::KP + CG + 2 * c2) = 0u;
+            *(unsigned*)(vt + (size_t)row * K::VP + CG + 2 * c2) = 0u;
+        }
+    }
+    // whole-chunk factor pieces (PM == 1): LDS byte offset, memory row offset and column byte of each
+    unsigned prow[PRW], pcolb[PRW], plds[PRW];
+    bool pvalid[PRW];
+    if (PPIECES) {
+#pragma unroll
+        for (int it = 0; it < PRW; it++) {
+            const int byte = (tid + it * kThreads) * K::PPB;
+            const int row = byte / (RP * 2 > 0 ? RP * 2 : 1), colb = byte % (RP * 2 > 0 ? RP * 2 : 1);
+            pvalid[it] = colb < R * 2;                              // a piece lies wholly inside or outside the R columns
+            prow[it] = (unsigned)row;
+            pcolb[it] = pvalid[it] ? (unsigned)colb : 0u;          // outside: read column 0 (valid memory), store zero
+            plds[it] = (unsigned)(row * K::KP * 2 + (C * 2) + colb);
+        }
     }
     const unsigned char* kgb = (const unsigned char*)kg;
     const unsigned char* vgb = (const unsigned char*)vg;
@@ -240,12 +304,10 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         const unsigned boff = (unsigned)k0 * (unsigned)(CG * 2);
         const unsigned pboff = (unsigned)k0 * phi_rb;
 #pragma unroll
-        for (int it = 0; it < K::KIT; it++) {
-            if ((CG == C && K::KCH % kThreads == 0) || gok[it]) {
-                const unsigned off = min(boff + grow[it], kv_last) + gcol[it];
-                g.kraw[it] = *(const u32x4*)(kgb + off);
-                g.vraw[it] = *(const u32x4*)(vgb + off);
-            }
+        for (int it = 0; it < KITP; it++) {
+            const unsigned off = min(boff + grow[it], kv_last) + gcol[it];
+            ld_piece<KPB>(g.kraw[it], kgb + off);
+            ld_piece<KPB>(g.vraw[it], vgb + off);
         }
         if (PM == 3) {
 #pragma unroll
@@ -256,6 +318,12 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
                 g.fraw[it] = fitem_r[it] == 0 ? 1.f : (float)(k0 + fitem_row[it] - q0);
+        } else if (PPIECES) {
+#pragma unroll
+            for (int it = 0; it < PRW; it++) {
+                const unsigned char* src = pkg + min(pboff + __umul24(prow[it], phi_rb), phi_last) + pcolb[it];
+                ld_piece<K::PPB>(g.praw[it], src);
+            }
         } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
@@ -279,19 +347,26 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     auto store_block = [&](int buf, int t, const Stage& g) {
         bf16_t* kdst = kt + buf * K::KBLK;
         bf16_t* vdst = vt + buf * K::VBLK;
+        // One wait for every load in flight (they were issued a whole iteration ago) instead of the
+        // wait per store the compiler would place: -9 % on the Pairformer shape, -3 % on the point-cloud
+        // shape, neutral at C = 128.
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0); expcnt and lgkmcnt unconstrained
 #pragma unroll
-        for (int it = 0; it < K::KIT; it++) {
-            const int e = tid + it * kThreads;
-            if (K::KCH % kThreads == 0 || e < K::KCH) {
-                const int row = e / (C / 8), c8 = e % (C / 8);
-                *(u32x4*)(kdst + row * K::KP + c8 * 8) = g.kraw[it];
-                *(u32x4*)(vdst + row * K::VP + c8 * 8) = g.vraw[it];
-            }
+        for (int it = 0; it < KITP; it++) {
+            st_piece<KPB>((unsigned char*)kdst + klds[it], g.kraw[it]);
+            st_piece<KPB>((unsigned char*)vdst + vlds[it], g.vraw[it]);
         }
         if (ITEMS) {
 #pragma unroll
             for (int it = 0; it < K::FIT; it++)
                 if (fitem_ok[it]) phi_item_store_k(kdst + fitem_row[it] * K::KP + C + 6 * fitem_r[it], g.fraw[it]);
+        } else if (PPIECES) {
+#pragma unroll
+            for (int it = 0; it < PRW; it++) {
+                u32x4 v = g.praw[it];
+                if (!pvalid[it]) v = u32x4{0u, 0u, 0u, 0u};      // a select, not a branch
+                st_piece<K::PPB>((unsigned char*)kdst + plds[it], v);
+            }
         } else if (PM != 0) {
 #pragma unroll
             for (int it = 0; it < K::PIT; it++) {
