@@ -208,11 +208,17 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     // threads idle and cost exec-mask branches (C <= 64: -4 % on the Pairformer shape); at C = 128 the
     // 16-byte chunk copy measured 8 % faster on the long-sequence shape and is kept.
     constexpr bool PPIECES = PM == 1 && C <= 64;
+    // fp32 factor items.  When a block has fewer items than the workgroup has threads (small R), one
+    // wave takes all of a block's items (64 per pass) and the waves take turns block by block: the
+    // other three skip the item code behind a scalar branch instead of running it with a quarter
+    // of their lanes (-1.4 % per launch at R = 2, C = 128).
+    constexpr bool DUTY = (PM == 3 || PM == 4) && BK * (RP / 6) < kThreads;
+    constexpr int FITN = DUTY ? (BK * (RP / 6) + 63) / 64 : K::FIT;
     constexpr int PRW = PPIECES ? K::PPIT : (K::PIT > 0 ? K::PIT : 1);
     struct Stage {                       // one block in flight between global memory and LDS
         u32x4 kraw[KITP], vraw[KITP];
         u32x4 praw[PRW];
-        float fraw[K::FIT];              // fp32 factors: one (key row, rank) item
+        float fraw[FITN];                // fp32 factors: one (key row, rank) item
     };
     auto init_stage = [&](Stage& g) {    // chunks and items a thread never loads stay zero
 #pragma unroll
@@ -223,18 +229,19 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
 #pragma unroll
         for (int it = 0; it < PRW; it++) g.praw[it] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int it = 0; it < K::FIT; it++) g.fraw[it] = 0.f;
+        for (int it = 0; it < FITN; it++) g.fraw[it] = 0.f;
     };
     Stage st;
     init_stage(st);
-    // fp32 factors: item e = (key row, rank r) of a block, spread evenly over the four waves
-    int fitem_row[K::FIT], fitem_r[K::FIT];
-    bool fitem_ok[K::FIT];
+    // fp32 factors: item e = (key row, rank r) of a block, spread evenly over the four waves (or all
+    // in the wave on duty)
+    int fitem_row[FITN], fitem_r[FITN];
+    bool fitem_ok[FITN];
     const float* pkf = (const float*)pkg;
     if (ITEMS) {
 #pragma unroll
-        for (int it = 0; it < K::FIT; it++) {
-            const int e = lane * kWaves + wave + it * kThreads;
+        for (int it = 0; it < FITN; it++) {
+            const int e = DUTY ? lane + 64 * it : lane * kWaves + wave + it * kThreads;
             fitem_ok[it] = e < BK * R;
             fitem_row[it] = fitem_ok[it] ? e / R : 0;
             fitem_r[it] = fitem_ok[it] ? e - fitem_row[it] * R : 0;
@@ -290,10 +297,10 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     const unsigned kv_last = (unsigned)(M - 1) * (unsigned)(CG * 2);       // byte offset of the last row
     const unsigned phi_rb = (unsigned)R * (unsigned)phi_esz;                // bytes per factor row
     const unsigned phi_last = (unsigned)(M - 1) * phi_rb;
-    unsigned fitem_off[K::FIT], fitem_col[K::FIT];
+    unsigned fitem_off[FITN], fitem_col[FITN];
     if (PM == 3) {
 #pragma unroll
-        for (int it = 0; it < K::FIT; it++) {
+        for (int it = 0; it < FITN; it++) {
             fitem_off[it] = (unsigned)fitem_row[it] * phi_rb;
             fitem_col[it] = (unsigned)fitem_r[it] * 4u;
         }
@@ -309,15 +316,20 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             ld_piece<KPB>(g.kraw[it], kgb + off);
             ld_piece<KPB>(g.vraw[it], vgb + off);
         }
+        const bool on_duty = !DUTY || (t & (kWaves - 1)) == wave;     // wave-uniform
         if (PM == 3) {
+            if (on_duty) {
 #pragma unroll
-            for (int it = 0; it < K::FIT; it++)
-                if (fitem_ok[it])
-                    g.fraw[it] = *(const float*)(pkg + (min(pboff + fitem_off[it], phi_last) + fitem_col[it]));
+                for (int it = 0; it < FITN; it++)
+                    if (fitem_ok[it])
+                        g.fraw[it] = *(const float*)(pkg + (min(pboff + fitem_off[it], phi_last) + fitem_col[it]));
+            }
         } else if (PM == 4) {
+            if (on_duty) {
 #pragma unroll
-            for (int it = 0; it < K::FIT; it++)
-                g.fraw[it] = fitem_r[it] == 0 ? 1.f : (float)(k0 + fitem_row[it] - q0);
+                for (int it = 0; it < FITN; it++)
+                    g.fraw[it] = fitem_r[it] == 0 ? 1.f : (float)(k0 + fitem_row[it] - q0);
+            }
         } else if (PPIECES) {
 #pragma unroll
             for (int it = 0; it < PRW; it++) {
@@ -357,9 +369,11 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
             st_piece<KPB>((unsigned char*)vdst + vlds[it], g.vraw[it]);
         }
         if (ITEMS) {
+            if (!DUTY || (t & (kWaves - 1)) == wave) {      // same block, same wave as in load_block
 #pragma unroll
-            for (int it = 0; it < K::FIT; it++)
-                if (fitem_ok[it]) phi_item_store_k(kdst + fitem_row[it] * K::KP + C + 6 * fitem_r[it], g.fraw[it]);
+                for (int it = 0; it < FITN; it++)
+                    if (fitem_ok[it]) phi_item_store_k(kdst + fitem_row[it] * K::KP + C + 6 * fitem_r[it], g.fraw[it]);
+            }
         } else if (PPIECES) {
 #pragma unroll
             for (int it = 0; it < PRW; it++) {
