@@ -209,7 +209,9 @@ int fb_lowrank_mulbias_attn_bwd(const void* q, const void* k, const void* v,
  * that gradient is not wanted (fixed biases).  The factor
  * gradients are the trailing R columns of the same contractions that give dq and dk
  * (Sec. 3.2 "Speed up training"; Sec. 4.1 "Implementation choices").
- * `out` and `lse` are the forward's results.  Needs dtype = FB_BF16.
+ * `out` and `lse` are the forward's results.  dtype = FB_BF16, or FB_F32 (all tensors and the
+ * factors float, N keys = N queries: the full-precision path, fp32 FMA arithmetic, which uses only
+ * the first 4 B H N bytes of the workspace, for D).
  * workspace: device scratch of at least fb_lowrank_attn_bwd_workspace_bytes(...) bytes,
  * 16-byte aligned, owned by the caller; its contents on entry are ignored and it may be
  * reused as soon as the call's work on `stream` has finished.  It receives, per (b, h, i):

@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libflashbias.so")
 PROBE_LIB = os.path.join(HERE, "libfb_bench_probe.so")     # bench-only probes, never linked into the product
 
 SOURCES = ["fb_api.hip", "fb_fwd_f32.hip", "fb_fwd_bf16.hip", "fb_fwd_bf16_c16.hip", "fb_fwd_bf16_c32.hip",
-           "fb_fwd_bf16_c64.hip", "fb_fwd_bf16_c128.hip", "fb_fwd_bf16_alibi.hip", "fb_bwd_bf16.hip",
+           "fb_fwd_bf16_c64.hip", "fb_fwd_bf16_c128.hip", "fb_fwd_bf16_alibi.hip", "fb_bwd_bf16.hip", "fb_bwd_f32.hip",
            "fb_mulbias.hip"]
 
 FLAGS = [

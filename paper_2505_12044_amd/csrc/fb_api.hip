@@ -377,9 +377,10 @@ static int lowrank_bwd_impl(const void* q, const void* k, const void* v,
     if (int st = check_common(B, H, N > M ? N : M, C, R)) return st;
     if (N <= 0 || M <= 0) return FB_ERR_SHAPE;
     if (R > 0 && (!phi_q || !phi_k)) return FB_ERR_NULL;       // dphi_q / dphi_k may be NULL: not wanted
-    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
+    if (dtype != FB_BF16 && dtype != FB_F32) return FB_ERR_UNSUPPORTED;
     if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
-    if (N != M && causal) return FB_ERR_UNSUPPORTED;
+    if (dtype == FB_F32 && R > 0 && phi_dtype != FB_F32) return FB_ERR_UNSUPPORTED;
+    if (N != M && (causal || dtype != FB_BF16)) return FB_ERR_UNSUPPORTED;
     const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
     for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
     if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k) || !aligned16(dphi_q) || !aligned16(dphi_k)))
@@ -399,7 +400,8 @@ static int lowrank_bwd_impl(const void* q, const void* k, const void* v,
     p.phi_bstride = phi_batch_broadcast ? 0 : (long long)H * N * R;
     p.phik_bstride = phi_batch_broadcast ? 0 : (long long)H * M * R;
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
-    const int rc = fb_launch_bwd_bf16(p, C, rp, (hipStream_t)stream);
+    const int rc = dtype == FB_F32 ? fb_launch_bwd_f32(p, C, (hipStream_t)stream)
+                                   : fb_launch_bwd_bf16(p, C, rp, (hipStream_t)stream);
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 

@@ -17,6 +17,9 @@ int fb_launch_fwd_bf16_alibi(const FwdParams& p, int C, int qb, hipStream_t stre
 // p.workspace points at fb_bwd_workspace_bytes(B*H*N, B*H*M, C, R) bytes of device scratch.
 int fb_launch_bwd_bf16(const BwdParams& p, int C, int rp, hipStream_t stream);
 size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R);
+// fp32 tensors and fp32 factors (N = M): p.workspace holds one float per query row (a prefix of the
+// size above).
+int fb_launch_bwd_f32(const BwdParams& p, int C, hipStream_t stream);
 // Dense-bias backward (p.bias, p.dbias, p.bias_bstride set; p.R = 0; workspace as above with R = 0).
 int fb_launch_bwd_dense_bf16(const BwdParams& p, int C, hipStream_t stream);
 

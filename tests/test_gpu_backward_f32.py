@@ -1,0 +1,76 @@
+"""GPU parity of the fp32 backward (fb_lowrank_attn_bwd with dtype = FB_F32: the full-precision path,
+fp32 FMA arithmetic) against the float64 oracle's chain-rule gradients.
+Tolerance: max abs error 1e-4 * max(1, max|ref|) per gradient tensor -- the forward's 1e-4 carried
+to gradients whose entries are not O(1) (fp32 rounding is relative: sums over up to 500 keys of terms
+of the gradient's own magnitude at 6e-8 each, plus the forward's lse at 1e-6).  Both the unscaled
+error and the error relative to RMS(ref) are printed."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fb_oracle as O
+from paper_2505_12044_amd import api, workloads as W
+from tests._gpu_util import host, report, workload_to_device
+
+pytestmark = pytest.mark.gpu
+
+NAMES = ("dq", "dk", "dv", "dphi_q", "dphi_k")
+F32_GRAD_TOL = 1e-4
+
+CASES = [
+    ("tiny_fp32", dict()),                                                     # the configuration the oracle runs whole
+    ("tiny_fp32", dict(B=2, H=2, N=200, C=32, R=8)),                            # ragged tail, per-batch factors
+    ("tiny_fp32", dict(B=1, H=2, N=129, C=64, R=5, causal=True)),               # one row past two tiles
+    ("tiny_fp32", dict(B=1, H=1, N=333, C=16, R=0, causal=True)),               # plain attention, head dimension 16
+    ("tiny_fp32", dict(B=2, H=1, N=96, C=128, R=33)),                           # widest rows (C + 64 columns)
+    ("tiny_fp32", dict(B=1, H=2, N=257, C=32, R=32, causal=True)),
+    ("vision_relpos", dict(B=2, H=2, N=256, dtype="f32", phi_dtype="f32")),     # factors shared over the batch
+]
+
+
+@pytest.mark.parametrize("idx", range(len(CASES)))
+def test_bwd_f32(idx):
+    name, ov = CASES[idx]
+    w = W.make_workload(name, with_dout=True, **ov)
+    assert w.dtype == "f32" and (w.R == 0 or w.phi_dtype == "f32")
+    d = workload_to_device(w)
+    out, lse = api.fb_lowrank_attn_fwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], causal=w.causal)
+    grads = api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out, lse, d["dout"],
+                                    causal=w.causal)
+    torch.cuda.synchronize()
+    ref = O.batched_attention_lowrank_grads(w.q, w.k, w.v, w.phi_q, w.phi_k, w.dout, causal=w.causal)
+    label = f"bwd f32 {w.name} B{w.B} H{w.H} N{w.N} C{w.C} R{w.R} causal={w.causal}"
+    for gname, g, r in zip(NAMES, grads, ref):
+        if g is None:
+            assert w.R == 0 and gname.startswith("dphi")
+            continue
+        assert g.dtype == torch.float32
+        got = host(g)
+        assert np.isfinite(got).all(), (label, gname)
+        e, _, big = report(label, gname, got, r)
+        assert e <= F32_GRAD_TOL * max(1.0, big), (label, gname, e, big)
+
+
+def test_bwd_f32_optional_factor_gradients():
+    """dphi_q / dphi_k may be NULL (fixed biases): the other gradients are unchanged."""
+    w = W.make_workload("tiny_fp32", with_dout=True, B=1, H=2, N=100, C=32, R=8)
+    d = workload_to_device(w)
+    out, lse = api.fb_lowrank_attn_fwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"])
+    full = api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out, lse, d["dout"])
+    dq, dk, dv = torch.empty_like(d["q"]), torch.empty_like(d["k"]), torch.empty_like(d["v"])
+    api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out, lse, d["dout"],
+                            grads=(dq, dk, dv, None, None))
+    torch.cuda.synchronize()
+    for a, b in zip(full[:3], (dq, dk, dv)):
+        assert torch.equal(a, b)
+
+
+def test_bwd_f32_deterministic():
+    w = W.make_workload("tiny_fp32", with_dout=True, B=2, H=2, N=300, C=64, R=8, causal=True)
+    d = workload_to_device(w)
+    out, lse = api.fb_lowrank_attn_fwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], causal=True)
+    g1 = api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out, lse, d["dout"], causal=True)
+    g2 = api.fb_lowrank_attn_bwd(d["q"], d["k"], d["v"], d["phi_q"], d["phi_k"], out, lse, d["dout"], causal=True)
+    torch.cuda.synchronize()
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)

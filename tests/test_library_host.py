@@ -96,7 +96,8 @@ def test_dense_and_backward_argument_errors(lib):
         return g(*ptrs, B, H, N, C, R, 0, dtype, phi, 0, 0.0, w, wb, None)
 
     assert bwd(ptrs=[None] + [64] * 12) == 1
-    assert bwd(dtype=api.FB_F32) == 3
+    assert bwd(dtype=api.FB_F32) == 3          # fp32 tensors need fp32 factors
+    assert bwd(dtype=api.FB_F32, phi=api.FB_F32, R=70) == 3
     assert bwd(R=70) == 3                      # padded width > 64
     assert bwd(w=None) == 5
     assert bwd(wb=ws - 1) == 5
