@@ -257,7 +257,7 @@ def main() -> int:
         "settle_s": SETTLE_S,
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {
-            "kernel": "low-rank bf16 forward (fwd_bf16_kernel; fwd_bf16_pp_kernel for long non-causal sequences)",
+            "kernel": "low-rank bf16 forward (fwd_bf16_kernel, four waves per workgroup)",
             "bound": "mfma",
             "achieved": round(kern_tflops, 2),
             "peak": PEAK_BF16_TFLOPS,
