@@ -25,6 +25,8 @@ CASES = [
     ("tiny_fp32", dict(B=2, H=1, N=96, C=128, R=33)),                           # widest rows (C + 64 columns)
     ("tiny_fp32", dict(B=1, H=2, N=257, C=32, R=32, causal=True)),
     ("vision_relpos", dict(B=2, H=2, N=256, dtype="f32", phi_dtype="f32")),     # factors shared over the batch
+    ("tiny_fp32", dict(B=1, H=2, N=1, C=32, R=4)),                              # a single row: P = 1, dS = 0
+    ("tiny_fp32", dict(B=2, H=1, N=31, C=32, R=64, causal=True)),               # less than one tile, widest factors
 ]
 
 
