@@ -119,11 +119,11 @@ struct Cfg {
 // One side per launch: QSIDE writes Aq = [q*scale | phi_q | 0] for the B*H*N query rows,
 // otherwise Ak = [k | phi_k | 0] for the B*H*M key rows.
 template <int C, int RP, bool QSIDE>
-__global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __restrict__ dst) {
+FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const unsigned block) {
     using K = Cfg<C, RP>;
     constexpr int CPR = K::W / 8;
     const int len = QSIDE ? p.N : p.M;
-    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long gid = (long long)block * 256 + threadIdx.x;
     const long long row = gid / CPR;                        // (b*H + h)*len + i
     const int c = (int)(gid - row * CPR);
     const long long rows = (long long)p.B * p.H * len;
@@ -165,12 +165,11 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdParams p, bf16_t* __re
 }
 
 template <int C>
-__global__ __launch_bounds__(256) void bwd_vec_kernel(const bf16_t* __restrict__ out,
-                                                      const bf16_t* __restrict__ dout,
-                                                      const float* __restrict__ lse,
-                                                      float2* __restrict__ vec, long long rows) {
+FB_DEV void bwd_vec_block(const bf16_t* __restrict__ out, const bf16_t* __restrict__ dout,
+                          const float* __restrict__ lse, float2* __restrict__ vec, long long rows,
+                          const unsigned block) {
     constexpr int LPR = C / 8;   // lanes per row, 16 bytes each
-    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long gid = (long long)block * 256 + threadIdx.x;
     const long long row = gid / LPR;
     const int c8 = (int)(gid % LPR);
     float acc = 0.f;
@@ -183,6 +182,22 @@ __global__ __launch_bounds__(256) void bwd_vec_kernel(const bf16_t* __restrict__
 #pragma unroll
     for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
     if (c8 == 0 && row < rows) vec[row] = make_float2(lse[row] * kLog2e, acc);
+}
+
+// The whole pre-pass in one launch: workgroups [0, nb_vec) form the (lse log2 e, D) rows (CV: channels
+// per row of out / dout in memory, 0 = not in this launch), the next nb_q write Aq, the rest Ak.
+template <int C, int RP, int CV>
+__global__ __launch_bounds__(256) void bwd_pre_kernel(BwdParams p, float2* __restrict__ vec, bf16_t* __restrict__ aq,
+                                                      bf16_t* __restrict__ ak, unsigned nb_vec, unsigned nb_q) {
+    const unsigned blk = blockIdx.x;
+    if (blk < nb_vec) {
+        if constexpr (CV > 0)
+            bwd_vec_block<CV>((const bf16_t*)p.out, (const bf16_t*)p.dout, p.lse, vec, (long long)p.B * p.H * p.N, blk);
+    } else if (blk < nb_vec + nb_q) {
+        bwd_prep_block<C, RP, true>(p, aq, blk - nb_vec);
+    } else {
+        bwd_prep_block<C, RP, false>(p, ak, blk - nb_vec - nb_q);
+    }
 }
 
 // Head dimension 16: rows of 16 channels widened to 32 with zeros (the main kernels stream
@@ -911,6 +926,8 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     a.ak = ak;
 
     BwdParams p = pin;
+    const unsigned nb_q = (unsigned)((rows * (K::W / 8) + 255) / 256);
+    const unsigned nb_k = (unsigned)((rowsk * (K::W / 8) + 255) / 256);
     bool narrow = false;
     if constexpr (C == 32) {
         if (pin.Cg == 16) {
@@ -923,8 +940,9 @@ int launch(const BwdParams& pin, hipStream_t stream) {
                                (const bf16_t*)pin.v, vpad, rowsk);
             hipLaunchKernelGGL(bwd_pad16_kernel, dim3((unsigned)((rows * 4 + 255) / 256)), dim3(256), 0, stream,
                                (const bf16_t*)pin.dout, dpad, rows);
-            hipLaunchKernelGGL((bwd_vec_kernel<16>), dim3((unsigned)((rows * 2 + 255) / 256)), dim3(256), 0, stream,
-                               (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
+            const unsigned nb_vec = (unsigned)((rows * 2 + 255) / 256);
+            hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 16>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                               pin, (float2*)ws, aq, ak, nb_vec, nb_q);
             if (hipGetLastError() != hipSuccess) return 1;
             p.v = vpad;
             p.dout = dpad;
@@ -932,17 +950,11 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     }
     if (!narrow) {
         if (pin.Cg != C) return -1;
-        const long long vthreads = rows * (C / 8);
-        hipLaunchKernelGGL((bwd_vec_kernel<C>), dim3((unsigned)((vthreads + 255) / 256)), dim3(256), 0, stream,
-                           (const bf16_t*)pin.out, (const bf16_t*)pin.dout, pin.lse, (float2*)ws, rows);
+        const unsigned nb_vec = (unsigned)((rows * (C / 8) + 255) / 256);
+        hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                           pin, (float2*)ws, aq, ak, nb_vec, nb_q);
         if (hipGetLastError() != hipSuccess) return 1;
     }
-    hipLaunchKernelGGL((bwd_prep_kernel<C, RP, true>), dim3((unsigned)((rows * (K::W / 8) + 255) / 256)),
-                       dim3(256), 0, stream, pin, aq);
-    if (hipGetLastError() != hipSuccess) return 1;
-    hipLaunchKernelGGL((bwd_prep_kernel<C, RP, false>), dim3((unsigned)((rowsk * (K::W / 8) + 255) / 256)),
-                       dim3(256), 0, stream, pin, ak);
-    if (hipGetLastError() != hipSuccess) return 1;
 
     auto set_tiles = [](BwdParams& p, int lane_rows) {
         p.n_tiles = (lane_rows + 127) / 128;
