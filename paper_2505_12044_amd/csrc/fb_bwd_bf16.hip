@@ -591,6 +591,34 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         // Ring of five slots: blocks i (transpose reads), i+1 (row reads), i+2 (prefetch),
         // i+3 (landing), i+4 (being issued).
         static_assert(NSLOT_DKV == 5, "slot arithmetic below assumes five slots");
+        // SV: the S and dP tiles are produced by hand-placed MFMA forms with VGPR results (the
+        // vector ALU reads them next); the compiler's own choice at one wave per SIMD is an AGPR
+        // result and a v_accvgpr_read per element, 32 per block (-4 % per backward on the headline
+        // shape together with the copy-free swap of the tile pairs below).  Not with a dense bias,
+        // whose tile is the chain's start value.
+        // Only where the kernel leaves the register allocator room (operand rows of at most 144
+        // columns): in the wider instantiations every VGPR is taken, the allocator parks values in
+        // spare AGPRs around the statements it cannot see into, and a copy of a tile placed right
+        // behind an inner link of a chain would read it too early (seen as a wrong dK at C = 128,
+        // R = 9 fp32 factors; those instantiations keep the compiler's forms).
+        constexpr bool SV = !DENSE && C + RP <= 144;
+        // one link of the S (n < KS) or dP chain of a block into the VGPR tiles st / dt
+        auto chain_link = [&](int n, f32x16& st, f32x16& dt, bf16x8 o) __attribute__((always_inline)) {
+            constexpr int CS = NA - K::KS;
+            // the last live link of each chain (head dimension 16: the second link of each chain is dead)
+            const bool last_s = n == K::KS - 1, last_d = n == NA - 1;
+            if (n < K::KS) {
+                if (n == 0) mfma32_vdst_first(st, o, l1reg[n]);
+                else if (last_s) mfma32_vdst_last(st, o, l1reg[n]);
+                else mfma32_vdst(st, o, l1reg[n]);
+            } else {
+                if (n == K::KS) mfma32_vdst_first(dt, o, l2reg[n - K::KS]);
+                else if (last_d) mfma32_vdst_last(dt, o, l2reg[n - K::KS]);
+                else mfma32_vdst(dt, o, l2reg[n - K::KS]);
+            }
+            (void)CS;
+        };
+        static_assert(K::KS >= 2 && NA - K::KS >= 2, "a first and a last link per chain");
         issue_block(0, 0); issue_bias(0, 0);
         issue_block(1, 1); issue_bias(1, 1);
         issue_block(2, 2); issue_bias(2, 2);
@@ -607,9 +635,14 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
             for (int n = 0; n < NA; n++) {
                 const bf16x8 o = read_op(r0, t0, n);
-                if (dead_step(n)) continue;
-                if (n < K::KS) sA = mfma32(o, l1reg[n], sA);
-                else dA = mfma32(o, l2reg[n - K::KS], dA);
+                // (SV: a chain's last link carries its wait states, so it is issued even when it adds zeros)
+                if (dead_step(n) && !(SV && (n == NA - 1 || n == K::KS - 1))) continue;
+                if (SV) {
+                    chain_link(n, sA, dA, o);
+                } else {
+                    if (n < K::KS) sA = mfma32(o, l1reg[n], sA);
+                    else dA = mfma32(o, l2reg[n - K::KS], dA);
+                }
             }
         }
         RowBase rb1 = mk_row(kSlotBytes);     // rows of block i+1
@@ -648,9 +681,13 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
             for (int n = 0; n < NA; n++) {
                 opr[(n + LA) % (LA + 1)] = read_op(rb1, tb0, n + LA);   // past NA: output operands of block i
-                if (!dead_step(n)) {
-                    if (n < K::KS) sn = mfma32(opr[n % (LA + 1)], l1reg[n], n == 0 ? sinit : sn);
-                    else dn = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], n == K::KS ? zero : dn);
+                if (!dead_step(n) || (SV && (n == NA - 1 || n == K::KS - 1))) {
+                    if (SV) {
+                        chain_link(n, sn, dn, opr[n % (LA + 1)]);
+                    } else {
+                        if (n < K::KS) sn = mfma32(opr[n % (LA + 1)], l1reg[n], n == 0 ? sinit : sn);
+                        else dn = mfma32(opr[n % (LA + 1)], l2reg[n - K::KS], n == K::KS ? zero : dn);
+                    }
                 }
 #pragma unroll
                 for (int e = (n * 16) / NA; e < ((n + 1) * 16) / NA; e++) {
@@ -712,9 +749,16 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
             rb1 = rb2;
             sl = sl1;
         };
-        // (unrolling by two to swap the score buffers without copies makes the register
-        // allocator shuffle all accumulators between VGPRs and AGPRs; the 32 copies are cheaper)
-        for (int i = 0; i < nIt; i++) {
+        int i = 0;
+        if (SV) {      // two steps at a time: the two pairs of score tiles swap roles without copies
+            for (; i + 2 <= nIt; i += 2) {
+                body(i, sA, dA, sB, dB);
+                body(i + 1, sB, dB, sA, dA);
+            }
+        }
+        // (with compiler-placed MFMA results, unrolling by two makes the register allocator shuffle all
+        // accumulators between VGPRs and AGPRs; the 32 copies are cheaper there)
+        for (; i < nIt; i++) {
             body(i, sA, dA, sB, dB);
             sA = sB;
             dA = dB;

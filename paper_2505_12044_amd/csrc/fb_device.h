@@ -35,6 +35,26 @@ FB_DEV f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// The same instruction with the result pinned to ordinary registers.  A kernel that runs one wave
+// per SIMD owns 512 registers, 256 of them accumulation registers (AGPRs) that only MFMAs and
+// v_accvgpr moves can touch; the compiler then gives every MFMA an AGPR result, also the score
+// tiles the vector ALU reads next (one v_accvgpr_read per element).  These forms keep such tiles in
+// VGPRs while the builtin form keeps the long-lived output accumulators in AGPRs.
+// The compiler does not know what the statements are, so it places none of the wait states an MFMA
+// result needs before another kind of instruction may read or overwrite it (11 after an 8-pass
+// MFMA).  Inside a chain the next link is the next such statement; the last link of a chain is
+// issued with the _last form, which carries the wait states itself, so that whatever the compiler
+// puts behind it (a copy, a spill, a reuse of the registers of a result nobody reads) is safe.
+FB_DEV void mfma32_vdst_first(f32x16& d, bf16x8 a, bf16x8 b) {    // d = a . b
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
+}
+FB_DEV void mfma32_vdst(f32x16& d, bf16x8 a, bf16x8 b) {          // d += a . b
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+}
+FB_DEV void mfma32_vdst_last(f32x16& d, bf16x8 a, bf16x8 b) {     // d += a . b, then the result's wait states
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 7\n\ts_nop 2" : "+v"(d) : "v"(a), "v"(b));
+}
+
 FB_DEV bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 FB_DEV u32x4 as_uint4(bf16x8 v) { return __builtin_bit_cast(u32x4, v); }
 

@@ -226,3 +226,20 @@ def test_tune_knob(lib):
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(api.FlashBiasError):
         api.load_library(str(tmp_path / "libflashbias.so"))
+
+
+def test_hand_placed_mfma_forms_keep_their_wait_states():
+    """The backward's inline-assembly MFMA forms are invisible to the compiler's hazard padding: the
+    generated code must show no instruction touching such a result inside its wait-state window
+    (compiles one source to assembly, about a minute and a half).  The scanner itself is checked on
+    a planted violation first."""
+    from paper_2505_12044_amd import check_mfma_hazards as chk
+    planted = ("_Zk:\n\tv_mfma_f32_32x32x16_bf16 v[0:15], v[16:19], v[20:23], v[0:15]\n"
+               "\tv_mfma_f32_32x32x16_bf16 v[0:15], v[24:27], v[20:23], v[0:15]\n"
+               "\tv_add_f32_e32 v40, v3, v41\n")
+    seen, found = chk.scan_asm(planted)
+    assert seen == 2 and len(found) == 1
+    fenced = planted.replace("\tv_add_f32", "\ts_nop 7\n\ts_nop 2\n\tv_add_f32")
+    assert chk.scan_asm(fenced)[1] == []
+    seen, found = chk.check()
+    assert seen > 0 and found == [], found[:3]
