@@ -74,8 +74,8 @@ def main() -> int:
                          "no timing output")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, "
-              "'How the path would shard'); run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (attention shards over "
+              "batch and heads with no communication); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
