@@ -105,7 +105,8 @@ int fb_lowrank_attn_fwd(const void* q, const void* k, const void* v,
 /*
  * Cross-attention form of fb_lowrank_attn_fwd (Eq. 1 with N queries and M keys): q, out
  * [B,H,N,C], k, v [B,H,M,C], phi_q [Bp,H,N,R], phi_k [Bp,H,M,R], lse [B,H,N].  No causal mask
- * (its alignment is undefined for N != M).  Needs dtype = FB_BF16 when N != M.
+ * (its alignment is undefined for N != M).  dtype FB_BF16 or FB_F32 (fp32 factors), as for
+ * fb_lowrank_attn_fwd.
  */
 int fb_lowrank_xattn_fwd(const void* q, const void* k, const void* v,
                          const void* phi_q, const void* phi_k, void* out, float* lse,
@@ -275,7 +276,7 @@ int fb_dense_bias_attn_bwd(const void* q, const void* k, const void* v, const vo
 /*
  * Cross-attention form of fb_lowrank_attn_bwd: q, out, dout, dq [B,H,N,C]; k, v, dk, dv
  * [B,H,M,C]; phi_q, dphi_q [.,H,N,R]; phi_k, dphi_k [.,H,M,R]; lse [B,H,N].  No causal mask.
- * Workspace as for fb_lowrank_attn_bwd, sized by the query below.
+ * dtype FB_BF16 or FB_F32.  Workspace as for fb_lowrank_attn_bwd, sized by the query below.
  */
 size_t fb_lowrank_xattn_bwd_workspace_bytes(int B, int H, int N, int M, int C, int R, fb_dtype dtype);
 

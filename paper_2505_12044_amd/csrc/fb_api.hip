@@ -134,7 +134,7 @@ static int lowrank_fwd_impl(const void* q, const void* k, const void* v,
     if (dtype != FB_F32 && dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (dtype == FB_F32 && R > 0 && phi_dtype != FB_F32) return FB_ERR_UNSUPPORTED;
-    if (N != M && (causal || dtype != FB_BF16)) return FB_ERR_UNSUPPORTED;
+    if (N != M && causal) return FB_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
         return FB_ERR_ALIGN;
     if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k))) return FB_ERR_ALIGN;
@@ -380,7 +380,7 @@ static int lowrank_bwd_impl(const void* q, const void* k, const void* v,
     if (dtype != FB_BF16 && dtype != FB_F32) return FB_ERR_UNSUPPORTED;
     if (phi_dtype != FB_F32 && phi_dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
     if (dtype == FB_F32 && R > 0 && phi_dtype != FB_F32) return FB_ERR_UNSUPPORTED;
-    if (N != M && (causal || dtype != FB_BF16)) return FB_ERR_UNSUPPORTED;
+    if (N != M && causal) return FB_ERR_UNSUPPORTED;
     const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv};
     for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
     if (R > 0 && (!aligned16(phi_q) || !aligned16(phi_k) || !aligned16(dphi_q) || !aligned16(dphi_k)))

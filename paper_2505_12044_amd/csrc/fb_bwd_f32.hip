@@ -51,15 +51,18 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
     const int bh = blockIdx.x / p.n_tiles;
     const int rt = blockIdx.x % p.n_tiles;
     const int b = bh / p.H, h = bh % p.H;
-    const int N = p.N, R = p.R;
+    const int N = p.N, M = p.M, R = p.R;       // N queries, M keys (M = N unless cross-attention)
+    const int NL = KEYSIDE ? M : N;            // rows on this kernel's own side
+    const int NO = KEYSIDE ? N : M;            // rows on the streamed side
     const int row = rt * kRows + (tid >> 2);
-    const bool valid = row < N;
-    const int rowc = valid ? row : N - 1;     // clamped: finite values, never stored
+    const bool valid = row < NL;
+    const int rowc = valid ? row : NL - 1;    // clamped: finite values, never stored
 
-    const size_t base = (size_t)bh * N * C;
+    const size_t base = (size_t)bh * N * C;    // query-side tensors
+    const size_t kbase = (size_t)bh * M * C;   // key-side tensors
     const float* qg = (const float*)p.q + base;
-    const float* kg = (const float*)p.k + base;
-    const float* vg = (const float*)p.v + base;
+    const float* kg = (const float*)p.k + kbase;
+    const float* vg = (const float*)p.v + kbase;
     const float* og = (const float*)p.out + base;
     const float* dog = (const float*)p.dout + base;
     const float* lseg = p.lse + (size_t)bh * N;
@@ -68,7 +71,7 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
     const float* pkg = nullptr;
     if (RP > 0) {
         pqg = (const float*)p.phi_q + (size_t)b * p.phi_bstride + (size_t)h * N * R;
-        pkg = (const float*)p.phi_k + (size_t)b * p.phik_bstride + (size_t)h * N * R;
+        pkg = (const float*)p.phi_k + (size_t)b * p.phik_bstride + (size_t)h * M * R;
     }
 
     // this thread's channels of its row: a[u] <-> column t + 4u of [x | phi], e[u] <-> channel t + 4u
@@ -100,10 +103,10 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
     }
 
     // range of the other side this workgroup's rows can see
-    int o_begin = 0, o_end = N;
-    if (p.causal) {
+    int o_begin = 0, o_end = NO;
+    if (p.causal) {                                              // (N = M)
         if (KEYSIDE) o_begin = (rt * kRows / kTile) * kTile;      // queries i >= j
-        else o_end = min(N, (rt + 1) * kRows);                   // keys j <= i
+        else o_end = min(NO, (rt + 1) * kRows);                  // keys j <= i
     }
 
     for (int o0 = o_begin; o0 < o_end; o0 += kTile) {
@@ -112,7 +115,7 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
             const int rr = x / W, c = x % W;
             const int orow = o0 + rr;
             float val = 0.f;
-            if (orow < N) {
+            if (orow < NO) {
                 if (c < C) val = KEYSIDE ? qg[(size_t)orow * C + c] * p.scale : kg[(size_t)orow * C + c];
                 else if (c - C < R) val = KEYSIDE ? pqg[(size_t)orow * R + (c - C)] : pkg[(size_t)orow * R + (c - C)];
             }
@@ -121,12 +124,12 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
         for (int x = tid; x < kTile * C; x += kThreads) {
             const int rr = x / C, c = x % C;
             const int orow = o0 + rr;
-            tv[rr][c] = orow < N ? (KEYSIDE ? dog[(size_t)orow * C + c] : vg[(size_t)orow * C + c]) : 0.f;
+            tv[rr][c] = orow < NO ? (KEYSIDE ? dog[(size_t)orow * C + c] : vg[(size_t)orow * C + c]) : 0.f;
         }
         if (KEYSIDE && tid < kTile) {
             const int orow = o0 + tid;
-            tl[tid] = orow < N ? lseg[orow] : 0.f;
-            td[tid] = orow < N ? Dg[orow] : 0.f;
+            tl[tid] = orow < NO ? lseg[orow] : 0.f;
+            td[tid] = orow < NO ? Dg[orow] : 0.f;
         }
         __syncthreads();
 
@@ -143,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
             // query i and key j of this pair
             const int qi = KEYSIDE ? orow : row;
             const int kj = KEYSIDE ? row : orow;
-            const bool live = orow < N && valid && !(p.causal && kj > qi);
+            const bool live = orow < NO && valid && !(p.causal && kj > qi);
             const float lse_i = KEYSIDE ? tl[rr] : lse_r;
             const float d_i = KEYSIDE ? td[rr] : d_r;
             const float pr = live ? expf(s - lse_i) : 0.f;
@@ -158,9 +161,9 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
     }
 
     if (!valid) return;
-    float* dxg = (float*)(KEYSIDE ? p.dk : p.dq) + base;
-    float* dphig = (float*)(KEYSIDE ? p.dphi_k : p.dphi_q);      // [B,H,N,R], per batch element; may be NULL
-    if (dphig) dphig += (size_t)bh * N * R;
+    float* dxg = (float*)(KEYSIDE ? p.dk : p.dq) + (KEYSIDE ? kbase : base);
+    float* dphig = (float*)(KEYSIDE ? p.dphi_k : p.dphi_q);      // [B,H,N or M,R], per batch element; may be NULL
+    if (dphig) dphig += (size_t)bh * NL * R;
 #pragma unroll
     for (int u = 0; u < WQ; u++) {
         const int c = t + 4 * u;
@@ -169,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
         else if (c - C < R && dphig) dphig[(size_t)row * R + (c - C)] = acc_a[u];
     }
     if (KEYSIDE) {
-        float* dvg = (float*)p.dv + base;
+        float* dvg = (float*)p.dv + kbase;
 #pragma unroll
         for (int u = 0; u < CQ; u++) dvg[(size_t)row * C + t + 4 * u] = acc_e[u];
     }
@@ -178,11 +181,13 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
 template <int C, int RP>
 int launch(const BwdParams& pin, hipStream_t stream) {
     BwdParams p = pin;
-    p.n_tiles = (p.N + kRows - 1) / kRows;
-    p.total_tiles = p.B * p.H * p.n_tiles;
     float* Dws = (float*)p.workspace;
+    p.n_tiles = (p.N + kRows - 1) / kRows;         // query-side pass: tiles of query rows
+    p.total_tiles = p.B * p.H * p.n_tiles;
     hipLaunchKernelGGL((bwd_f32_kernel<C, RP, false>), dim3(p.total_tiles), dim3(kThreads), 0, stream, p, Dws);
     if (hipGetLastError() != hipSuccess) return 1;
+    p.n_tiles = (p.M + kRows - 1) / kRows;         // key-side pass: tiles of key rows
+    p.total_tiles = p.B * p.H * p.n_tiles;
     hipLaunchKernelGGL((bwd_f32_kernel<C, RP, true>), dim3(p.total_tiles), dim3(kThreads), 0, stream, p, Dws);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
@@ -197,10 +202,11 @@ int dispatch_c(const BwdParams& p, hipStream_t stream) {
 
 }  // namespace
 
-// fp32 tensors and fp32 factors, N = M; p.workspace: at least 4 B H N bytes (the D row sums).
+// fp32 tensors and fp32 factors (N queries, M keys; causal needs N = M); p.workspace: at least
+// 4 B H N bytes (the D row sums).
 // Returns 0 on success, 1 on launch failure, -1 when no instantiation fits.
 int fb_launch_bwd_f32(const BwdParams& p, int C, hipStream_t stream) {
-    if (p.R > 64 || p.N != p.M) return -1;
+    if (p.R > 64 || (p.causal && p.N != p.M)) return -1;
     switch (C) {
         case 16: return dispatch_c<16>(p, stream);
         case 32: return dispatch_c<32>(p, stream);

@@ -31,23 +31,23 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
     const int bh = blockIdx.x / p.n_qtiles;
     const int qt = blockIdx.x % p.n_qtiles;
     const int b = bh / p.H, h = bh % p.H;
-    const int N = p.N, R = p.R;
+    const int N = p.N, M = p.M, R = p.R;      // N queries, M keys (M = N unless cross-attention)
     const int i = qt * kThreads + tid;
     const bool valid = i < N;
 
     const size_t base = (size_t)bh * N * C;
+    const size_t kbase = (size_t)bh * M * C;
     const float* qg = (const float*)p.q + base;
-    const float* kg = (const float*)p.k + base;
-    const float* vg = (const float*)p.v + base;
+    const float* kg = (const float*)p.k + kbase;
+    const float* vg = (const float*)p.v + kbase;
     const float* pqg = nullptr;
     const float* pkg = nullptr;
     if (RP > 0) {
-        const size_t pbase = (size_t)b * p.phi_bstride + (size_t)h * N * R;
-        pqg = (const float*)p.phi_q + pbase;
-        pkg = (const float*)p.phi_k + pbase;
+        pqg = (const float*)p.phi_q + (size_t)b * p.phi_bstride + (size_t)h * N * R;
+        pkg = (const float*)p.phi_k + (size_t)b * p.phik_bstride + (size_t)h * M * R;
     }
     const float* bg = nullptr;
-    if (DENSE) bg = (const float*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * N;
+    if (DENSE) bg = (const float*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * M;
 
     float qr[W];
     float o[C];
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
     for (int c = 0; c < C; c++) o[c] = 0.f;
 
     float m = -INFINITY, l = 0.f;
-    const int n_keys = p.causal ? min(N, (qt + 1) * kThreads) : N;
+    const int n_keys = p.causal ? min(M, (qt + 1) * kThreads) : M;
 
     for (int j0 = 0; j0 < n_keys; j0 += kTK) {
         __syncthreads();
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
             const int jj = e / W, c = e % W;
             const int j = j0 + jj;
             float x = 0.f;
-            if (j < N) {
+            if (j < M) {
                 if (c < C) x = kg[(size_t)j * C + c];
                 else if (c - C < R) x = pkg[(size_t)j * R + (c - C)];
             }
@@ -92,13 +92,13 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
         for (int e = tid; e < kTK * C; e += kThreads) {
             const int jj = e / C, c = e % C;
             const int j = j0 + jj;
-            vs[jj][c] = j < N ? vg[(size_t)j * C + c] : 0.f;
+            vs[jj][c] = j < M ? vg[(size_t)j * C + c] : 0.f;
         }
         if (DENSE) {
             for (int e = tid; e < kThreads * kTK; e += kThreads) {
                 const int rr = e / kTK, jj = e % kTK;
                 const int row = qt * kThreads + rr, j = j0 + jj;
-                bs[rr][jj] = (row < N && j < N) ? bg[(size_t)row * N + j] : 0.f;
+                bs[rr][jj] = (row < N && j < M) ? bg[(size_t)row * M + j] : 0.f;
             }
         }
         __syncthreads();
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(FwdParams p) {
             for (int c = 0; c < W; c++) acc = fmaf(qr[c], ks[jj][c], acc);
             const int j = j0 + jj;
             if (DENSE) acc += bs[tid][jj];
-            if (j >= N || (p.causal && j > i)) acc = -INFINITY;
+            if (j >= M || (p.causal && j > i)) acc = -INFINITY;
             s[jj] = acc;
             mt = fmaxf(mt, acc);
         }

@@ -76,3 +76,36 @@ def test_bwd_f32_deterministic():
     torch.cuda.synchronize()
     for a, b in zip(g1, g2):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("B,H,N,M,C,R", [(2, 2, 150, 333, 32, 8), (1, 2, 300, 70, 64, 5), (1, 1, 97, 1, 16, 0),
+                                         (2, 1, 64, 129, 128, 33)])
+def test_xattn_f32(B, H, N, M, C, R):
+    """Cross-attention (N queries, M keys) on the fp32 path, forward and backward, per (b, h) against
+    the oracle's single-head functions; factors shared over the batch in the first case."""
+    rng = np.random.default_rng(100 * N + M)
+    f32 = lambda *s: rng.standard_normal(s).astype(np.float32)
+    q, dout, k, v = f32(B, H, N, C), f32(B, H, N, C), f32(B, H, M, C), f32(B, H, M, C)
+    Bp = 1 if (B, N) == (2, 150) else B
+    pq = (0.5 * f32(Bp, H, N, R)) if R else None
+    pk = (0.5 * f32(Bp, H, M, R)) if R else None
+    t = lambda x: None if x is None else torch.from_numpy(x).cuda()
+    d = [t(q), t(k), t(v), t(pq), t(pk)]
+    out, lse = api.fb_lowrank_xattn_fwd(*d)
+    grads = api.fb_lowrank_xattn_bwd(*d, out, lse, t(dout))
+    torch.cuda.synchronize()
+    for b in range(B):
+        for h in range(H):
+            fq = pq[min(b, Bp - 1), h] if R else np.zeros((N, 0))
+            fk = pk[min(b, Bp - 1), h] if R else np.zeros((M, 0))
+            ro, rl = O.attention_lowrank(q[b, h], k[b, h], v[b, h], fq, fk)
+            label = f"xattn f32 N{N} M{M} C{C} R{R} (b,h)=({b},{h})"
+            for name, got, ref in (("out", out[b, h], ro), ("lse", lse[b, h], rl)):
+                e, _, _ = report(label, name, host(got), ref)
+                assert e <= 1e-4, (label, name, e)
+            ref = O.attention_lowrank_grads(q[b, h], k[b, h], v[b, h], fq, fk, dout[b, h])
+            for name, g, r in zip(NAMES, grads, ref):
+                if g is None:
+                    continue
+                e, _, big = report(label, name, host(g[b, h]), r)
+                assert e <= F32_GRAD_TOL * max(1.0, big), (label, name, e, big)
