@@ -262,7 +262,8 @@ int fb_lowrank_attn_bwd_noalloc(const void* q, const void* k, const void* v,
  * to write the dense gradient dbias [B,H,N,N] (= dL/dS, storage type `dtype`, always per batch
  * element), the N x N object that the factorised form never materialises (Sec. 4.3).  Entries
  * above the diagonal are zero when causal.
- * Needs dtype = FB_BF16 and N % 8 == 0.  Workspace as for fb_lowrank_attn_bwd with R = 0.
+ * dtype FB_BF16 (needs N % 8 == 0) or FB_F32 (the fp32 FMA path).  Workspace as for
+ * fb_lowrank_attn_bwd with R = 0.
  */
 size_t fb_dense_bias_attn_bwd_workspace_bytes(int B, int H, int N, int C, fb_dtype dtype);
 

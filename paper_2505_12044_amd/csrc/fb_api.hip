@@ -455,8 +455,8 @@ int fb_dense_bias_attn_bwd(const void* q, const void* k, const void* v, const vo
     if (!q || !k || !v || !bias || !out || !lse || !dout || !dq || !dk || !dv || !dbias) return FB_ERR_NULL;
     if (int st = check_common(B, H, N, C, 0)) return st;
     if ((long long)B * H * N * (long long)N >= (1LL << 40)) return FB_ERR_SHAPE;
-    if (dtype != FB_BF16) return FB_ERR_UNSUPPORTED;
-    if ((N % 8) != 0) return FB_ERR_UNSUPPORTED;      // bias rows are copied in 16-byte pieces
+    if (dtype != FB_BF16 && dtype != FB_F32) return FB_ERR_UNSUPPORTED;
+    if (dtype == FB_BF16 && (N % 8) != 0) return FB_ERR_UNSUPPORTED;      // bf16 bias rows are copied in 16-byte pieces
     const void* ptrs[] = {q, k, v, bias, out, lse, dout, dq, dk, dv, dbias};
     for (const void* ptr : ptrs) if (!aligned16(ptr)) return FB_ERR_ALIGN;
     if (!workspace || workspace_bytes < bwd_ws_impl(B, H, N, N, C, 0)) return FB_ERR_WORKSPACE;
@@ -474,7 +474,8 @@ int fb_dense_bias_attn_bwd(const void* q, const void* k, const void* v, const vo
     p.phi_bstride = 0;
     p.phik_bstride = 0;
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
-    const int rc = fb_launch_bwd_dense_bf16(p, C, (hipStream_t)stream);
+    const int rc = dtype == FB_F32 ? fb_launch_bwd_dense_f32(p, C, (hipStream_t)stream)
+                                   : fb_launch_bwd_dense_bf16(p, C, (hipStream_t)stream);
     return rc == 0 ? FB_OK : (rc < 0 ? FB_ERR_UNSUPPORTED : FB_ERR_LAUNCH);
 }
 

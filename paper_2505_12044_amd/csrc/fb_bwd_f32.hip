@@ -35,9 +35,11 @@ __device__ __forceinline__ float quad_sum(float x) {
     return x;
 }
 
-// KEYSIDE = false: rows are queries, tiles are keys; outputs dq, dphi_q, D.
+// KEYSIDE = false: rows are queries, tiles are keys; outputs dq, dphi_q, D (and dBias when DENSE).
 // KEYSIDE = true:  rows are keys, tiles are queries; outputs dk, dv, dphi_k.
-template <int C, int RP, bool KEYSIDE>
+// DENSE: the bias is a materialised [N, M] matrix per head, added to the scores (the training-side
+// baseline of Sec. 4.3); its gradient dBias = dS is written by the query-side pass, zero where masked.
+template <int C, int RP, bool KEYSIDE, bool DENSE = false>
 __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* __restrict__ Dws) {
     constexpr int W = C + RP;
     constexpr int WQ = W / 4, CQ = C / 4;
@@ -45,6 +47,9 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
     __shared__ float ts[kTile][W + 1];       // tile rows [x | phi] of the other side (queries: x = q*scale)
     __shared__ float tv[kTile][C + 1];       // tile rows v (query side) or dout (key side)
     __shared__ float tl[kTile], td[kTile];   // key side: lse and D of the tile's queries
+    // dense bias of (this workgroup's rows) x (the tile's rows): [own row][tile row] on the query side,
+    // [tile row][own row] on the key side, so that both are filled along the key index (coalesced)
+    __shared__ float tb[DENSE ? (KEYSIDE ? kTile : kRows) : 1][DENSE ? (KEYSIDE ? kRows : kTile) + 1 : 1];
 
     const int tid = threadIdx.x;
     const int t = tid & 3;
@@ -67,6 +72,12 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
     const float* dog = (const float*)p.dout + base;
     const float* lseg = p.lse + (size_t)bh * N;
     float* Dg = Dws + (size_t)bh * N;
+    const float* bg = nullptr;
+    float* dbg = nullptr;
+    if (DENSE) {
+        bg = (const float*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * M;
+        dbg = (float*)p.dbias + (size_t)bh * N * M;
+    }
     const float* pqg = nullptr;
     const float* pkg = nullptr;
     if (RP > 0) {
@@ -131,6 +142,21 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
             tl[tid] = orow < NO ? lseg[orow] : 0.f;
             td[tid] = orow < NO ? Dg[orow] : 0.f;
         }
+        if (DENSE) {
+            if (KEYSIDE) {       // tb[query of the tile][key of this workgroup]
+                for (int x = tid; x < kTile * kRows; x += kThreads) {
+                    const int rr = x / kRows, cc = x % kRows;
+                    const int qi = o0 + rr, kj = rt * kRows + cc;
+                    tb[rr][cc] = (qi < N && kj < M) ? bg[(size_t)qi * M + kj] : 0.f;
+                }
+            } else {             // tb[query of this workgroup][key of the tile]
+                for (int x = tid; x < kRows * kTile; x += kThreads) {
+                    const int rr = x / kTile, cc = x % kTile;
+                    const int qi = rt * kRows + rr, kj = o0 + cc;
+                    tb[rr][cc] = (qi < N && kj < M) ? bg[(size_t)qi * M + kj] : 0.f;
+                }
+            }
+        }
         __syncthreads();
 
 #pragma unroll 2
@@ -141,7 +167,8 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
             for (int u = 0; u < WQ; u++) sp = fmaf(a[u], ts[rr][t + 4 * u], sp);
 #pragma unroll
             for (int u = 0; u < CQ; u++) dpp = fmaf(e[u], tv[rr][t + 4 * u], dpp);
-            const float s = quad_sum(sp);
+            float s = quad_sum(sp);
+            if (DENSE) s += KEYSIDE ? tb[rr][tid >> 2] : tb[tid >> 2][rr];
             const float dp = quad_sum(dpp);     // dout_i . v_j
             // query i and key j of this pair
             const int qi = KEYSIDE ? orow : row;
@@ -151,6 +178,8 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
             const float d_i = KEYSIDE ? td[rr] : d_r;
             const float pr = live ? expf(s - lse_i) : 0.f;
             const float ds = pr * (dp - d_i);
+            // dBias = dS: the four threads of a row take turns over the tile's keys
+            if (DENSE && !KEYSIDE && valid && orow < NO && (rr & 3) == t) dbg[(size_t)row * M + orow] = ds;
 #pragma unroll
             for (int u = 0; u < WQ; u++) acc_a[u] = fmaf(ds, ts[rr][t + 4 * u], acc_a[u]);
             if (KEYSIDE) {
@@ -160,6 +189,18 @@ __global__ __launch_bounds__(kThreads) void bwd_f32_kernel(BwdParams p, float* _
         }
     }
 
+    if (DENSE && !KEYSIDE && p.causal) {
+        // the keys past this workgroup's last query were never visited: their dBias entries are zero
+        const int k0 = ((o_end + kTile - 1) / kTile) * kTile;
+        const int w = M - k0;
+        if (w > 0) {
+            for (long long x = tid; x < (long long)kRows * w; x += kThreads) {
+                const int rr = (int)(x / w), cc = (int)(x % w);
+                const int qi = rt * kRows + rr;
+                if (qi < N) dbg[(size_t)qi * M + k0 + cc] = 0.f;
+            }
+        }
+    }
     if (!valid) return;
     float* dxg = (float*)(KEYSIDE ? p.dk : p.dq) + (KEYSIDE ? kbase : base);
     float* dphig = (float*)(KEYSIDE ? p.dphi_k : p.dphi_q);      // [B,H,N or M,R], per batch element; may be NULL
@@ -193,6 +234,18 @@ int launch(const BwdParams& pin, hipStream_t stream) {
 }
 
 template <int C>
+int launch_dense(const BwdParams& pin, hipStream_t stream) {
+    BwdParams p = pin;
+    float* Dws = (float*)p.workspace;
+    p.n_tiles = (p.N + kRows - 1) / kRows;
+    p.total_tiles = p.B * p.H * p.n_tiles;
+    hipLaunchKernelGGL((bwd_f32_kernel<C, 0, false, true>), dim3(p.total_tiles), dim3(kThreads), 0, stream, p, Dws);
+    if (hipGetLastError() != hipSuccess) return 1;
+    hipLaunchKernelGGL((bwd_f32_kernel<C, 0, true, true>), dim3(p.total_tiles), dim3(kThreads), 0, stream, p, Dws);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+template <int C>
 int dispatch_c(const BwdParams& p, hipStream_t stream) {
     if (p.R == 0) return launch<C, 0>(p, stream);
     if (p.R <= 8) return launch<C, 8>(p, stream);
@@ -212,6 +265,18 @@ int fb_launch_bwd_f32(const BwdParams& p, int C, hipStream_t stream) {
         case 32: return dispatch_c<32>(p, stream);
         case 64: return dispatch_c<64>(p, stream);
         case 128: return dispatch_c<128>(p, stream);
+        default: return -1;
+    }
+}
+
+// Dense-bias backward in fp32 (p.bias, p.dbias, p.bias_bstride set; p.R = 0; N = M).
+int fb_launch_bwd_dense_f32(const BwdParams& p, int C, hipStream_t stream) {
+    if (p.N != p.M) return -1;
+    switch (C) {
+        case 16: return launch_dense<16>(p, stream);
+        case 32: return launch_dense<32>(p, stream);
+        case 64: return launch_dense<64>(p, stream);
+        case 128: return launch_dense<128>(p, stream);
         default: return -1;
     }
 }

@@ -20,6 +20,7 @@ size_t fb_bwd_workspace_bytes(long long rows_q, long long rows_k, int C, int R);
 // fp32 tensors and fp32 factors (N = M): p.workspace holds one float per query row (a prefix of the
 // size above).
 int fb_launch_bwd_f32(const BwdParams& p, int C, hipStream_t stream);
+int fb_launch_bwd_dense_f32(const BwdParams& p, int C, hipStream_t stream);
 // Dense-bias backward (p.bias, p.dbias, p.bias_bstride set; p.R = 0; workspace as above with R = 0).
 int fb_launch_bwd_dense_bf16(const BwdParams& p, int C, hipStream_t stream);
 

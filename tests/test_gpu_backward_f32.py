@@ -109,3 +109,33 @@ def test_xattn_f32(B, H, N, M, C, R):
                     continue
                 e, _, big = report(label, name, host(g[b, h]), r)
                 assert e <= F32_GRAD_TOL * max(1.0, big), (label, name, e, big)
+
+
+@pytest.mark.parametrize("B,H,N,C,causal,shared", [(2, 2, 150, 32, False, True), (1, 2, 333, 64, True, False),
+                                                   (1, 1, 61, 16, True, True), (2, 1, 97, 128, False, False)])
+def test_dense_bias_backward_f32(B, H, N, C, causal, shared):
+    """fb_dense_bias_attn_bwd on the fp32 path (any N): dq, dk, dv and the dense dBias against the oracle;
+    the output buffer starts as NaN, so the zero entries above the diagonal must have been written."""
+    rng = np.random.default_rng(31 * N + C)
+    f32 = lambda *s: rng.standard_normal(s).astype(np.float32)
+    q, k, v, dout = f32(B, H, N, C), f32(B, H, N, C), f32(B, H, N, C), f32(B, H, N, C)
+    bias = f32(1 if shared else B, H, N, N)
+    t = lambda x: torch.from_numpy(x).cuda()
+    d = [t(q), t(k), t(v)]
+    out, lse = api.fb_dense_bias_attn_fwd(*d, t(bias), causal=causal)
+    grads = (torch.empty_like(d[0]), torch.empty_like(d[1]), torch.empty_like(d[2]),
+             torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda"))
+    dq, dk, dv, dbias = api.fb_dense_bias_attn_bwd(*d, t(bias), out, lse, t(dout), causal=causal, grads=grads)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for h in range(H):
+            ref = O.attention_with_bias_grads(q[b, h], k[b, h], v[b, h], bias[0 if shared else b, h], dout[b, h],
+                                              causal=causal)
+            label = f"dense bwd f32 N{N} C{C} causal={causal} shared={shared} (b,h)=({b},{h})"
+            for name, g, r in zip(("dq", "dk", "dv", "dbias"), (dq, dk, dv, dbias), ref):
+                got = host(g[b, h])
+                assert np.isfinite(got).all(), (label, name)
+                e, _, big = report(label, name, got, r)
+                assert e <= F32_GRAD_TOL * max(1.0, big), (label, name, e, big)
+            if causal:
+                assert float(np.abs(np.triu(host(dbias[b, h]), 1)).max()) == 0.0
