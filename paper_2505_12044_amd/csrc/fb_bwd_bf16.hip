@@ -118,16 +118,24 @@ struct Cfg {
 // ------------------------------------------------------------------------------------------
 // One side per launch: QSIDE writes Aq = [q*scale | phi_q | 0] for the B*H*N query rows,
 // otherwise Ak = [k | phi_k | 0] for the B*H*M key rows.
+// A workgroup covers kPrepRows<C, RP> whole rows (one thread per 16-byte piece; the few threads past
+// the last whole row idle), so a thread's row and piece come from its index by a division by a
+// constant, and the head and position of the row from one block-uniform division plus a wrap.
+template <int C, int RP>
+constexpr int kPrepRows = 256 / (Cfg<C, RP>::W / 8);
+
 template <int C, int RP, bool QSIDE>
 FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const unsigned block) {
     using K = Cfg<C, RP>;
     constexpr int CPR = K::W / 8;
-    const int len = QSIDE ? p.N : p.M;
-    const long long gid = (long long)block * 256 + threadIdx.x;
-    const long long row = gid / CPR;                        // (b*H + h)*len + i
-    const int c = (int)(gid - row * CPR);
+    constexpr int RPB = kPrepRows<C, RP>;
+    const unsigned len = (unsigned)(QSIDE ? p.N : p.M);
+    const unsigned dr = threadIdx.x / CPR;
+    const int c = (int)(threadIdx.x - dr * CPR);
+    const long long row0 = (long long)block * RPB;            // block-uniform
+    const long long row = row0 + dr;                          // (b*H + h)*len + i
     const long long rows = (long long)p.B * p.H * len;
-    if (row >= rows) return;
+    if (dr >= (unsigned)RPB || row >= rows) return;
     bf16x8 a;
     if (c < C / 8) {
         bf16x8 x;
@@ -146,19 +154,34 @@ FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const u
     } else {
         const bool f32 = p.phi_f32 != 0;
         const size_t esz = f32 ? 4 : 2;
-        const long long bh = row / len;
-        const int i = (int)(row - bh * len);
-        const int bb = (int)(bh / p.H), h = (int)(bh - (long long)bb * p.H);
+        // rows < 2^31: the block's first row splits into head and position once, the thread's row wraps
+        const unsigned bh0 = (unsigned)((unsigned long long)row0 / len);
+        unsigned bb = bh0 / (unsigned)p.H;
+        unsigned h = bh0 - bb * (unsigned)p.H;
+        unsigned i = (unsigned)((unsigned long long)row0 - (unsigned long long)bh0 * len) + dr;
+        while (i >= len) {
+            i -= len;
+            if (++h == (unsigned)p.H) { h = 0; ++bb; }
+        }
+        const int pc = c - C / 8;
         if (p.slopes != nullptr) {
             // ALiBi factors of Example 3.4 from the head's slope and the row's position (App. D)
             const float m = p.slopes[h];
             float pair[2];
             pair[0] = QSIDE ? -m * (float)i : 1.f;
             pair[1] = QSIDE ? m : (float)i;
-            a = phi_chunk_switch<QSIDE>(pair, c - C / 8, 2, true);
+            a = phi_chunk_switch<QSIDE>(pair, pc, 2, true);
         } else {
             const size_t off = ((size_t)bb * (QSIDE ? p.phi_bstride : p.phik_bstride) + ((size_t)h * len + i) * p.R) * esz;
-            a = phi_chunk_switch<QSIDE>((const unsigned char*)(QSIDE ? p.phi_q : p.phi_k) + off, c - C / 8, p.R, f32);
+            const unsigned char* src = (const unsigned char*)(QSIDE ? p.phi_q : p.phi_k) + off;
+            if (!f32 && (p.R & 7) == 0) {
+                // bf16 factors in whole 16-byte pieces: a copy (rows and the batch stride are then multiples of 16 bytes)
+                u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+                if (pc * 8 < p.R) raw = *(const u32x4*)(src + pc * 16);
+                a = as_bf16x8(raw);
+            } else {
+                a = phi_chunk_switch<QSIDE>(src, pc, p.R, f32);
+            }
         }
     }
     *(u32x4*)(dst + row * K::W + c * 8) = as_uint4(a);
@@ -970,8 +993,9 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     a.ak = ak;
 
     BwdParams p = pin;
-    const unsigned nb_q = (unsigned)((rows * (K::W / 8) + 255) / 256);
-    const unsigned nb_k = (unsigned)((rowsk * (K::W / 8) + 255) / 256);
+    constexpr int RPB = kPrepRows<C, RP>;
+    const unsigned nb_q = (unsigned)((rows + RPB - 1) / RPB);
+    const unsigned nb_k = (unsigned)((rowsk + RPB - 1) / RPB);
     bool narrow = false;
     if constexpr (C == 32) {
         if (pin.Cg == 16) {

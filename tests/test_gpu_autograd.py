@@ -176,7 +176,7 @@ def test_training_factor_parameters_recovers_a_low_rank_bias():
         loss = (out.float() - target).square().mean()
         loss.backward()
         opt.step()
-        losses.append(float(loss))
+        losses.append(float(loss.detach()))
     print(f"[train] loss {losses[0]:.4e} -> {losses[-1]:.4e}", flush=True)
     assert np.isfinite(losses).all()
     assert losses[-1] < 0.1 * losses[0]
