@@ -33,6 +33,7 @@
 
 #include <type_traits>
 
+#include <cmath>
 #include "fb_device.h"
 #include "fb_launch.h"
 #include "fb_params.h"
@@ -121,17 +122,27 @@ struct Cfg {
 // A workgroup covers kPrepRows<C, RP> whole rows (one thread per 16-byte piece; the few threads past
 // the last whole row idle), so a thread's row and piece come from its index by a division by a
 // constant, and the head and position of the row from one block-uniform division plus a wrap.
-template <int C, int RP>
-constexpr int kPrepRows = 256 / (Cfg<C, RP>::W / 8);
+//
+// SPLIT: the main kernels read the C channel columns straight from the caller's q or k rows, and
+// only the factor columns are written, as rows of RP2 columns (key side: a plain saving, the k
+// columns were a copy; query side: the scale moves out of the q columns, see fmul).
+template <int C, int RP, bool SPLIT>
+constexpr int kPrepRows = 256 / ((SPLIT ? Cfg<C, RP>::RP2 : Cfg<C, RP>::W) / 8);
 
-template <int C, int RP, bool QSIDE>
-FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const unsigned block) {
+// fmul: factor of the factor columns (1, or 1/scale on the query side of a launch whose q columns
+// carry no scale: q k^T scale + phi_q phi_k^T = scale (q k^T + (phi_q / scale) phi_k^T); always a power
+// of two, so exact for bf16 factors and for the limbs of fp32 ones).
+template <int C, int RP, bool QSIDE, bool SPLIT>
+FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const unsigned block, const float fmul) {
     using K = Cfg<C, RP>;
-    constexpr int CPR = K::W / 8;
-    constexpr int RPB = kPrepRows<C, RP>;
+    static_assert(!SPLIT || (RP > 0 && C % 64 == 0), "split rows: whole 64-column panels of channels, and factor columns to write");
+    constexpr int CPR = (SPLIT ? K::RP2 : K::W) / 8;
+    constexpr int RPB = kPrepRows<C, RP, SPLIT>;
+    constexpr int DW = SPLIT ? K::RP2 : K::W;                 // columns of a destination row
+    constexpr int C0 = SPLIT ? C / 8 : 0;                     // first piece of a destination row
     const unsigned len = (unsigned)(QSIDE ? p.N : p.M);
     const unsigned dr = threadIdx.x / CPR;
-    const int c = (int)(threadIdx.x - dr * CPR);
+    const int c = (int)(threadIdx.x - dr * CPR) + C0;
     const long long row0 = (long long)block * RPB;            // block-uniform
     const long long row = row0 + dr;                          // (b*H + h)*len + i
     const long long rows = (long long)p.B * p.H * len;
@@ -170,7 +181,7 @@ FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const u
             float pair[2];
             pair[0] = QSIDE ? -m * (float)i : 1.f;
             pair[1] = QSIDE ? m : (float)i;
-            a = phi_chunk_switch<QSIDE>(pair, pc, 2, true);
+            a = phi_chunk_switch<QSIDE>(pair, pc, 2, true, fmul);
         } else {
             const size_t off = ((size_t)bb * (QSIDE ? p.phi_bstride : p.phik_bstride) + ((size_t)h * len + i) * p.R) * esz;
             const unsigned char* src = (const unsigned char*)(QSIDE ? p.phi_q : p.phi_k) + off;
@@ -180,11 +191,15 @@ FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const u
                 if (pc * 8 < p.R) raw = *(const u32x4*)(src + pc * 16);
                 a = as_bf16x8(raw);
             } else {
-                a = phi_chunk_switch<QSIDE>(src, pc, p.R, f32);
+                a = phi_chunk_switch<QSIDE>(src, pc, p.R, f32, fmul);
+            }
+            if (!f32 && fmul != 1.f) {      // a power of two: exact
+#pragma unroll
+                for (int e = 0; e < 8; e++) a[e] = (bf16_t)((float)a[e] * fmul);
             }
         }
     }
-    *(u32x4*)(dst + row * K::W + c * 8) = as_uint4(a);
+    *(u32x4*)(dst + row * DW + (c - C0) * 8) = as_uint4(a);
 }
 
 template <int C>
@@ -209,17 +224,18 @@ FB_DEV void bwd_vec_block(const bf16_t* __restrict__ out, const bf16_t* __restri
 
 // The whole pre-pass in one launch: workgroups [0, nb_vec) form the (lse log2 e, D) rows (CV: channels
 // per row of out / dout in memory, 0 = not in this launch), the next nb_q write Aq, the rest Ak.
-template <int C, int RP, int CV>
+// SQ, SK: the query-side / key-side rows are written in the split form (factor columns only).
+template <int C, int RP, int CV, bool SQ = false, bool SK = false>
 __global__ __launch_bounds__(256) void bwd_pre_kernel(BwdParams p, float2* __restrict__ vec, bf16_t* __restrict__ aq,
-                                                      bf16_t* __restrict__ ak, unsigned nb_vec, unsigned nb_q) {
+                                                      bf16_t* __restrict__ ak, unsigned nb_vec, unsigned nb_q, float qmul) {
     const unsigned blk = blockIdx.x;
     if (blk < nb_vec) {
         if constexpr (CV > 0)
             bwd_vec_block<CV>((const bf16_t*)p.out, (const bf16_t*)p.dout, p.lse, vec, (long long)p.B * p.H * p.N, blk);
     } else if (blk < nb_vec + nb_q) {
-        bwd_prep_block<C, RP, true>(p, aq, blk - nb_vec);
+        bwd_prep_block<C, RP, true, SQ>(p, aq, blk - nb_vec, qmul);
     } else {
-        bwd_prep_block<C, RP, false>(p, ak, blk - nb_vec - nb_q);
+        bwd_prep_block<C, RP, false, SK>(p, ak, blk - nb_vec - nb_q, 1.f);
     }
 }
 
@@ -283,10 +299,19 @@ FB_DEV void store_dphi(const f32x16* acc_phi /* [RP2/32] */, float* scratch /* w
 //   T1 tile: rows of the streamed operand of S (Aq when DKV, else Ak), width W
 //   T2 tile: rows of the streamed operand of dP (dO when DKV, else V), width C
 // ------------------------------------------------------------------------------------------
+// Operand rows [channels | factor columns] of one side.  Whole rows in the workspace: main = the rows,
+// phi = main + C, both pitches W.  Split: main = the caller's q or k rows (pitch C), phi = rows of the
+// RP2 factor columns in the workspace.
+struct OperandRows {
+    const bf16_t* main; int main_pitch;
+    const bf16_t* phi;  int phi_pitch;
+};
 struct MainArgs {
-    const bf16_t* aq;     // [B*H*N][W]
-    const bf16_t* ak;     // [B*H*N][W]
+    OperandRows aq;       // B*H*N rows
+    OperandRows ak;       // B*H*M rows
     const float2* vec;    // [B*H*N]  (lse * log2 e, D)
+    float exp_mul;        // S exp_mul - lse2 is the exponent of P to base two: log2 e, times the scale where the q columns carry none
+    float dkv_mul;        // factor of d[K | phi_k] (the scale, where the q columns carry none)
 };
 
 // DENSE (RP = 0 only): the bias is a dense [N][M] matrix instead of factors.  Every wave also
@@ -318,9 +343,14 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     const int rc = min(ri, NL - 1);       // rows past the end compute on the last row and are not stored
 
     const size_t lbase = (size_t)bh * NL, sbase_rows = (size_t)bh * NS;
-    const bf16_t* l1g = (DKV ? a.ak : a.aq) + lbase * K::W;                         // lane-side operand of S
+    const OperandRows& L1 = DKV ? a.ak : a.aq;                                      // lane-side operand of S
+    const OperandRows& S1 = DKV ? a.aq : a.ak;                                      // streamed operand of S
+    const bf16_t* l1m = L1.main + lbase * L1.main_pitch;
+    const bf16_t* l1p = L1.phi + lbase * L1.phi_pitch;
     const bf16_t* l2g = (const bf16_t*)(DKV ? p.v : p.dout) + lbase * C;            // lane-side operand of dP
-    const bf16_t* t1g = (DKV ? a.aq : a.ak) + sbase_rows * K::W;                    // streamed
+    const bf16_t* t1m = S1.main + sbase_rows * S1.main_pitch;
+    const bf16_t* t1p = S1.phi + sbase_rows * S1.phi_pitch;
+    const float emul = a.exp_mul;
     const bf16_t* t2g = (const bf16_t*)(DKV ? p.dout : p.v) + sbase_rows * C;
     const float2* vecg = a.vec + (size_t)bh * p.N;                                  // per query row
 
@@ -328,7 +358,8 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     bf16x8 l1reg[K::KS], l2reg[K::CS];
 #pragma unroll
     for (int ks = 0; ks < K::KS; ks++)
-        l1reg[ks] = as_bf16x8(*(const u32x4*)(l1g + (size_t)rc * K::W + ks * 16 + 8 * hf));
+        l1reg[ks] = as_bf16x8(*(const u32x4*)(ks * 16 < C ? l1m + (size_t)rc * L1.main_pitch + ks * 16 + 8 * hf
+                                                          : l1p + (size_t)rc * L1.phi_pitch + (ks * 16 - C) + 8 * hf));
 #pragma unroll
     for (int cs = 0; cs < K::CS; cs++)
         l2reg[cs] = as_bf16x8(*(const u32x4*)(l2g + (size_t)rc * C + cs * 16 + 8 * hf));
@@ -380,9 +411,14 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         int row = 0, chunk = 0, dst = 0;
         if (d < T1::NDMA) {
             T1::dma_map(d, lane, row, chunk, dst);
-            dma_src_j = (const unsigned char*)t1g;
-            dma_bstride[j] = BT * K::W * 2; dma_pitch_j = K::W * 2; dma_lshift_j = 0;
-            dma_col[j] = (unsigned)chunk * 16u;
+            // a panel of 64 (or the last 32) columns comes from one array: the channel rows, or the factor
+            // rows when it starts at or behind column C (split rows have C % 64 == 0, so no panel mixes)
+            const int panel = d < T1::NP64 * 4 ? (d >> 2) : T1::NP64;
+            const bool fpart = panel * 64 >= C;
+            const int pitch_el = fpart ? S1.phi_pitch : S1.main_pitch;
+            dma_src_j = (const unsigned char*)(fpart ? t1p : t1m);
+            dma_bstride[j] = BT * pitch_el * 2; dma_pitch_j = pitch_el * 2; dma_lshift_j = 0;
+            dma_col[j] = (unsigned)(fpart ? chunk - C / 8 : chunk) * 16u;
             dma_dst[j] = dst;
         } else if (d < T1::NDMA + T2::NDMA) {
             T2::dma_map(d - T1::NDMA, lane, row, chunk, dst);
@@ -591,7 +627,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     // P and dS of one accumulator element r (streamed row sb0 + 8*(r/4) + 4*hf + (r%4), lane row ri)
     auto elem = [&](int r, const f32x16& s, const f32x16& dp, float lvx, float dvx, bool need_mask, int sb0,
                     bf16x8 (&pb)[2], bf16x8 (&dsb)[2]) __attribute__((always_inline)) {
-        float pr = fast_exp2(fmaf(s[r], kLog2e, -lvx));
+        float pr = fast_exp2(fmaf(s[r], emul, -lvx));
         float ds = pr * (dp[r] - dvx);
         if (need_mask) {
             const int srow = sb0 + 8 * (r / 4) + 4 * hf + (r % 4);
@@ -715,7 +751,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
                 for (int e = (n * 16) / NA; e < ((n + 1) * 16) / NA; e++) {
                     if (LAZY_DS) {
-                        prf[e] = fast_exp2(fmaf(sc[e], kLog2e, -vq[e >> 2][e & 3]));
+                        prf[e] = fast_exp2(fmaf(sc[e], emul, -vq[e >> 2][e & 3]));
                         pb[e / 8][e % 8] = (bf16_t)prf[e];
                     } else {
                         elem(e, sc, dc, vq[e >> 2][e & 3], vd[e >> 2][e & 3], false, sb0, pb, dsb);
@@ -882,6 +918,12 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
     __syncthreads();
 
     // ---- epilogue ----
+    if (DKV && a.dkv_mul != 1.f) {      // wave-uniform: the q columns carried no scale
+#pragma unroll
+        for (int mb = 0; mb < K::MB; mb++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc1[mb][r] *= a.dkv_mul;
+    }
     const bool rok = ri < NL;
     const int Cg = p.Cg;      // channels of the caller's gradient rows (< C: the rest is not stored)
     const size_t base = (size_t)bh * NL * Cg;
@@ -983,25 +1025,40 @@ int launch(const BwdParams& pin, hipStream_t stream) {
 
     const long long rows = (long long)pin.B * pin.H * pin.N;      // query rows
     const long long rowsk = (long long)pin.B * pin.H * pin.M;     // key rows
-    // workspace: vec [rows] float2 | Aq [rows][W] bf16 | Ak [rowsk][W] bf16  (each a multiple of 16 bytes)
+    // Split rows (C a multiple of 64, caller's rows of C channels): the k columns of the key-side rows were
+    // a copy, so the kernels read k itself.  On the query side the q columns carry the scale; it can move
+    // onto the factor columns (as 1/scale) and into the exponent and the dK epilogue, so that q is read in
+    // place too -- but the forward formed its scores from bf16(q scale), and the recomputed scores must be
+    // those (lse and D belong to them), so only where that rounding changes nothing: a scale that is a power
+    // of two (head dimensions 16 and 64 with the default scale, and the multiplicative form, whose prepared
+    // rows carry their scale already).  Never with a dense bias, which enters the chain unscaled.
+    constexpr bool kCanSplit = C % 64 == 0;
+    int mant_exp = 0;
+    const bool pow2 = std::frexp(pin.scale, &mant_exp) == 0.5f;
+    const bool split_k = kCanSplit && pin.Cg == C;
+    const bool split_q = split_k && !DENSE && pow2;
+    // workspace: vec [rows] float2 | Aq [rows][W or RP2] bf16 | Ak [rowsk][W or RP2] bf16  (each a multiple of 16 bytes)
     unsigned char* ws = (unsigned char*)pin.workspace;
     MainArgs a;
     a.vec = (const float2*)ws;
     bf16_t* aq = (bf16_t*)(ws + (((size_t)rows * 8 + 15) & ~(size_t)15));
-    bf16_t* ak = aq + (size_t)rows * K::W;
-    a.aq = aq;
-    a.ak = ak;
+    bf16_t* ak = aq + (size_t)rows * (split_q ? K::RP2 : K::W);
+    a.aq = split_q ? OperandRows{(const bf16_t*)pin.q, C, aq, K::RP2} : OperandRows{aq, K::W, aq + C, K::W};
+    a.ak = split_k ? OperandRows{(const bf16_t*)pin.k, C, ak, K::RP2} : OperandRows{ak, K::W, ak + C, K::W};
+    a.exp_mul = split_q ? kLog2e * pin.scale : kLog2e;
+    a.dkv_mul = split_q ? pin.scale : 1.f;
+    const float qmul = split_q ? 1.f / pin.scale : 1.f;
 
     BwdParams p = pin;
-    constexpr int RPB = kPrepRows<C, RP>;
-    const unsigned nb_q = (unsigned)((rows + RPB - 1) / RPB);
-    const unsigned nb_k = (unsigned)((rowsk + RPB - 1) / RPB);
     bool narrow = false;
     if constexpr (C == 32) {
         if (pin.Cg == 16) {
             // widened copies of v and dO behind the operand rows; out and dO keep their 16-channel rows
             // for the row sums
             narrow = true;
+            constexpr int RPB = kPrepRows<C, RP, false>;
+            const unsigned nb_q = (unsigned)((rows + RPB - 1) / RPB);
+            const unsigned nb_k = (unsigned)((rowsk + RPB - 1) / RPB);
             bf16_t* vpad = ak + (size_t)rowsk * K::W;
             bf16_t* dpad = vpad + (size_t)rowsk * 32;
             hipLaunchKernelGGL(bwd_pad16_kernel, dim3((unsigned)((rowsk * 4 + 255) / 256)), dim3(256), 0, stream,
@@ -1010,7 +1067,7 @@ int launch(const BwdParams& pin, hipStream_t stream) {
                                (const bf16_t*)pin.dout, dpad, rows);
             const unsigned nb_vec = (unsigned)((rows * 2 + 255) / 256);
             hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 16>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
-                               pin, (float2*)ws, aq, ak, nb_vec, nb_q);
+                               pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
             if (hipGetLastError() != hipSuccess) return 1;
             p.v = vpad;
             p.dout = dpad;
@@ -1019,8 +1076,30 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     if (!narrow) {
         if (pin.Cg != C) return -1;
         const unsigned nb_vec = (unsigned)((rows * (C / 8) + 255) / 256);
-        hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
-                           pin, (float2*)ws, aq, ak, nb_vec, nb_q);
+        auto blocks = [](long long r, int rows_per_block) { return (unsigned)((r + rows_per_block - 1) / rows_per_block); };
+        if constexpr (kCanSplit && RP > 0) {
+            constexpr int RS = kPrepRows<C, RP, true>, RW = kPrepRows<C, RP, false>;
+            if (split_q) {
+                const unsigned nb_q = blocks(rows, RS), nb_k = blocks(rowsk, RS);
+                hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C, true, true>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                                   pin, (float2*)ws, aq, ak, nb_vec, nb_q, qmul);
+            } else if (split_k) {
+                const unsigned nb_q = blocks(rows, RW), nb_k = blocks(rowsk, RS);
+                hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C, false, true>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                                   pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
+            } else {
+                const unsigned nb_q = blocks(rows, RW), nb_k = blocks(rowsk, RW);
+                hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                                   pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
+            }
+        } else {
+            // no factor columns to write for a split side (RP = 0): its workgroups are simply not launched
+            constexpr int RW = kPrepRows<C, RP, false>;
+            const unsigned nb_q = split_q ? 0u : blocks(rows, RW);
+            const unsigned nb_k = split_k ? 0u : blocks(rowsk, RW);
+            hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                               pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
+        }
         if (hipGetLastError() != hipSuccess) return 1;
     }
 

@@ -221,7 +221,7 @@ FB_DEV bf16x8 phi_chunk_from_pair(int c8, float x0, float x1) {
 // of the eight columns are constants, so an fp32 chunk costs at most three loads and three
 // limb splits instead of eight of each.
 template <bool QSIDE, int C8>
-FB_DEV bf16x8 phi_chunk_static(const void* row, int R, bool f32) {
+FB_DEV bf16x8 phi_chunk_static(const void* row, int R, bool f32, float mul = 1.f) {
     bf16x8 out;
     if (!f32) {
 #pragma unroll
@@ -232,7 +232,7 @@ FB_DEV bf16x8 phi_chunk_static(const void* row, int R, bool f32) {
     bf16_t limb[3][3];
 #pragma unroll
     for (int d = 0; d < 3; d++) {
-        const float x = (r0 + d < R && r0 + d <= (C8 * 8 + 7) / 6) ? ((const float*)row)[r0 + d] : 0.f;
+        const float x = (r0 + d < R && r0 + d <= (C8 * 8 + 7) / 6) ? ((const float*)row)[r0 + d] * mul : 0.f;
         const bf16_t l1 = (bf16_t)x;
         const float e1 = x - (float)l1;
         const bf16_t l2 = (bf16_t)e1;
@@ -250,17 +250,17 @@ FB_DEV bf16x8 phi_chunk_static(const void* row, int R, bool f32) {
     return out;
 }
 template <bool QSIDE>
-FB_DEV bf16x8 phi_chunk_switch(const void* row, int c8, int R, bool f32) {
+FB_DEV bf16x8 phi_chunk_switch(const void* row, int c8, int R, bool f32, float mul = 1.f) {   // mul: fp32 factors only
     if (!f32) return phi_chunk_gather<QSIDE>(row, c8, R, false);   // any chunk index (rows wider than 64 columns)
     switch (c8) {
-        case 0: return phi_chunk_static<QSIDE, 0>(row, R, f32);
-        case 1: return phi_chunk_static<QSIDE, 1>(row, R, f32);
-        case 2: return phi_chunk_static<QSIDE, 2>(row, R, f32);
-        case 3: return phi_chunk_static<QSIDE, 3>(row, R, f32);
-        case 4: return phi_chunk_static<QSIDE, 4>(row, R, f32);
-        case 5: return phi_chunk_static<QSIDE, 5>(row, R, f32);
-        case 6: return phi_chunk_static<QSIDE, 6>(row, R, f32);
-        default: return phi_chunk_static<QSIDE, 7>(row, R, f32);
+        case 0: return phi_chunk_static<QSIDE, 0>(row, R, f32, mul);
+        case 1: return phi_chunk_static<QSIDE, 1>(row, R, f32, mul);
+        case 2: return phi_chunk_static<QSIDE, 2>(row, R, f32, mul);
+        case 3: return phi_chunk_static<QSIDE, 3>(row, R, f32, mul);
+        case 4: return phi_chunk_static<QSIDE, 4>(row, R, f32, mul);
+        case 5: return phi_chunk_static<QSIDE, 5>(row, R, f32, mul);
+        case 6: return phi_chunk_static<QSIDE, 6>(row, R, f32, mul);
+        default: return phi_chunk_static<QSIDE, 7>(row, R, f32, mul);
     }
 }
 

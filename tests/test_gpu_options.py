@@ -109,6 +109,31 @@ def test_alibi_explicit_scale():
         assert max_abs(host(out[0, h]), ro) <= TOL["bf16"] and max_abs(host(lse[0, h]), rl) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("C,R,phi_dtype,causal", [(128, 2, "f32", True), (128, 8, "bf16", False), (64, 5, "f32", False),
+                                                  (64, 16, "bf16", True)])
+def test_power_of_two_scale_backward(C, R, phi_dtype, causal):
+    """With a scale that is a power of two the backward reads q in place and carries 1/scale on the
+    query-side factor columns instead (exact then); every gradient against the oracle, and the same
+    call with a neighbouring scale that takes the other route."""
+    B, H, N = 2, 2, 300
+    q, k, v, dout, pq, pk = _case(B, H, N, C, R, seed=9500 + C + R, phi_dtype=phi_dtype)
+    d = [dev(x, "bf16") for x in (q, k, v)] + [dev(pq, phi_dtype), dev(pk, phi_dtype)]
+    dd = dev(dout, "bf16")
+    for scale in (0.125, 0.11):
+        out, lse = api.fb_lowrank_attn_fwd(*d, causal=causal, scale=scale)
+        g = api.fb_lowrank_attn_bwd(*d, out, lse, dd, causal=causal, scale=scale)
+        torch.cuda.synchronize()
+        for b in range(B):
+            for h in range(H):
+                rg = O.attention_lowrank_grads(q[b, h], k[b, h], v[b, h], pq[b, h], pk[b, h], dout[b, h],
+                                               causal=causal, scale=scale)
+                for name, got, ref in zip(("dq", "dk", "dv", "dphi_q", "dphi_k"), g, rg):
+                    e = max_abs(host(got[b, h]), ref)
+                    lim = GRAD_TOL * max(1.0, float(np.abs(ref).max()) / 2.5)
+                    print(f"[parity] scale {scale} C{C} R{R} {phi_dtype} causal={causal} {name}[{b},{h}]: {e:.3e}", flush=True)
+                    assert np.isfinite(host(got[b, h])).all() and e <= lim, (name, b, h, e, lim)
+
+
 def test_side_stream_and_caller_buffers():
     """Work is enqueued on the stream handed in (default priority) and lands in the buffers handed
     in; results are bit-identical to the default-stream call."""
