@@ -151,6 +151,7 @@ static int lowrank_fwd_impl(const void* q, const void* k, const void* v,
     p.bias_bstride = 0;
     p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    p.inv_scale = 1.0f / p.scale;
     int rc;
     if (dtype == FB_F32) {
         rc = fb_launch_fwd_f32(p, C, false, (hipStream_t)stream);
@@ -200,6 +201,7 @@ int fb_dense_bias_attn_fwd(const void* q, const void* k, const void* v, const vo
     p.bias_bstride = bias_batch_broadcast ? 0 : (long long)H * N * N;
     p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    p.inv_scale = 1.0f / p.scale;
     int rc;
     if (dtype == FB_F32) rc = fb_launch_fwd_f32(p, C, true, (hipStream_t)stream);
     else rc = fb_launch_fwd_bf16(p, C, 0, true, pick_qb(B, H, N, C, 0, true, causal != 0), (hipStream_t)stream);
@@ -227,6 +229,7 @@ int fb_alibi_attn_fwd(const void* q, const void* k, const void* v, const float* 
     p.bias_bstride = 0;
     p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = scale > 0.f ? scale : 1.0f / std::sqrt((float)C);
+    p.inv_scale = 1.0f / p.scale;
     int qb = pick_qb(B, H, N, C, 16, false, causal != 0);
     if (qb != 2) qb = 1;     // only the four-wave kernel generates factors
     const int rc = fb_launch_fwd_bf16_alibi(p, C, qb, (hipStream_t)stream);
@@ -283,6 +286,7 @@ int fb_lowrank_mulbias_attn_fwd(const void* q, const void* k, const void* v,
     p.bias_bstride = 0;
     p.causal_up = g_causal_up.load(std::memory_order_relaxed);
     p.scale = 1.0f;                                 // already folded into q'
+    p.inv_scale = 1.0f / p.scale;
     const int rp = mulbias_padded(rest);
     int qb = pick_qb(B, H, N, C, rp, false, causal != 0);
     if (rp > 64) qb = 1;                           // wide blocks: four-wave kernel, one query block per wave

@@ -130,8 +130,8 @@ template <int C, int RP, bool SPLIT>
 constexpr int kPrepRows = 256 / ((SPLIT ? Cfg<C, RP>::RP2 : Cfg<C, RP>::W) / 8);
 
 // fmul: factor of the factor columns (1, or 1/scale on the query side of a launch whose q columns
-// carry no scale: q k^T scale + phi_q phi_k^T = scale (q k^T + (phi_q / scale) phi_k^T); always a power
-// of two, so exact for bf16 factors and for the limbs of fp32 ones).
+// carry no scale: q k^T scale + phi_q phi_k^T = scale (q k^T + (phi_q / scale) phi_k^T); applied to fp32
+// factors before the limb split, as the forward does, and to bf16 factors only as a power of two).
 template <int C, int RP, bool QSIDE, bool SPLIT>
 FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const unsigned block, const float fmul) {
     using K = Cfg<C, RP>;
@@ -1028,15 +1028,17 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     // Split rows (C a multiple of 64, caller's rows of C channels): the k columns of the key-side rows were
     // a copy, so the kernels read k itself.  On the query side the q columns carry the scale; it can move
     // onto the factor columns (as 1/scale) and into the exponent and the dK epilogue, so that q is read in
-    // place too -- but the forward formed its scores from bf16(q scale), and the recomputed scores must be
-    // those (lse and D belong to them), so only where that rounding changes nothing: a scale that is a power
-    // of two (head dimensions 16 and 64 with the default scale, and the multiplicative form, whose prepared
-    // rows carry their scale already).  Never with a dense bias, which enters the chain unscaled.
+    // place too -- where the forward formed its scores that way as well (lse and D belong to the forward's
+    // scores, and the recomputed ones must be those): no factors, fp32 factors (scaled before the limb
+    // split) and ALiBi factors made in the kernels; and wherever bf16(q scale) = q scale, i.e. for a scale
+    // that is a power of two (head dimension 64 at the default scale with bf16 factors, and the
+    // multiplicative form, whose prepared rows carry their scale already).  Never with a dense bias, which
+    // enters the chain unscaled.
     constexpr bool kCanSplit = C % 64 == 0;
     int mant_exp = 0;
     const bool pow2 = std::frexp(pin.scale, &mant_exp) == 0.5f;
     const bool split_k = kCanSplit && pin.Cg == C;
-    const bool split_q = split_k && !DENSE && pow2;
+    const bool split_q = split_k && !DENSE && (pow2 || RP == 0 || pin.phi_f32 != 0 || pin.slopes != nullptr);
     // workspace: vec [rows] float2 | Aq [rows][W or RP2] bf16 | Ak [rowsk][W or RP2] bf16  (each a multiple of 16 bytes)
     unsigned char* ws = (unsigned char*)pin.workspace;
     MainArgs a;

@@ -130,7 +130,14 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
     // block costs more than the sixteen multiply-adds it saves, 0.0695 against 0.0668 ms on the
     // Pairformer shape.)
     constexpr bool FOLD = !DENSE && (PM == 3 || PM == 4) && C == 32;
-    const float qmul = FOLD ? kLog2e : 1.f;
+    // RAWQ (head dimensions 64 and 128; no factors, fp32 factors or factors made in the kernel): the
+    // query operand is q itself, not bf16(q scale).  q k^T scale + phi_q phi_k^T = scale (q k^T +
+    // (phi_q / scale) phi_k^T): the factor columns carry 1/scale (applied in fp32, before the limb
+    // split) and the scale goes into the exponent's multiply-add.  One rounding less on the scores,
+    // and the backward, which recomputes exactly these scores, can read q in place as well.
+    constexpr bool RAWQ = !DENSE && !FOLD && C % 64 == 0 && CG == C && (PM == 0 || PM == 3 || PM == 4);
+    const float qmul = FOLD ? kLog2e : (RAWQ ? p.inv_scale : 1.f);       // factor of the query-side factor columns
+    const float emul = RAWQ ? p.scale * kLog2e : kLog2e;                 // scores to exponents of two
     const float slope = PM == 4 ? p.slopes[h] * qmul : 0.f;
 
     const int tid = threadIdx.x;
@@ -474,7 +481,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
         load_block(1, st1);
         // ---- query operand [q*scale | phi_q | 0] in registers (B-operand layout).  Rows past N
         // read row N-1 (finite values) and are never stored.
-        const float qscale = p.scale * qmul;
+        const float qscale = FOLD ? p.scale * kLog2e : p.scale;
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) {
             const int qi = min(qw0 + qb * 32 + l32, N - 1);
@@ -485,7 +492,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                     if (ks * 16 < CG) {
                         const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qi * CG + ks * 16 + 8 * hf));
 #pragma unroll
-                        for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * qscale);
+                        for (int e = 0; e < 8; e++) val[e] = RAWQ ? x[e] : (bf16_t)((float)x[e] * qscale);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 8; e++) val[e] = (bf16_t)0.f;
@@ -598,8 +605,8 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
-                    const bf16x2 pr2 = {(bf16_t)fast_exp2(FOLD ? s[qb][r] : fmaf(s[qb][r], kLog2e, nm)),
-                                        (bf16_t)fast_exp2(FOLD ? s[qb][r + 1] : fmaf(s[qb][r + 1], kLog2e, nm))};
+                    const bf16x2 pr2 = {(bf16_t)fast_exp2(FOLD ? s[qb][r] : fmaf(s[qb][r], emul, nm)),
+                                        (bf16_t)fast_exp2(FOLD ? s[qb][r + 1] : fmaf(s[qb][r + 1], emul, nm))};
                     ps[(r >> 1) & 3] = pair_sum(pr2, ps[(r >> 1) & 3]);
                     pb[qb][r / 8][r % 8] = pr2[0];
                     pb[qb][r / 8][r % 8 + 1] = pr2[1];
@@ -622,7 +629,7 @@ FB_DEV void fwd_tile(const FwdParams& p, unsigned char* smem, const int bh, cons
                 asm volatile("" ::: "memory");   // keep this a real (rarely taken) branch
                 // FOLD: what the scores already carry (0 while the row has no reference)
                 const float emb = mref[qb] == -INFINITY ? 0.f : mref[qb];
-                const float mx = FOLD ? half_max(max16(s[qb])) + emb : half_max(max16(s[qb])) * kLog2e;
+                const float mx = FOLD ? half_max(max16(s[qb])) + emb : half_max(max16(s[qb])) * emul;
                 if (__any(mx > mref[qb])) {
                     const float mnew = fmaxf(fmaxf(mref[qb], mx), -1e30f);
                     const float alpha = fast_exp2(mref[qb] - mnew);

@@ -23,6 +23,7 @@ struct FwdParams {
     long long phik_bstride;  // ... of phi_k
     long long bias_bstride;  // elements between batch items of bias (0 when shared)
     float scale;
+    float inv_scale;      // 1 / scale, formed on the host (the backward forms the same value there)
     int causal_up;        // causal pairs: the first tile walks its off-diagonal blocks upwards from key 0
     int n_qtiles;         // query tiles per (b,h)
     int n_units;          // work units (workgroups) per (b,h): tiles, or tile pairs when causal

@@ -128,8 +128,12 @@ def test_alibi_backward_matches_factor_tensor_path_at_full_size():
     torch.cuda.synchronize()
     for name, a, b in zip(("dq", "dk", "dv"), g1, g2):
         diff = float((a.float() - b.float()).abs().max())
-        print(f"alibi bwd in-kernel vs factor tensors, {name}: max diff {diff:.3e}", flush=True)
-        assert diff <= 2e-2
+        big = float(a.float().abs().max())
+        print(f"alibi bwd in-kernel vs factor tensors, {name}: max diff {diff:.3e}  max|g| {big:.3g}", flush=True)
+        # the tensor path holds fp32(m i) formed from the float64 slope, the kernel path the product of the
+        # fp32 slope and i: scores differ by a few 1e-4, which moves a gradient entry across a bf16 rounding
+        # boundary now and then.  Two bf16 steps of the largest entry (2^-6 relative), or the flat bound.
+        assert diff <= max(2e-2, 2.0 ** -6 * big)
 
 
 def _oracle_slope_rows(q, k, v, slope, dout, causal):
