@@ -83,9 +83,6 @@ const char* fb_status_string(int status);
  *                 1, 2 = four-wave kernel with that many 32-row query blocks per wave
  *                 8    = eight-wave ping-pong kernel
  *                 16   = direct-to-LDS kernel (falls back to 1 for shapes it does not take)
- *                 (8 and 16 form their scores from bf16(q scale); the four-wave kernel at C = 64, 128
- *                 with no, fp32 or in-kernel factors forms them from q itself, which is what the
- *                 backward recomputes: pair a backward call with a forward of the automatic choice)
  *   "fwd_causal_up" 1 (default): of the two query tiles a workgroup of the causal four-wave
  *                 kernel takes, the first walks its off-diagonal key blocks upwards from key 0
  *                 and the second downwards, so the workgroups of a head read the same block at

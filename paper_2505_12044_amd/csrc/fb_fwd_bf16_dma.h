@@ -159,7 +159,11 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_dma_kernel(FwdParams p) 
     const bf16_t* bg = nullptr;
     if (DENSE) bg = (const bf16_t*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * N;
 
-    // ---- query operand [q*scale | phi_q | 0] (rows past N read row N-1 and are never stored)
+    // ---- query operand [q*scale | phi_q | 0] (rows past N read row N-1 and are never stored); as in the
+    // four-wave kernel, with no factors or fp32 factors at C = 64, 128 it is [q | phi_q / scale | 0] and the
+    // scale sits in the exponent's multiply-add
+    constexpr bool RAWQ = !DENSE && C % 64 == 0 && (PM == 0 || PM == 3);
+    const float emul = RAWQ ? p.scale * kLog2e : kLog2e;
     bf16x8 qreg[K::KS];
     {
         const int qc = min(qi, N - 1);
@@ -169,10 +173,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_dma_kernel(FwdParams p) 
             if (ks < K::KSC) {
                 const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qc * C + ks * 16 + 8 * hf));
 #pragma unroll
-                for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
+                for (int e = 0; e < 8; e++) val[e] = RAWQ ? x[e] : (bf16_t)((float)x[e] * p.scale);
             } else {
                 const int c8 = (ks - K::KSC) * 2 + hf;
-                val = phi_chunk_gather<true>(pqg + (size_t)qc * R * phi_esz, c8, R, phi_f32);
+                val = phi_chunk_gather<true>(pqg + (size_t)qc * R * phi_esz, c8, R, phi_f32, RAWQ ? p.inv_scale : 1.f);
             }
             qreg[ks] = val;
         }
@@ -369,7 +373,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_dma_kernel(FwdParams p) 
         for (int ks = 0; ks < K::KS; ks++) sA = mfma32(ka[ks], qreg[ks], sA);
         const int kb0 = blk_of(0) * BK;
         if ((kb0 + BK > N) || (CAUSAL && kb0 + BK - 1 > qw0)) mask_block(sA, kb0);
-        mx2 = half_max(max16(sA)) * kLog2e;
+        mx2 = half_max(max16(sA)) * emul;
 #pragma unroll
         for (int ks = 0; ks < LA && ks < K::KS; ks++) read_k(1, ks);
     }
@@ -422,7 +426,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_dma_kernel(FwdParams p) 
             if (i + LA < K::KS) read_k(kslot1, i + LA);
 #pragma unroll
             for (int e = (i * 16) / K::KS; e < ((i + 1) * 16) / K::KS; e++) {
-                float pr = fast_exp2(fmaf(scur[e], kLog2e, nm));
+                float pr = fast_exp2(fmaf(scur[e], emul, nm));
                 // the empty asm pins the computation to this step: without it the optimiser
                 // sinks the whole exponentiation down to its first use
                 asm volatile("" : "+v"(pr));
@@ -463,7 +467,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_dma_kernel(FwdParams p) 
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            mx2 = half_max(m) * kLog2e;
+            mx2 = half_max(m) * emul;
         }
         // everything issued before this iteration must have landed before the barrier: only this
         // iteration's own direct loads (NDMA for K/V, two for a bias tile, one for factors) may remain

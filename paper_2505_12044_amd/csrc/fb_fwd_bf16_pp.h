@@ -95,7 +95,12 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
     const bf16_t* bg = nullptr;
     if (DENSE) bg = (const bf16_t*)p.bias + (size_t)b * p.bias_bstride + (size_t)h * N * N;
 
-    // ---- query operand [q*scale | phi_q | 0] (rows past N read row N-1 and are never stored)
+    // ---- query operand [q*scale | phi_q | 0] (rows past N read row N-1 and are never stored); as in the
+    // four-wave kernel, with no factors or fp32 factors at C = 64, 128 it is [q | phi_q / scale | 0] and the
+    // scale sits in the exponent's multiply-add, so that every forward variant forms the scores the
+    // backward recomputes
+    const bool rawq = !DENSE && C % 64 == 0 && (PM == 0 || phi_f32);      // wave-uniform
+    const float emul = rawq ? p.scale * kLog2e : kLog2e;
     bf16x8 qreg[K::KS];
     {
         const int qc = min(qi, N - 1);
@@ -105,10 +110,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
             if (ks < C / 16) {
                 const bf16x8 x = as_bf16x8(*(const u32x4*)(qg + (size_t)qc * C + ks * 16 + 8 * hf));
 #pragma unroll
-                for (int e = 0; e < 8; e++) val[e] = (bf16_t)((float)x[e] * p.scale);
+                for (int e = 0; e < 8; e++) val[e] = rawq ? x[e] : (bf16_t)((float)x[e] * p.scale);
             } else {
                 const int c8 = (ks - C / 16) * 2 + hf;
-                val = phi_chunk_gather<true>(pqg + (size_t)qc * R * phi_esz, c8, R, phi_f32);
+                val = phi_chunk_gather<true>(pqg + (size_t)qc * R * phi_esz, c8, R, phi_f32, rawq ? p.inv_scale : 1.f);
             }
             qreg[ks] = val;
         }
@@ -303,8 +308,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
             float ps[4] = {0.f, 0.f, 0.f, 0.f};   // independent partial sums: short dependency chains
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
-                const bf16x2 pr2 = {(bf16_t)fast_exp2(fmaf(s[r], kLog2e, nm)),
-                                    (bf16_t)fast_exp2(fmaf(s[r + 1], kLog2e, nm))};
+                const bf16x2 pr2 = {(bf16_t)fast_exp2(fmaf(s[r], emul, nm)),
+                                    (bf16_t)fast_exp2(fmaf(s[r + 1], emul, nm))};
                 ps[(r >> 1) & 3] = pair_sum(pr2, ps[(r >> 1) & 3]);
                 pb[r / 8][r % 8] = pr2[0];
                 pb[r / 8][r % 8 + 1] = pr2[1];
@@ -321,7 +326,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_bf16_pp_kernel(FwdParams p) {
         }
         if (!done) {
             asm volatile("" ::: "memory");   // keep this a real (rarely taken) branch
-            const float mx = half_max(max16(s)) * kLog2e;
+            const float mx = half_max(max16(s)) * emul;
             if (__any(mx > mref)) {
                 const float mnew = fmaxf(fmaxf(mref, mx), -1e30f);
                 const float alpha = fast_exp2(mref - mnew);
