@@ -9,18 +9,20 @@
 // gradient is ever written.  No atomics; results are deterministic.
 //
 // Kernels:
-//   prep  : writes the concatenated operands Aq = [q*scale | phi_q | 0], Ak = [k | phi_k | 0]
+//   pre   : writes the concatenated operands Aq = [q*scale | phi_q | 0], Ak = [k | phi_k | 0]
 //           (bf16, width W = C + 32 or C + 64 when R > 0; fp32 factors as three bf16 limbs, six product
-//           columns per rank as in the forward) into the workspace
-//   vec   : (lse * log2 e, D) per query row
+//           columns per rank as in the forward) into the workspace -- or, for C = 64, 128, only their
+//           factor columns, the channel columns being read from k (and from q, where the scores are
+//           formed from q itself) in place
+//   main<DKV = false> : a lane owns a query; streams 32-key blocks;   accumulates dAq^T; runs first and
+//                       leaves (lse * log2 e, D) per query row for the other
 //   main<DKV = true>  : a lane owns a key;   streams 32-query blocks; accumulates dV^T, dAk^T
-//   main<DKV = false> : a lane owns a query; streams 32-key blocks;   accumulates dAq^T
 // Both main kernels recompute S and dP (7 contractions instead of 5, but no atomic dQ).  They
 // use the transposed orientation of the forward: the lane-side operands stay in registers,
 // score-shaped accumulators feed the next MFMA as its B operand without leaving registers,
 // and the transposed A operands come from the LDS transpose read.
 //
-// Streaming.  Because prep has already built the operand rows, a streamed block is a pure
+// Streaming.  Because the operand rows exist in memory, a streamed block is a pure
 // copy, done with direct-to-LDS loads (global_load_lds_dwordx4 from inline assembly, see
 // fb_fwd_bf16_dma.h for why) into a ring of four block slots; nothing passes through
 // registers.  One barrier per iteration, in the middle:
@@ -309,7 +311,8 @@ struct OperandRows {
 struct MainArgs {
     OperandRows aq;       // B*H*N rows
     OperandRows ak;       // B*H*M rows
-    const float2* vec;    // [B*H*N]  (lse * log2 e, D)
+    const float2* vec;    // [B*H*N]  (lse * log2 e, D): written by the dq kernel, read by the dkv kernel
+    float2* vec_w;        // the same rows, for the dq kernel
     float exp_mul;        // S exp_mul - lse2 is the exponent of P to base two: log2 e, times the scale where the q columns carry none
     float dkv_mul;        // factor of d[K | phi_k] (the scale, where the q columns carry none)
 };
@@ -363,11 +366,25 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
     for (int cs = 0; cs < K::CS; cs++)
         l2reg[cs] = as_bf16x8(*(const u32x4*)(l2g + (size_t)rc * C + cs * 16 + 8 * hf));
+    // The dq kernel owns every query row once and already holds the row's dO: it forms
+    // D = rowsum(dO o O) and lse log2 e itself and leaves the pair for the dkv kernel, which is
+    // launched behind it (no separate pass over out and dO).
     float my_lse2 = 0.f, my_d = 0.f;
     if (!DKV) {
-        const float2 v2 = vecg[rc];
-        my_lse2 = v2.x;
-        my_d = v2.y;
+        const bf16_t* og = (const bf16_t*)p.out + (lbase + rc) * p.Cg;
+        float dsum = 0.f;
+#pragma unroll
+        for (int cs = 0; cs < K::CS; cs++) {
+            if (cs * 16 < p.Cg) {      // (head dimension 16: the widened dO rows hold zeros there, out has no such channels)
+                const bf16x8 o8 = as_bf16x8(*(const u32x4*)(og + cs * 16 + 8 * hf));
+#pragma unroll
+                for (int e = 0; e < 8; e++) dsum = fmaf((float)o8[e], (float)l2reg[cs][e], dsum);
+            }
+        }
+        dsum += __shfl_xor(dsum, 32);
+        my_d = dsum;
+        my_lse2 = p.lse[lbase + rc] * kLog2e;
+        if (hf == 0 && ri < NL) a.vec_w[lbase + ri] = make_float2(my_lse2, my_d);
     }
 
     f32x16 acc1[K::MB];                 // dAk^T or dAq^T
@@ -1043,6 +1060,7 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     unsigned char* ws = (unsigned char*)pin.workspace;
     MainArgs a;
     a.vec = (const float2*)ws;
+    a.vec_w = (float2*)ws;
     bf16_t* aq = (bf16_t*)(ws + (((size_t)rows * 8 + 15) & ~(size_t)15));
     bf16_t* ak = aq + (size_t)rows * (split_q ? K::RP2 : K::W);
     a.aq = split_q ? OperandRows{(const bf16_t*)pin.q, C, aq, K::RP2} : OperandRows{aq, K::W, aq + C, K::W};
@@ -1067,8 +1085,8 @@ int launch(const BwdParams& pin, hipStream_t stream) {
                                (const bf16_t*)pin.v, vpad, rowsk);
             hipLaunchKernelGGL(bwd_pad16_kernel, dim3((unsigned)((rows * 4 + 255) / 256)), dim3(256), 0, stream,
                                (const bf16_t*)pin.dout, dpad, rows);
-            const unsigned nb_vec = (unsigned)((rows * 2 + 255) / 256);
-            hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 16>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+            const unsigned nb_vec = 0;     // (lse log2 e, D) come from the dq kernel
+            hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
                                pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
             if (hipGetLastError() != hipSuccess) return 1;
             p.v = vpad;
@@ -1077,21 +1095,21 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     }
     if (!narrow) {
         if (pin.Cg != C) return -1;
-        const unsigned nb_vec = (unsigned)((rows * (C / 8) + 255) / 256);
+        const unsigned nb_vec = 0;         // (lse log2 e, D) come from the dq kernel
         auto blocks = [](long long r, int rows_per_block) { return (unsigned)((r + rows_per_block - 1) / rows_per_block); };
         if constexpr (kCanSplit && RP > 0) {
             constexpr int RS = kPrepRows<C, RP, true>, RW = kPrepRows<C, RP, false>;
             if (split_q) {
                 const unsigned nb_q = blocks(rows, RS), nb_k = blocks(rowsk, RS);
-                hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C, true, true>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0, true, true>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
                                    pin, (float2*)ws, aq, ak, nb_vec, nb_q, qmul);
             } else if (split_k) {
                 const unsigned nb_q = blocks(rows, RW), nb_k = blocks(rowsk, RS);
-                hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C, false, true>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0, false, true>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
                                    pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
             } else {
                 const unsigned nb_q = blocks(rows, RW), nb_k = blocks(rowsk, RW);
-                hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
                                    pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
             }
         } else {
@@ -1099,7 +1117,7 @@ int launch(const BwdParams& pin, hipStream_t stream) {
             constexpr int RW = kPrepRows<C, RP, false>;
             const unsigned nb_q = split_q ? 0u : blocks(rows, RW);
             const unsigned nb_k = split_k ? 0u : blocks(rowsk, RW);
-            hipLaunchKernelGGL((bwd_pre_kernel<C, RP, C>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
+            if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
                                pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
         }
         if (hipGetLastError() != hipSuccess) return 1;
@@ -1111,11 +1129,12 @@ int launch(const BwdParams& pin, hipStream_t stream) {
         p.total_tiles = p.B * p.H * n_units;
         p.tiles_per_xcd = (p.total_tiles + 7) / 8;
     };
-    set_tiles(p, p.M);
-    hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p, a);
-    if (hipGetLastError() != hipSuccess) return 1;
+    // dq first: it also leaves (lse log2 e, D) of every query row for the dkv kernel
     set_tiles(p, p.N);
     hipLaunchKernelGGL(kdq, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dq, stream, p, a);
+    if (hipGetLastError() != hipSuccess) return 1;
+    set_tiles(p, p.M);
+    hipLaunchKernelGGL(kdkv, dim3(8 * p.tiles_per_xcd), dim3(kThreads), lds_dkv, stream, p, a);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
