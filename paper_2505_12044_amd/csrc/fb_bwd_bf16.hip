@@ -204,40 +204,16 @@ FB_DEV void bwd_prep_block(const BwdParams& p, bf16_t* __restrict__ dst, const u
     *(u32x4*)(dst + row * DW + (c - C0) * 8) = as_uint4(a);
 }
 
-template <int C>
-FB_DEV void bwd_vec_block(const bf16_t* __restrict__ out, const bf16_t* __restrict__ dout,
-                          const float* __restrict__ lse, float2* __restrict__ vec, long long rows,
-                          const unsigned block) {
-    constexpr int LPR = C / 8;   // lanes per row, 16 bytes each
-    const long long gid = (long long)block * 256 + threadIdx.x;
-    const long long row = gid / LPR;
-    const int c8 = (int)(gid % LPR);
-    float acc = 0.f;
-    if (row < rows) {
-        const bf16x8 a = as_bf16x8(*(const u32x4*)(out + row * C + c8 * 8));
-        const bf16x8 b = as_bf16x8(*(const u32x4*)(dout + row * C + c8 * 8));
-#pragma unroll
-        for (int e = 0; e < 8; e++) acc = fmaf((float)a[e], (float)b[e], acc);
-    }
-#pragma unroll
-    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-    if (c8 == 0 && row < rows) vec[row] = make_float2(lse[row] * kLog2e, acc);
-}
-
-// The whole pre-pass in one launch: workgroups [0, nb_vec) form the (lse log2 e, D) rows (CV: channels
-// per row of out / dout in memory, 0 = not in this launch), the next nb_q write Aq, the rest Ak.
-// SQ, SK: the query-side / key-side rows are written in the split form (factor columns only).
-template <int C, int RP, int CV, bool SQ = false, bool SK = false>
-__global__ __launch_bounds__(256) void bwd_pre_kernel(BwdParams p, float2* __restrict__ vec, bf16_t* __restrict__ aq,
-                                                      bf16_t* __restrict__ ak, unsigned nb_vec, unsigned nb_q, float qmul) {
+// The whole pre-pass in one launch: the first nb_q workgroups write the query-side rows, the rest the
+// key-side rows.  SQ, SK: that side is written in the split form (factor columns only).
+template <int C, int RP, bool SQ = false, bool SK = false>
+__global__ __launch_bounds__(256) void bwd_pre_kernel(BwdParams p, bf16_t* __restrict__ aq, bf16_t* __restrict__ ak,
+                                                      unsigned nb_q, float qmul) {
     const unsigned blk = blockIdx.x;
-    if (blk < nb_vec) {
-        if constexpr (CV > 0)
-            bwd_vec_block<CV>((const bf16_t*)p.out, (const bf16_t*)p.dout, p.lse, vec, (long long)p.B * p.H * p.N, blk);
-    } else if (blk < nb_vec + nb_q) {
-        bwd_prep_block<C, RP, true, SQ>(p, aq, blk - nb_vec, qmul);
+    if (blk < nb_q) {
+        bwd_prep_block<C, RP, true, SQ>(p, aq, blk, qmul);
     } else {
-        bwd_prep_block<C, RP, false, SK>(p, ak, blk - nb_vec - nb_q, 1.f);
+        bwd_prep_block<C, RP, false, SK>(p, ak, blk - nb_q, 1.f);
     }
 }
 
@@ -1085,9 +1061,7 @@ int launch(const BwdParams& pin, hipStream_t stream) {
                                (const bf16_t*)pin.v, vpad, rowsk);
             hipLaunchKernelGGL(bwd_pad16_kernel, dim3((unsigned)((rows * 4 + 255) / 256)), dim3(256), 0, stream,
                                (const bf16_t*)pin.dout, dpad, rows);
-            const unsigned nb_vec = 0;     // (lse log2 e, D) come from the dq kernel
-            hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
-                               pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
+            hipLaunchKernelGGL((bwd_pre_kernel<C, RP>), dim3(nb_q + nb_k), dim3(256), 0, stream, pin, aq, ak, nb_q, 1.f);
             if (hipGetLastError() != hipSuccess) return 1;
             p.v = vpad;
             p.dout = dpad;
@@ -1095,30 +1069,25 @@ int launch(const BwdParams& pin, hipStream_t stream) {
     }
     if (!narrow) {
         if (pin.Cg != C) return -1;
-        const unsigned nb_vec = 0;         // (lse log2 e, D) come from the dq kernel
         auto blocks = [](long long r, int rows_per_block) { return (unsigned)((r + rows_per_block - 1) / rows_per_block); };
         if constexpr (kCanSplit && RP > 0) {
             constexpr int RS = kPrepRows<C, RP, true>, RW = kPrepRows<C, RP, false>;
             if (split_q) {
                 const unsigned nb_q = blocks(rows, RS), nb_k = blocks(rowsk, RS);
-                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0, true, true>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
-                                   pin, (float2*)ws, aq, ak, nb_vec, nb_q, qmul);
+                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, true, true>), dim3(nb_q + nb_k), dim3(256), 0, stream, pin, aq, ak, nb_q, qmul);
             } else if (split_k) {
                 const unsigned nb_q = blocks(rows, RW), nb_k = blocks(rowsk, RS);
-                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0, false, true>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
-                                   pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
+                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, false, true>), dim3(nb_q + nb_k), dim3(256), 0, stream, pin, aq, ak, nb_q, 1.f);
             } else {
                 const unsigned nb_q = blocks(rows, RW), nb_k = blocks(rowsk, RW);
-                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
-                                   pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
+                if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP>), dim3(nb_q + nb_k), dim3(256), 0, stream, pin, aq, ak, nb_q, 1.f);
             }
         } else {
             // no factor columns to write for a split side (RP = 0): its workgroups are simply not launched
             constexpr int RW = kPrepRows<C, RP, false>;
             const unsigned nb_q = split_q ? 0u : blocks(rows, RW);
             const unsigned nb_k = split_k ? 0u : blocks(rowsk, RW);
-            if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP, 0>), dim3(nb_vec + nb_q + nb_k), dim3(256), 0, stream,
-                               pin, (float2*)ws, aq, ak, nb_vec, nb_q, 1.f);
+            if (nb_q + nb_k) hipLaunchKernelGGL((bwd_pre_kernel<C, RP>), dim3(nb_q + nb_k), dim3(256), 0, stream, pin, aq, ak, nb_q, 1.f);
         }
         if (hipGetLastError() != hipSuccess) return 1;
     }
