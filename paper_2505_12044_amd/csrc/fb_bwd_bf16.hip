@@ -342,26 +342,7 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
 #pragma unroll
     for (int cs = 0; cs < K::CS; cs++)
         l2reg[cs] = as_bf16x8(*(const u32x4*)(l2g + (size_t)rc * C + cs * 16 + 8 * hf));
-    // The dq kernel owns every query row once and already holds the row's dO: it forms
-    // D = rowsum(dO o O) and lse log2 e itself and leaves the pair for the dkv kernel, which is
-    // launched behind it (no separate pass over out and dO).
-    float my_lse2 = 0.f, my_d = 0.f;
-    if (!DKV) {
-        const bf16_t* og = (const bf16_t*)p.out + (lbase + rc) * p.Cg;
-        float dsum = 0.f;
-#pragma unroll
-        for (int cs = 0; cs < K::CS; cs++) {
-            if (cs * 16 < p.Cg) {      // (head dimension 16: the widened dO rows hold zeros there, out has no such channels)
-                const bf16x8 o8 = as_bf16x8(*(const u32x4*)(og + cs * 16 + 8 * hf));
-#pragma unroll
-                for (int e = 0; e < 8; e++) dsum = fmaf((float)o8[e], (float)l2reg[cs][e], dsum);
-            }
-        }
-        dsum += __shfl_xor(dsum, 32);
-        my_d = dsum;
-        my_lse2 = p.lse[lbase + rc] * kLog2e;
-        if (hf == 0 && ri < NL) a.vec_w[lbase + ri] = make_float2(my_lse2, my_d);
-    }
+    float my_lse2 = 0.f, my_d = 0.f;    // dq kernel: this lane's row (formed below, behind the first block loads)
 
     f32x16 acc1[K::MB];                 // dAk^T or dAq^T
     f32x16 acc2[DKV ? K::MBC : 1];      // dV^T
@@ -822,6 +803,26 @@ FB_DEV void bwd_tile(const BwdParams& p, const MainArgs& a, unsigned char* smem,
         issue_block(0, 0); issue_bias(0, 0);
         issue_block(1, 1); issue_bias(1, 1);
         issue_block(2, 2); issue_bias(2, 2);
+        // This kernel owns every query row once and already holds the row's dO: it forms
+        // D = rowsum(dO o O) and lse log2 e itself and leaves the pair for the dkv kernel, which is
+        // launched behind it (no separate pass over out and dO).  Placed here so that the row loads
+        // are in flight together with the first blocks.
+        {
+            const bf16_t* og = (const bf16_t*)p.out + (lbase + rc) * p.Cg;
+            float dsum = 0.f;
+#pragma unroll
+            for (int cs = 0; cs < K::CS; cs++) {
+                if (cs * 16 < p.Cg) {      // (head dimension 16: the widened dO rows hold zeros there, out has no such channels)
+                    const bf16x8 o8 = as_bf16x8(*(const u32x4*)(og + cs * 16 + 8 * hf));
+#pragma unroll
+                    for (int e = 0; e < 8; e++) dsum = fmaf((float)o8[e], (float)l2reg[cs][e], dsum);
+                }
+            }
+            dsum += __shfl_xor(dsum, 32);
+            my_d = dsum;
+            my_lse2 = p.lse[lbase + rc] * kLog2e;
+            if (hf == 0 && ri < NL) a.vec_w[lbase + ri] = make_float2(my_lse2, my_d);
+        }
         wait_vmcnt<0>();
         __syncthreads();
         RowBase rb0 = mk_row(0);
